@@ -1,0 +1,196 @@
+/*
+ * ctr_sparse.h - C ABI of the single-GPU sparse embedding cycle (MI355X / gfx950).
+ *
+ * One mini-batch cycle of a CTR model's embedding layer on one GPU's shard of
+ * the parameter server: look up 64-bit feature keys in an HBM-resident hash
+ * table (inserting unseen keys), sum-pool the rows per (sample, slot), and on
+ * the way back reduce the pooled gradients per distinct key and apply one
+ * sparse Adam step to the touched rows; with several model replicas on the
+ * device, merge them every k steps.
+ *
+ * The calls mirror the per-mini-batch steps of the paper's training workflow
+ * (Algorithm 1: insert into the GPU hash table, pull, train, push) and its
+ * k-step Adam (Algorithm 2).
+ *
+ * Conventions
+ *  - Pointers named d_* are DEVICE pointers, h_* are HOST pointers.  Every
+ *    device buffer (table storage, workspace, keys, offsets, pooled, grads) is
+ *    allocated by the caller and only borrowed; the library allocates no device
+ *    memory and frees none.  ctr_table / ctr_batch are small host objects owned
+ *    by the library.
+ *  - `hip_stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *    ctr_pull_pool, ctr_push_adam and ctr_kstep_merge only enqueue work on it
+ *    and return; they never synchronise.  The export/size/status calls
+ *    synchronise the stream they are given.
+ *  - Every call returns a ctr_status.  Errors the host can see (null pointers,
+ *    bad sizes, workspace too small, a stale batch) are returned at once and
+ *    change nothing.  Errors only the device can see (reserved key in the
+ *    input, table full, malformed offsets) are recorded in a device status
+ *    word; the pull that hit one leaves the table exactly as it was (tentative
+ *    inserts are rolled back), its `pooled` output is unspecified, the push
+ *    that consumes its batch is a no-op, and the code is returned (and cleared)
+ *    by ctr_last_status.  While the status word is set, later pulls, pushes
+ *    and merges are no-ops too.
+ *  - Determinism: the same call sequence on the same inputs gives bit-identical
+ *    key->row assignment (new keys take consecutive rows in order of their
+ *    first occurrence in the batch), unique sets and pooled/updated values.
+ *  - Limits: dim a multiple of 4 and <= 256; capacity_rows <= 2^30;
+ *    n_keys < 2^31 per call; n_replicas <= 31.
+ *  - Calls on one table must be issued from one host thread at a time and on
+ *    one stream (or on streams the caller has ordered).
+ */
+#ifndef CTR_SPARSE_H
+#define CTR_SPARSE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ctr_table ctr_table; /* opaque host-side handle */
+typedef struct ctr_batch ctr_batch; /* opaque: dedup result of one pull */
+
+typedef enum {
+  CTR_OK = 0,
+  CTR_E_INVAL = 1,  /* bad argument / malformed offsets */
+  CTR_E_NOMEM = 2,  /* caller-provided table memory or workspace too small */
+  CTR_E_FULL = 3,   /* the pull would need more than capacity_rows rows */
+  CTR_E_BADKEY = 4, /* input holds the reserved key 0xFFFFFFFFFFFFFFFF */
+  CTR_E_STATE = 5,  /* push without a matching live pull */
+  CTR_E_DEVICE = 6  /* a HIP runtime call failed */
+} ctr_status;
+
+/* flags */
+#define CTR_F_KSTEP 1u /* k-step Adam of Algorithm 2: shared frozen denominator + merge */
+
+/* step modes for ctr_push_adam */
+#define CTR_STEP_LOCAL 0u         /* t mod k != 0 (or single-table mode): moments and model */
+#define CTR_STEP_MERGE_PENDING 1u /* t mod k == 0: moments only; the model update of this step \
+                                     is applied inside the next ctr_kstep_merge */
+
+typedef struct {
+  uint64_t capacity_rows; /* R: value rows; the key index has pow2ceil(R / load_factor) slots */
+  uint32_t dim;           /* D: floats per embedding row */
+  float load_factor;      /* in (0, 0.9]; 0 selects 0.5 */
+  uint32_t n_replicas;    /* W >= 1 model replicas sharing one key->row index */
+  float lr, beta1, beta2, eps; /* alpha, beta_1, beta_2, epsilon of Algorithm 2 */
+  uint64_t init_seed;     /* seed of the deterministic row initialiser */
+  float init_std;         /* spread of a new row's parameters */
+  uint32_t flags;         /* CTR_F_* */
+} ctr_config;
+
+/* Bytes of device memory a table with this configuration needs (0 if the
+ * configuration is invalid).  The caller allocates them (256-byte aligned)
+ * and passes them to ctr_table_create. */
+size_t ctr_table_bytes(const ctr_config* cfg);
+
+/* Bytes of device workspace needed by a pull/push pair of at most `max_keys`
+ * key occurrences in `max_segments` segments (0 if invalid). */
+size_t ctr_workspace_bytes(const ctr_config* cfg, uint64_t max_keys, uint32_t max_segments);
+
+/* Creates an empty table in caller-provided device memory (Algorithm 1: the
+ * per-GPU HBM hash table that receives the working parameters; Algorithm 2,
+ * "Initialize", fixes the state of a row when it is created: m = 0, v = eps).
+ * Enqueues the clearing of the key index on `hip_stream`.
+ * d_mem: device, >= ctr_table_bytes(cfg) bytes, 256-byte aligned, must outlive
+ * the table.  *out receives the handle.  Errors: CTR_E_INVAL, CTR_E_NOMEM,
+ * CTR_E_DEVICE. */
+int ctr_table_create(const ctr_config* cfg, void* d_mem, size_t bytes, void* hip_stream,
+                     ctr_table** out);
+
+/* Releases the host handle (and any live batch).  Never touches d_mem. */
+int ctr_table_destroy(ctr_table* t);
+
+/* Pull (Algorithm 1: insert_into_hash_table + pull for one mini-batch; the
+ * training workflow's "union of the referenced parameters"; the embedding
+ * layer of Section 2.1 with per-slot sum pooling).
+ *   d_keys[n_keys]        device, uint64 feature keys in CSR order
+ *   d_offsets[n_seg + 1]  device, uint32 CSR boundaries, offsets[0] = 0,
+ *                         non-decreasing, offsets[n_seg] = n_keys
+ *   d_pooled[n_seg * D]   device, out: pooled[g, :] = sum of replica `replica`'s
+ *                         rows of the keys in segment g (zeros if empty)
+ *   d_workspace           device, >= ctr_workspace_bytes(cfg, n_keys, n_seg),
+ *                         256-byte aligned; owned by the returned batch until
+ *                         the batch is pushed or the next pull on this table
+ *   *batch_out            handle to the dedup result, consumed by ctr_push_adam
+ * Unseen keys are inserted (rows created in all replicas).  A previous batch
+ * of this table that was not pushed becomes stale.
+ * Errors: CTR_E_INVAL, CTR_E_NOMEM (workspace); deferred: CTR_E_INVAL
+ * (offsets), CTR_E_BADKEY, CTR_E_FULL. */
+int ctr_pull_pool(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint64_t n_keys,
+                  const uint32_t* d_offsets, uint32_t n_segments, float* d_pooled,
+                  void* d_workspace, size_t workspace_bytes, ctr_batch** batch_out,
+                  void* hip_stream);
+
+/* Push (Algorithm 1: push_parameters_updates_back; Algorithm 2: the m, v and
+ * model lines).  The gradient of sum pooling hands grad_pooled[g, :] to every
+ * key occurrence of segment g; per distinct key the occurrences' gradients are
+ * summed and ONE Adam step is applied to that key's row of replica `replica`:
+ *   m = b1 m + (1 - b1) g;  v = b2 v + (1 - b2) g^2;  x -= lr m / sqrt(den)
+ * with den = v (single-table mode) or the shared denominator frozen at the
+ * last merge (CTR_F_KSTEP, CTR_STEP_LOCAL); with CTR_STEP_MERGE_PENDING only
+ * m and v change.  Rows not in the batch are untouched.
+ *   d_grad_pooled[n_seg * D]  device, in
+ * `batch` must be the live batch of the last pull on `t` with the same
+ * replica; it is consumed (freed) whatever the outcome, unless CTR_E_INVAL.
+ * Errors: CTR_E_INVAL, CTR_E_STATE. */
+int ctr_push_adam(ctr_table* t, uint32_t replica, ctr_batch* batch, const float* d_grad_pooled,
+                  uint32_t mode, void* hip_stream);
+
+/* k-step merge (Algorithm 2, "global averaging" branch), over every row touched
+ * by any replica since the previous merge:
+ *   vhat = (1/W) sum_j v_j;
+ *   x_i  = (1/W) sum_j (x_j - [row pending in j] lr m_j / sqrt(vhat))   for all i.
+ * m_j and v_j stay local.  Needs CTR_F_KSTEP.  Errors: CTR_E_INVAL. */
+int ctr_kstep_merge(ctr_table* t, void* hip_stream);
+
+/* ---- parity / debug surface (synchronising, not part of the timed path) ---- */
+
+/* Number of rows in use. */
+int ctr_table_size(ctr_table* t, uint64_t* n_rows, void* hip_stream);
+
+/* Table contents in row order into HOST buffers (any may be NULL):
+ * h_keys[n_rows], h_x/h_m/h_v[n_rows * D] of one replica, h_vhat[n_rows * D]
+ * (CTR_F_KSTEP only, else CTR_E_INVAL if requested). */
+int ctr_table_export(ctr_table* t, uint32_t replica, uint64_t* h_keys, float* h_x, float* h_m,
+                     float* h_v, float* h_vhat, void* hip_stream);
+
+/* Dedup result of a live batch in canonical form into HOST buffers (any may be
+ * NULL): *n_unique; h_uniq[n_unique] distinct keys ascending; h_rows[n_unique]
+ * their row ids; h_inverse[n_keys] index of each occurrence's key in h_uniq.
+ * Call with NULL arrays first to learn n_unique. */
+int ctr_batch_export(ctr_table* t, ctr_batch* batch, uint64_t* n_unique, uint64_t* h_uniq,
+                     uint32_t* h_rows, uint32_t* h_inverse, void* hip_stream);
+
+/* Counters of the last pull/push pair: distinct keys in the batch (valid after
+ * the push) and rows created by the pull. */
+int ctr_batch_stats(ctr_table* t, uint64_t* n_unique, uint64_t* n_new, void* hip_stream);
+
+/* Returns the deferred device status (a ctr_status) and clears it. */
+int ctr_last_status(ctr_table* t, void* hip_stream);
+
+/* ---- stage timers (measurement aid) ---- */
+
+#define CTR_STAGE_PROBE 0   /* key probe / tentative insert */
+#define CTR_STAGE_INSERT 1  /* ranking of new keys, row creation */
+#define CTR_STAGE_POOL 2    /* row gather + per-segment sum */
+#define CTR_STAGE_SORT 3    /* grouping of occurrences by row */
+#define CTR_STAGE_PUSH 4    /* gradient segment-reduce fused with Adam */
+#define CTR_STAGE_FIXUP 5   /* rows whose occurrences span several work spans */
+#define CTR_STAGE_MERGE 6   /* k-step merge */
+#define CTR_N_STAGES 7
+
+/* When enabled, a pair of HIP events is recorded around each stage of the
+ * following calls, on the stream they run on (one pair per execution). */
+int ctr_profile_enable(ctr_table* t, int on);
+/* Synchronises the device, writes per stage the summed milliseconds
+ * (h_ms[CTR_N_STAGES]) and the number of executions (h_count[CTR_N_STAGES],
+ * may be NULL) recorded since the previous read, and starts a new record. */
+int ctr_profile_read(ctr_table* t, float* h_ms, uint32_t* h_count);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CTR_SPARSE_H */

@@ -1,0 +1,269 @@
+"""Thin ctypes binding of the C ABI in include/ctr_sparse.h (argument marshalling only).
+
+The functions carry the ABI's names and take raw device addresses; ``CtrTable``
+is a convenience that owns the torch allocations (device memory and the stream
+come from PyTorch, nothing else does).  There is no fallback: if the HIP
+library is not built, importing the symbols raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libctr_sparse.so")
+
+CTR_OK, CTR_E_INVAL, CTR_E_NOMEM, CTR_E_FULL, CTR_E_BADKEY, CTR_E_STATE, CTR_E_DEVICE = range(7)
+CTR_F_KSTEP = 1
+CTR_STEP_LOCAL, CTR_STEP_MERGE_PENDING = 0, 1
+CTR_N_STAGES = 7
+STAGE_NAMES = ("probe", "insert", "pool", "sort", "push", "fixup", "merge")
+
+EXPORTED = (
+    "ctr_table_bytes", "ctr_workspace_bytes", "ctr_table_create", "ctr_table_destroy",
+    "ctr_pull_pool", "ctr_push_adam", "ctr_kstep_merge", "ctr_table_size", "ctr_table_export",
+    "ctr_batch_export", "ctr_batch_stats", "ctr_last_status", "ctr_profile_enable",
+    "ctr_profile_read",
+)
+
+
+class ctr_config(C.Structure):
+    _fields_ = [
+        ("capacity_rows", C.c_uint64),
+        ("dim", C.c_uint32),
+        ("load_factor", C.c_float),
+        ("n_replicas", C.c_uint32),
+        ("lr", C.c_float),
+        ("beta1", C.c_float),
+        ("beta2", C.c_float),
+        ("eps", C.c_float),
+        ("init_seed", C.c_uint64),
+        ("init_std", C.c_float),
+        ("flags", C.c_uint32),
+    ]
+
+
+_lib = None
+
+
+def lib():
+    """Loads libctr_sparse.so; raises if it has not been built (no CPU fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            "HIP library %s is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+            "(hipcc, gfx950) first" % LIB_PATH)
+    L = C.CDLL(LIB_PATH)
+    vp, u64, u32, sz, ci = C.c_void_p, C.c_uint64, C.c_uint32, C.c_size_t, C.c_int
+    cfgp = C.POINTER(ctr_config)
+    L.ctr_table_bytes.restype = sz
+    L.ctr_table_bytes.argtypes = [cfgp]
+    L.ctr_workspace_bytes.restype = sz
+    L.ctr_workspace_bytes.argtypes = [cfgp, u64, u32]
+    L.ctr_table_create.restype = ci
+    L.ctr_table_create.argtypes = [cfgp, vp, sz, vp, C.POINTER(vp)]
+    L.ctr_table_destroy.restype = ci
+    L.ctr_table_destroy.argtypes = [vp]
+    L.ctr_pull_pool.restype = ci
+    L.ctr_pull_pool.argtypes = [vp, u32, vp, u64, vp, u32, vp, vp, sz, C.POINTER(vp), vp]
+    L.ctr_push_adam.restype = ci
+    L.ctr_push_adam.argtypes = [vp, u32, vp, vp, u32, vp]
+    L.ctr_kstep_merge.restype = ci
+    L.ctr_kstep_merge.argtypes = [vp, vp]
+    L.ctr_table_size.restype = ci
+    L.ctr_table_size.argtypes = [vp, C.POINTER(u64), vp]
+    L.ctr_table_export.restype = ci
+    L.ctr_table_export.argtypes = [vp, u32, vp, vp, vp, vp, vp, vp]
+    L.ctr_batch_export.restype = ci
+    L.ctr_batch_export.argtypes = [vp, vp, C.POINTER(u64), vp, vp, vp, vp]
+    L.ctr_batch_stats.restype = ci
+    L.ctr_batch_stats.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), vp]
+    L.ctr_last_status.restype = ci
+    L.ctr_last_status.argtypes = [vp, vp]
+    L.ctr_profile_enable.restype = ci
+    L.ctr_profile_enable.argtypes = [vp, ci]
+    L.ctr_profile_read.restype = ci
+    L.ctr_profile_read.argtypes = [vp, vp, vp]
+    _lib = L
+    return L
+
+
+# ---- the ABI's calls under their own names (raw addresses in, status out) ----
+
+def ctr_table_bytes(cfg: ctr_config) -> int:
+    return int(lib().ctr_table_bytes(C.byref(cfg)))
+
+
+def ctr_workspace_bytes(cfg: ctr_config, max_keys: int, max_segments: int) -> int:
+    return int(lib().ctr_workspace_bytes(C.byref(cfg), max_keys, max_segments))
+
+
+def ctr_table_create(cfg: ctr_config, d_mem: int, nbytes: int, stream: int):
+    out = C.c_void_p()
+    st = lib().ctr_table_create(C.byref(cfg), d_mem, nbytes, stream, C.byref(out))
+    return st, out.value
+
+
+def ctr_table_destroy(table: int) -> int:
+    return lib().ctr_table_destroy(table)
+
+
+def ctr_pull_pool(table, replica, d_keys, n_keys, d_offsets, n_segments, d_pooled, d_ws, ws_bytes, stream):
+    out = C.c_void_p()
+    st = lib().ctr_pull_pool(table, replica, d_keys, n_keys, d_offsets, n_segments, d_pooled, d_ws,
+                             ws_bytes, C.byref(out), stream)
+    return st, out.value
+
+
+def ctr_push_adam(table, replica, batch, d_grad, mode, stream) -> int:
+    return lib().ctr_push_adam(table, replica, batch, d_grad, mode, stream)
+
+
+def ctr_kstep_merge(table, stream) -> int:
+    return lib().ctr_kstep_merge(table, stream)
+
+
+def ctr_last_status(table, stream) -> int:
+    return lib().ctr_last_status(table, stream)
+
+
+def _np_ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+class CtrTable:
+    """Owns the torch allocations for one table and forwards to the ABI."""
+
+    def __init__(self, capacity_rows, dim, n_replicas=1, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8,
+                 init_seed=0, init_std=0.01, kstep=False, load_factor=0.5, max_keys=0, max_segments=0,
+                 device="cuda:0"):
+        import torch
+        self._torch = torch
+        self.device = torch.device(device)
+        self.cfg = ctr_config(capacity_rows, dim, load_factor, n_replicas, lr, beta1, beta2, eps,
+                              init_seed, init_std, CTR_F_KSTEP if kstep else 0)
+        self.D, self.W, self.R, self.kstep = int(dim), int(n_replicas), int(capacity_rows), bool(kstep)
+        nbytes = ctr_table_bytes(self.cfg)
+        if nbytes == 0:
+            raise ValueError("invalid table configuration")
+        self.table_bytes = nbytes
+        self._mem = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self._ws = None
+        self.ws_bytes = 0
+        self._handle = None
+        st, h = ctr_table_create(self.cfg, self._mem.data_ptr(), nbytes, self.stream)
+        if st != CTR_OK:
+            raise RuntimeError("ctr_table_create failed: %d" % st)
+        self._handle = h
+        if max_keys:
+            self.reserve(max_keys, max_segments)
+
+    @property
+    def stream(self) -> int:
+        return int(self._torch.cuda.current_stream(self.device).cuda_stream)
+
+    def reserve(self, max_keys: int, max_segments: int):
+        need = ctr_workspace_bytes(self.cfg, max_keys, max_segments)
+        if need == 0:
+            raise ValueError("invalid workspace request")
+        if need > self.ws_bytes:
+            self._torch.cuda.synchronize(self.device)
+            self._ws = self._torch.empty(need, dtype=self._torch.uint8, device=self.device)
+            self.ws_bytes = need
+
+    def close(self):
+        if self._handle:
+            self._torch.cuda.synchronize(self.device)
+            ctr_table_destroy(self._handle)
+            self._handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- hot path
+    def pull_pool(self, replica, keys, offsets, pooled=None):
+        """keys: int64/uint64 device tensor [L]; offsets: int32 device tensor [G+1].
+        Returns (status, batch handle, pooled[G, D])."""
+        torch = self._torch
+        n_keys, n_seg = keys.numel(), offsets.numel() - 1
+        self.reserve(max(n_keys, 1), n_seg)
+        if pooled is None:
+            pooled = torch.empty((n_seg, self.D), dtype=torch.float32, device=self.device)
+        st, batch = ctr_pull_pool(self._handle, replica, keys.data_ptr() if n_keys else None, n_keys,
+                                  offsets.data_ptr(), n_seg, pooled.data_ptr() if n_seg else None,
+                                  self._ws.data_ptr(), self.ws_bytes, self.stream)
+        return st, batch, pooled
+
+    def push_adam(self, replica, batch, grad, mode=CTR_STEP_LOCAL):
+        return ctr_push_adam(self._handle, replica, batch, grad.data_ptr() if grad.numel() else None,
+                             mode, self.stream)
+
+    def kstep_merge(self):
+        return ctr_kstep_merge(self._handle, self.stream)
+
+    # -- debug / parity surface
+    def last_status(self) -> int:
+        return ctr_last_status(self._handle, self.stream)
+
+    @property
+    def n_rows(self) -> int:
+        n = C.c_uint64()
+        st = lib().ctr_table_size(self._handle, C.byref(n), self.stream)
+        if st != CTR_OK:
+            raise RuntimeError("ctr_table_size: %d" % st)
+        return int(n.value)
+
+    def batch_stats(self):
+        u, n = C.c_uint64(), C.c_uint64()
+        st = lib().ctr_batch_stats(self._handle, C.byref(u), C.byref(n), self.stream)
+        if st != CTR_OK:
+            raise RuntimeError("ctr_batch_stats: %d" % st)
+        return int(u.value), int(n.value)
+
+    def batch_export(self, batch, n_keys):
+        nu = C.c_uint64()
+        st = lib().ctr_batch_export(self._handle, batch, C.byref(nu), None, None, None, self.stream)
+        if st != CTR_OK:
+            raise RuntimeError("ctr_batch_export: %d" % st)
+        U = int(nu.value)
+        uniq = np.empty(U, np.uint64)
+        rows = np.empty(U, np.uint32)
+        inv = np.empty(int(n_keys), np.uint32)
+        st = lib().ctr_batch_export(self._handle, batch, C.byref(nu), _np_ptr(uniq), _np_ptr(rows),
+                                    _np_ptr(inv), self.stream)
+        if st != CTR_OK:
+            raise RuntimeError("ctr_batch_export: %d" % st)
+        return uniq, rows, inv
+
+    def table_export(self, replica=0):
+        n = self.n_rows
+        keys = np.empty(n, np.uint64)
+        x = np.empty((n, self.D), np.float32)
+        m = np.empty((n, self.D), np.float32)
+        v = np.empty((n, self.D), np.float32)
+        vhat = np.empty((n, self.D), np.float32) if self.kstep else None
+        st = lib().ctr_table_export(self._handle, replica, _np_ptr(keys), _np_ptr(x), _np_ptr(m),
+                                    _np_ptr(v), _np_ptr(vhat), self.stream)
+        if st != CTR_OK:
+            raise RuntimeError("ctr_table_export: %d" % st)
+        return {"keys": keys, "x": x, "m": m, "v": v, "vhat": vhat}
+
+    def profile_enable(self, on=True):
+        return lib().ctr_profile_enable(self._handle, 1 if on else 0)
+
+    def profile_read(self):
+        """{stage: (total ms, executions)} since the previous read."""
+        ms = np.zeros(CTR_N_STAGES, np.float32)
+        cnt = np.zeros(CTR_N_STAGES, np.uint32)
+        st = lib().ctr_profile_read(self._handle, _np_ptr(ms), _np_ptr(cnt))
+        if st != CTR_OK:
+            raise RuntimeError("ctr_profile_read: %d" % st)
+        return {n: (float(m), int(c)) for n, m, c in zip(STAGE_NAMES, ms, cnt)}

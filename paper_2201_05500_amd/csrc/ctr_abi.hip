@@ -1,0 +1,553 @@
+// Host side of the C ABI declared in include/ctr_sparse.h: argument checks, memory layout,
+// kernel launches.  No arithmetic of the method happens on the host.
+#include "../../include/ctr_sparse.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "common.h"
+#include "push_kernels.h"
+#include "sort_kernels.h"
+#include "table_kernels.h"
+
+using namespace ctr;
+
+namespace {
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+inline u64 pow2ceil(u64 x) {
+  u64 p = 1;
+  while (p < x) p <<= 1;
+  return p;
+}
+
+struct TableLayout {
+  u64 n_slots;
+  size_t off_hdr, off_slots, off_row_key, off_row_state, off_values, off_vhat, total;
+  u64 replica_stride;  // floats between replicas
+};
+
+bool config_ok(const ctr_config* c) {
+  if (!c) return false;
+  if (c->dim == 0 || c->dim % 4 != 0 || c->dim > 256) return false;
+  if (c->capacity_rows == 0 || c->capacity_rows > (1ull << 30)) return false;
+  if (c->n_replicas == 0 || c->n_replicas > 31) return false;
+  if (!(c->load_factor >= 0.0f) || c->load_factor > 0.9f) return false;
+  if (c->flags & ~CTR_F_KSTEP) return false;
+  if (!(c->lr > 0.0f) || !(c->beta1 >= 0.0f && c->beta1 < 1.0f) || !(c->beta2 >= 0.0f && c->beta2 < 1.0f) ||
+      !(c->eps > 0.0f) || !(c->init_std >= 0.0f))
+    return false;
+  return true;
+}
+
+bool table_layout(const ctr_config* c, TableLayout* L) {
+  if (!config_ok(c)) return false;
+  const double lf = c->load_factor == 0.0f ? 0.5 : (double)c->load_factor;
+  u64 want = (u64)std::ceil((double)c->capacity_rows / lf);
+  L->n_slots = std::max<u64>(pow2ceil(want), 64);
+  if (L->n_slots > (1ull << 30)) return false;
+  const u64 R = c->capacity_rows, D = c->dim, W = c->n_replicas;
+  size_t o = 0;
+  L->off_hdr = o; o += align256(sizeof(DevHeader));
+  L->off_slots = o; o += align256(L->n_slots * sizeof(Slot));
+  L->off_row_key = o; o += align256(R * sizeof(u64));
+  L->off_row_state = o; o += align256(R * sizeof(u32));
+  L->off_values = o;
+  L->replica_stride = (align256(R * 3 * D * sizeof(float))) / sizeof(float);
+  o += L->replica_stride * sizeof(float) * W;
+  L->off_vhat = o;
+  if (c->flags & CTR_F_KSTEP) o += align256(R * D * sizeof(float));
+  L->total = o;
+  return true;
+}
+
+struct WorkLayout {
+  u32 n_rank_tiles, n_spans;
+  SortGeom geo;
+  size_t off_occ_row, off_seg_of, off_ka, off_va, off_kb, off_vb, off_hist, off_digit_total, off_tile_count,
+      off_head, off_tail, off_span_flags, off_span_rows, total;
+};
+
+void work_layout(u32 D, u64 n_keys, WorkLayout* L) {
+  const u64 n = n_keys;
+  L->n_rank_tiles = (u32)((n + RANK_TILE - 1) / RANK_TILE);
+  L->n_spans = (u32)((n + SPAN - 1) / SPAN);
+  u64 tiles = (n + SORT_TILE - 1) / SORT_TILE;
+  u64 chunks = std::min<u64>(std::max<u64>(tiles, 1), SORT_MAX_CHUNKS);
+  u64 per = (n + chunks - 1) / chunks;
+  u64 chunk_elems = std::max<u64>(((per + SORT_TILE - 1) / SORT_TILE) * SORT_TILE, SORT_TILE);
+  L->geo.n = (u32)n;
+  L->geo.chunk_elems = (u32)chunk_elems;
+  L->geo.n_chunks = (u32)std::max<u64>((n + chunk_elems - 1) / chunk_elems, 1);
+  size_t o = 0;
+  const size_t arr = align256(n * sizeof(u32));
+  L->off_occ_row = o; o += arr;
+  L->off_seg_of = o; o += arr;
+  L->off_ka = o; o += arr;
+  L->off_va = o; o += arr;
+  L->off_kb = o; o += arr;
+  L->off_vb = o; o += arr;
+  L->off_hist = o; o += align256((size_t)RADIX * SORT_MAX_CHUNKS * sizeof(u32));
+  L->off_digit_total = o; o += align256(RADIX * sizeof(u32));
+  L->off_tile_count = o; o += align256(((size_t)L->n_rank_tiles + 1) * sizeof(u32));
+  L->off_head = o; o += align256((size_t)L->n_spans * D * sizeof(double));
+  L->off_tail = o; o += align256((size_t)L->n_spans * D * sizeof(double));
+  L->off_span_flags = o; o += align256((size_t)L->n_spans * sizeof(u32));
+  L->off_span_rows = o; o += align256((size_t)L->n_spans * sizeof(u32));
+  L->total = std::max<size_t>(o, 256);
+}
+
+inline u32 lanes_per_row(u32 D) {
+  u32 v = D / 4, p = 1;
+  while (p < v) p <<= 1;
+  return p;  // 1..64
+}
+
+inline u32 blocks_for(u64 threads) { return (u32)((threads + BLOCK - 1) / BLOCK); }
+
+}  // namespace
+
+struct ctr_batch {
+  ctr_table* t;
+  u64 generation;
+  u32 replica, n_keys, n_seg;
+  char* ws;
+  WorkLayout wl;
+  u32* sorted_rows;
+  u32* sorted_segs;
+};
+
+struct ctr_table {
+  ctr_config cfg;
+  TableLayout tl;
+  u32 D, W, lpr, row_bits;
+  u64 R;
+  char* mem;
+  DevHeader* hdr;
+  Slot* slots;
+  u64* row_key;
+  u32* row_state;
+  float* values;
+  float* vhat;
+  u64 seed_mul;
+  float init_scale;
+  u64 generation;
+  ctr_batch* live;
+  bool profile;
+  // stage timers: one (start, stop) event pair per recorded execution since the last read
+  std::vector<hipEvent_t> ev_start[CTR_N_STAGES], ev_stop[CTR_N_STAGES];
+  size_t ev_used[CTR_N_STAGES];
+};
+
+namespace {
+
+struct StageTimer {
+  ctr_table* t;
+  int stage;
+  hipStream_t st;
+  bool on;
+  size_t idx;
+  StageTimer(ctr_table* t_, int stage_, hipStream_t st_) : t(t_), stage(stage_), st(st_), on(false), idx(0) {
+    if (!t->profile) return;
+    idx = t->ev_used[stage];
+    if (idx == t->ev_start[stage].size()) {
+      hipEvent_t a, b;
+      if (hipEventCreate(&a) != hipSuccess) return;
+      if (hipEventCreate(&b) != hipSuccess) {
+        (void)hipEventDestroy(a);
+        return;
+      }
+      t->ev_start[stage].push_back(a);
+      t->ev_stop[stage].push_back(b);
+    }
+    on = hipEventRecord(t->ev_start[stage][idx], st) == hipSuccess;
+  }
+  ~StageTimer() {
+    if (on && hipEventRecord(t->ev_stop[stage][idx], st) == hipSuccess) t->ev_used[stage] = idx + 1;
+  }
+};
+
+#define LPR_DISPATCH(lpr, KERNEL, grid, stream, ...)                                                     \
+  switch (lpr) {                                                                                         \
+    case 1: hipLaunchKernelGGL((KERNEL<1>), dim3(grid), dim3(BLOCK), 0, stream, __VA_ARGS__); break;     \
+    case 2: hipLaunchKernelGGL((KERNEL<2>), dim3(grid), dim3(BLOCK), 0, stream, __VA_ARGS__); break;     \
+    case 4: hipLaunchKernelGGL((KERNEL<4>), dim3(grid), dim3(BLOCK), 0, stream, __VA_ARGS__); break;     \
+    case 8: hipLaunchKernelGGL((KERNEL<8>), dim3(grid), dim3(BLOCK), 0, stream, __VA_ARGS__); break;     \
+    case 16: hipLaunchKernelGGL((KERNEL<16>), dim3(grid), dim3(BLOCK), 0, stream, __VA_ARGS__); break;   \
+    case 32: hipLaunchKernelGGL((KERNEL<32>), dim3(grid), dim3(BLOCK), 0, stream, __VA_ARGS__); break;   \
+    default: hipLaunchKernelGGL((KERNEL<64>), dim3(grid), dim3(BLOCK), 0, stream, __VA_ARGS__); break;   \
+  }
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? CTR_OK : CTR_E_DEVICE; }
+
+int status_code_from_bits(u32 bits) {
+  if (bits & ST_INVAL) return CTR_E_INVAL;
+  if (bits & ST_BADKEY) return CTR_E_BADKEY;
+  if (bits & ST_FULL) return CTR_E_FULL;
+  return CTR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t ctr_table_bytes(const ctr_config* cfg) {
+  TableLayout L;
+  return table_layout(cfg, &L) ? L.total : 0;
+}
+
+size_t ctr_workspace_bytes(const ctr_config* cfg, uint64_t max_keys, uint32_t max_segments) {
+  (void)max_segments;
+  if (!config_ok(cfg) || max_keys >= (1ull << 31)) return 0;
+  WorkLayout L;
+  work_layout(cfg->dim, max_keys, &L);
+  return L.total;
+}
+
+int ctr_table_create(const ctr_config* cfg, void* d_mem, size_t bytes, void* hip_stream, ctr_table** out) {
+  if (!cfg || !d_mem || !out) return CTR_E_INVAL;
+  TableLayout L;
+  if (!table_layout(cfg, &L)) return CTR_E_INVAL;
+  if (((uintptr_t)d_mem & 255) != 0) return CTR_E_INVAL;
+  if (bytes < L.total) return CTR_E_NOMEM;
+  ctr_table* t = new (std::nothrow) ctr_table();
+  if (!t) return CTR_E_NOMEM;
+  t->cfg = *cfg;
+  if (t->cfg.load_factor == 0.0f) t->cfg.load_factor = 0.5f;
+  t->tl = L;
+  t->D = cfg->dim;
+  t->W = cfg->n_replicas;
+  t->R = cfg->capacity_rows;
+  t->lpr = lanes_per_row(t->D);
+  t->row_bits = 1;
+  while ((1ull << t->row_bits) < t->R) ++t->row_bits;
+  t->mem = (char*)d_mem;
+  t->hdr = (DevHeader*)(t->mem + L.off_hdr);
+  t->slots = (Slot*)(t->mem + L.off_slots);
+  t->row_key = (u64*)(t->mem + L.off_row_key);
+  t->row_state = (u32*)(t->mem + L.off_row_state);
+  t->values = (float*)(t->mem + L.off_values);
+  t->vhat = (cfg->flags & CTR_F_KSTEP) ? (float*)(t->mem + L.off_vhat) : nullptr;
+  t->seed_mul = cfg->init_seed * 0x9E3779B97F4A7C15ull;
+  t->init_scale = (float)((double)cfg->init_std / 37837.2);
+  t->generation = 0;
+  t->live = nullptr;
+  t->profile = false;
+  for (int i = 0; i < CTR_N_STAGES; ++i) t->ev_used[i] = 0;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const u64 work = std::max<u64>(L.n_slots, t->R);
+  const u32 grid = (u32)std::min<u64>((work + BLOCK - 1) / BLOCK, 8192);
+  hipLaunchKernelGGL(k_table_clear, dim3(grid), dim3(BLOCK), 0, st, t->hdr, t->slots, L.n_slots, t->row_state,
+                     t->R);
+  if (launch_status() != CTR_OK) {
+    delete t;
+    return CTR_E_DEVICE;
+  }
+  *out = t;
+  return CTR_OK;
+}
+
+int ctr_table_destroy(ctr_table* t) {
+  if (!t) return CTR_E_INVAL;
+  if (t->live) {
+    delete t->live;
+    t->live = nullptr;
+  }
+  for (int i = 0; i < CTR_N_STAGES; ++i) {
+    for (hipEvent_t e : t->ev_start[i]) (void)hipEventDestroy(e);
+    for (hipEvent_t e : t->ev_stop[i]) (void)hipEventDestroy(e);
+  }
+  delete t;
+  return CTR_OK;
+}
+
+int ctr_pull_pool(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint64_t n_keys,
+                  const uint32_t* d_offsets, uint32_t n_segments, float* d_pooled, void* d_workspace,
+                  size_t workspace_bytes, ctr_batch** batch_out, void* hip_stream) {
+  if (!t || !batch_out || !d_offsets || !d_workspace) return CTR_E_INVAL;
+  if (replica >= t->W) return CTR_E_INVAL;
+  if (n_keys >= (1ull << 31) || n_segments == 0xFFFFFFFFu) return CTR_E_INVAL;
+  if (n_keys > 0 && !d_keys) return CTR_E_INVAL;
+  if (n_segments > 0 && !d_pooled) return CTR_E_INVAL;
+  if (((uintptr_t)d_workspace & 255) != 0) return CTR_E_INVAL;
+  WorkLayout wl;
+  work_layout(t->D, n_keys, &wl);
+  if (workspace_bytes < wl.total) return CTR_E_NOMEM;
+
+  ctr_batch* b = new (std::nothrow) ctr_batch();
+  if (!b) return CTR_E_NOMEM;
+  if (t->live) {  // an unpushed batch goes stale
+    delete t->live;
+    t->live = nullptr;
+  }
+  b->t = t;
+  b->generation = ++t->generation;
+  b->replica = replica;
+  b->n_keys = (u32)n_keys;
+  b->n_seg = n_segments;
+  b->ws = (char*)d_workspace;
+  b->wl = wl;
+  b->sorted_rows = nullptr;
+  b->sorted_segs = nullptr;
+
+  hipStream_t st = (hipStream_t)hip_stream;
+  const u32 n = (u32)n_keys;
+  u32* occ_row = (u32*)(b->ws + wl.off_occ_row);
+  u32* seg_of = (u32*)(b->ws + wl.off_seg_of);
+  u32* tile_count = (u32*)(b->ws + wl.off_tile_count);
+  const u32 slot_mask = (u32)(t->tl.n_slots - 1);
+
+  {
+    StageTimer tm(t, CTR_STAGE_PROBE, st);
+    const u64 work = std::max<u64>(n, (u64)n_segments + 1);
+    hipLaunchKernelGGL(k_probe_insert, dim3(blocks_for(work)), dim3(BLOCK), 0, st, t->hdr, t->slots, slot_mask,
+                       (const u64*)d_keys, n, d_offsets, n_segments, occ_row);
+  }
+  {
+    StageTimer tm(t, CTR_STAGE_INSERT, st);
+    if (wl.n_rank_tiles > 0)
+      hipLaunchKernelGGL(k_count_first, dim3(wl.n_rank_tiles), dim3(BLOCK), 0, st, t->hdr, t->slots, occ_row, n,
+                         tile_count);
+    hipLaunchKernelGGL(k_scan_tiles, dim3(1), dim3(BLOCK), 0, st, t->hdr, tile_count, wl.n_rank_tiles, t->R);
+    if (wl.n_rank_tiles > 0) {
+      hipLaunchKernelGGL(k_assign_rows, dim3(wl.n_rank_tiles), dim3(BLOCK), 0, st, t->hdr, t->slots, occ_row, n,
+                         tile_count, t->row_key);
+      const u32 groups_per_block = BLOCK / t->lpr;
+      const u32 grid = std::min<u32>(blocks_for((u64)n * t->lpr), 4096);
+      (void)groups_per_block;
+      LPR_DISPATCH(t->lpr, k_init_rows, grid, st, t->hdr, t->row_key, t->values, t->tl.replica_stride, t->W,
+                   t->vhat, t->D, t->seed_mul, t->init_scale, t->cfg.eps);
+      hipLaunchKernelGGL(k_resolve, dim3(blocks_for(n)), dim3(BLOCK), 0, st, t->hdr, t->slots, occ_row, n);
+    }
+  }
+  if (n_segments > 0) {
+    StageTimer tm(t, CTR_STAGE_POOL, st);
+    const float* vals = t->values + (u64)replica * t->tl.replica_stride;
+    LPR_DISPATCH(t->lpr, k_pool, blocks_for((u64)n_segments * t->lpr), st, t->hdr, occ_row, seg_of, d_offsets,
+                 n_segments, vals, t->D, d_pooled);
+  }
+  if (n > 0) {
+    StageTimer tm(t, CTR_STAGE_SORT, st);
+    u32* hist = (u32*)(b->ws + wl.off_hist);
+    u32* digit_total = (u32*)(b->ws + wl.off_digit_total);
+    u32* ka = (u32*)(b->ws + wl.off_ka);
+    u32* va = (u32*)(b->ws + wl.off_va);
+    u32* kb = (u32*)(b->ws + wl.off_kb);
+    u32* vb = (u32*)(b->ws + wl.off_vb);
+    const u32 passes = (t->row_bits + 7) / 8;
+    const u32* kin = occ_row;
+    const u32* vin = seg_of;
+    u32 shift = 0;
+    for (u32 p = 0; p < passes; ++p) {
+      // spread the row bits evenly over the passes
+      const u32 bits = (t->row_bits - shift + (passes - p) - 1) / (passes - p);
+      const u32 mask = (1u << bits) - 1u;
+      u32* kout = (p & 1) ? kb : ka;
+      u32* vout = (p & 1) ? vb : va;
+      hipLaunchKernelGGL(k_sort_hist, dim3(wl.geo.n_chunks), dim3(BLOCK), 0, st, t->hdr, kin, wl.geo, shift, mask,
+                         hist);
+      hipLaunchKernelGGL(k_sort_scan, dim3(RADIX), dim3(BLOCK), 0, st, t->hdr, hist, wl.geo.n_chunks, digit_total);
+      hipLaunchKernelGGL(k_sort_scatter, dim3(wl.geo.n_chunks), dim3(BLOCK), 0, st, t->hdr, kin, vin, kout, vout,
+                         wl.geo, shift, mask, hist, digit_total);
+      kin = kout;
+      vin = vout;
+      shift += bits;
+    }
+    b->sorted_rows = (u32*)kin;
+    b->sorted_segs = (u32*)vin;
+  }
+  if (launch_status() != CTR_OK) {
+    delete b;
+    return CTR_E_DEVICE;
+  }
+  t->live = b;
+  *batch_out = b;
+  return CTR_OK;
+}
+
+int ctr_push_adam(ctr_table* t, uint32_t replica, ctr_batch* batch, const float* d_grad_pooled, uint32_t mode,
+                  void* hip_stream) {
+  if (!t || !batch) return CTR_E_INVAL;
+  if (replica >= t->W) return CTR_E_INVAL;
+  if (mode != CTR_STEP_LOCAL && mode != CTR_STEP_MERGE_PENDING) return CTR_E_INVAL;
+  const bool kstep = (t->cfg.flags & CTR_F_KSTEP) != 0;
+  if (!kstep && mode != CTR_STEP_LOCAL) return CTR_E_INVAL;
+  if (t->live != batch) return CTR_E_STATE;  // stale, foreign or already consumed
+  if (batch->replica != replica) return CTR_E_STATE;
+  if (batch->n_seg > 0 && !d_grad_pooled) return CTR_E_INVAL;
+
+  hipStream_t st = (hipStream_t)hip_stream;
+  const WorkLayout& wl = batch->wl;
+  const u32 n = batch->n_keys;
+  if (n > 0) {
+    AdamParams P;
+    P.b1 = (double)t->cfg.beta1;
+    P.omb1 = 1.0 - P.b1;
+    P.b2 = (double)t->cfg.beta2;
+    P.omb2 = 1.0 - P.b2;
+    P.lr = t->cfg.lr;
+    P.kstep = kstep ? 1u : 0u;
+    P.mode = !kstep ? 0u : (mode == CTR_STEP_LOCAL ? 1u : 2u);
+    P.pend_bit = (P.mode == 2u) ? (1u << replica) : 0u;
+    float* vals = t->values + (u64)replica * t->tl.replica_stride;
+    double* head = (double*)(batch->ws + wl.off_head);
+    double* tail = (double*)(batch->ws + wl.off_tail);
+    u32* span_flags = (u32*)(batch->ws + wl.off_span_flags);
+    u32* span_rows = (u32*)(batch->ws + wl.off_span_rows);
+    {
+      StageTimer tm(t, CTR_STAGE_PUSH, st);
+      LPR_DISPATCH(t->lpr, k_push_span, blocks_for((u64)wl.n_spans * t->lpr), st, t->hdr, batch->sorted_rows,
+                   batch->sorted_segs, n, d_grad_pooled, vals, t->vhat, t->row_state, t->D, P, head, tail,
+                   span_flags, span_rows);
+    }
+    {
+      StageTimer tm(t, CTR_STAGE_FIXUP, st);
+      LPR_DISPATCH(t->lpr, k_push_fixup, blocks_for((u64)wl.n_spans * WAVE), st, t->hdr, batch->sorted_rows, n,
+                   wl.n_spans, vals, t->vhat, t->row_state, t->D, P, head, tail, span_flags);
+      const u32 grid = std::min<u32>(blocks_for(wl.n_spans), 128);
+      hipLaunchKernelGGL(k_count_unique, dim3(grid), dim3(BLOCK), 0, st, t->hdr, span_rows, wl.n_spans);
+    }
+  }
+  t->live = nullptr;
+  delete batch;
+  return launch_status();
+}
+
+int ctr_kstep_merge(ctr_table* t, void* hip_stream) {
+  if (!t) return CTR_E_INVAL;
+  if (!(t->cfg.flags & CTR_F_KSTEP)) return CTR_E_INVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  StageTimer tm(t, CTR_STAGE_MERGE, st);
+  const u32 grid = std::min<u32>(blocks_for(t->R * t->lpr), 16384);
+  LPR_DISPATCH(t->lpr, k_merge, grid, st, t->hdr, t->values, t->tl.replica_stride, t->W, t->vhat, t->row_state,
+               t->D, t->cfg.lr);
+  return launch_status();
+}
+
+int ctr_table_size(ctr_table* t, uint64_t* n_rows, void* hip_stream) {
+  if (!t || !n_rows) return CTR_E_INVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  DevHeader h;
+  if (hipMemcpyAsync(&h, t->hdr, sizeof(h), hipMemcpyDeviceToHost, st) != hipSuccess) return CTR_E_DEVICE;
+  if (hipStreamSynchronize(st) != hipSuccess) return CTR_E_DEVICE;
+  *n_rows = h.n_rows;
+  return CTR_OK;
+}
+
+int ctr_table_export(ctr_table* t, uint32_t replica, uint64_t* h_keys, float* h_x, float* h_m, float* h_v,
+                     float* h_vhat, void* hip_stream) {
+  if (!t || replica >= t->W) return CTR_E_INVAL;
+  if (h_vhat && !t->vhat) return CTR_E_INVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  uint64_t n = 0;
+  int rc = ctr_table_size(t, &n, hip_stream);
+  if (rc != CTR_OK) return rc;
+  if (n == 0) return CTR_OK;
+  const size_t D = t->D, rowb = D * sizeof(float), pitch = 3 * rowb;
+  const float* vals = t->values + (u64)replica * t->tl.replica_stride;
+  bool ok = true;
+  if (h_keys) ok = ok && hipMemcpyAsync(h_keys, t->row_key, n * sizeof(u64), hipMemcpyDeviceToHost, st) == hipSuccess;
+  if (h_x) ok = ok && hipMemcpy2DAsync(h_x, rowb, vals, pitch, rowb, n, hipMemcpyDeviceToHost, st) == hipSuccess;
+  if (h_m) ok = ok && hipMemcpy2DAsync(h_m, rowb, vals + D, pitch, rowb, n, hipMemcpyDeviceToHost, st) == hipSuccess;
+  if (h_v) ok = ok && hipMemcpy2DAsync(h_v, rowb, vals + 2 * D, pitch, rowb, n, hipMemcpyDeviceToHost, st) == hipSuccess;
+  if (h_vhat) ok = ok && hipMemcpyAsync(h_vhat, t->vhat, n * rowb, hipMemcpyDeviceToHost, st) == hipSuccess;
+  ok = ok && hipStreamSynchronize(st) == hipSuccess;
+  return ok ? CTR_OK : CTR_E_DEVICE;
+}
+
+int ctr_batch_export(ctr_table* t, ctr_batch* batch, uint64_t* n_unique, uint64_t* h_uniq, uint32_t* h_rows,
+                     uint32_t* h_inverse, void* hip_stream) {
+  if (!t || !batch) return CTR_E_INVAL;
+  if (t->live != batch) return CTR_E_STATE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  DevHeader h;
+  if (hipMemcpyAsync(&h, t->hdr, sizeof(h), hipMemcpyDeviceToHost, st) != hipSuccess) return CTR_E_DEVICE;
+  if (hipStreamSynchronize(st) != hipSuccess) return CTR_E_DEVICE;
+  if (h.status) return CTR_E_STATE;  // the pull failed: there is no dedup result
+  const size_t n = batch->n_keys;
+  // Re-expression of device results for comparison: the device keeps the batch's
+  // distinct set as row ids; the canonical form lists the keys in ascending order.
+  std::vector<u32> occ(n);
+  std::vector<u64> row_key(h.n_rows);
+  if (n && hipMemcpyAsync(occ.data(), batch->ws + batch->wl.off_occ_row, n * sizeof(u32), hipMemcpyDeviceToHost,
+                          st) != hipSuccess)
+    return CTR_E_DEVICE;
+  if (h.n_rows && hipMemcpyAsync(row_key.data(), t->row_key, (size_t)h.n_rows * sizeof(u64),
+                                 hipMemcpyDeviceToHost, st) != hipSuccess)
+    return CTR_E_DEVICE;
+  if (hipStreamSynchronize(st) != hipSuccess) return CTR_E_DEVICE;
+  std::vector<u32> rows(occ);
+  std::sort(rows.begin(), rows.end());
+  rows.erase(std::unique(rows.begin(), rows.end()), rows.end());
+  for (u32 r : rows)
+    if (r >= h.n_rows) return CTR_E_DEVICE;
+  std::vector<std::pair<u64, u32>> kr(rows.size());
+  for (size_t i = 0; i < rows.size(); ++i) kr[i] = {row_key[rows[i]], rows[i]};
+  std::sort(kr.begin(), kr.end());
+  if (n_unique) *n_unique = kr.size();
+  if (h_uniq)
+    for (size_t i = 0; i < kr.size(); ++i) h_uniq[i] = kr[i].first;
+  if (h_rows)
+    for (size_t i = 0; i < kr.size(); ++i) h_rows[i] = kr[i].second;
+  if (h_inverse) {
+    std::vector<u32> index_of_row(h.n_rows, 0);
+    for (size_t i = 0; i < kr.size(); ++i) index_of_row[kr[i].second] = (u32)i;
+    for (size_t p = 0; p < n; ++p) h_inverse[p] = index_of_row[occ[p]];
+  }
+  return CTR_OK;
+}
+
+int ctr_batch_stats(ctr_table* t, uint64_t* n_unique, uint64_t* n_new, void* hip_stream) {
+  if (!t) return CTR_E_INVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  DevHeader h;
+  if (hipMemcpyAsync(&h, t->hdr, sizeof(h), hipMemcpyDeviceToHost, st) != hipSuccess) return CTR_E_DEVICE;
+  if (hipStreamSynchronize(st) != hipSuccess) return CTR_E_DEVICE;
+  if (n_unique) *n_unique = h.n_unique;
+  if (n_new) *n_new = h.n_new;
+  return CTR_OK;
+}
+
+int ctr_last_status(ctr_table* t, void* hip_stream) {
+  if (!t) return CTR_E_INVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  DevHeader h;
+  if (hipMemcpyAsync(&h, t->hdr, sizeof(h), hipMemcpyDeviceToHost, st) != hipSuccess) return CTR_E_DEVICE;
+  if (hipStreamSynchronize(st) != hipSuccess) return CTR_E_DEVICE;
+  if (h.status == 0) return CTR_OK;
+  // clear status, pull_err and rollback (three consecutive words after n_rows)
+  if (hipMemsetAsync((char*)t->hdr + offsetof(DevHeader, status), 0, 3 * sizeof(u32), st) != hipSuccess)
+    return CTR_E_DEVICE;
+  if (hipStreamSynchronize(st) != hipSuccess) return CTR_E_DEVICE;
+  return status_code_from_bits(h.status);
+}
+
+int ctr_profile_enable(ctr_table* t, int on) {
+  if (!t) return CTR_E_INVAL;
+  t->profile = on != 0;
+  return CTR_OK;
+}
+
+int ctr_profile_read(ctr_table* t, float* h_ms, uint32_t* h_count) {
+  if (!t || !h_ms) return CTR_E_INVAL;
+  if (hipDeviceSynchronize() != hipSuccess) return CTR_E_DEVICE;
+  for (int i = 0; i < CTR_N_STAGES; ++i) {
+    float total = 0.0f;
+    for (size_t k = 0; k < t->ev_used[i]; ++k) {
+      float ms = 0.0f;
+      if (hipEventElapsedTime(&ms, t->ev_start[i][k], t->ev_stop[i][k]) != hipSuccess) return CTR_E_DEVICE;
+      total += ms;
+    }
+    h_ms[i] = total;
+    if (h_count) h_count[i] = (uint32_t)t->ev_used[i];
+    t->ev_used[i] = 0;
+  }
+  return CTR_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,81 @@
+"""CPU-side checks of the C ABI: the library loads, exports every declared symbol, and the host
+logic (configuration checks, memory sizing) behaves.  No compute call is made here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2201_05500_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _cfg(**kw):
+    d = dict(capacity_rows=1 << 16, dim=8, load_factor=0.5, n_replicas=1, lr=1e-3, beta1=0.9,
+             beta2=0.999, eps=1e-8, init_seed=0, init_std=0.01, flags=0)
+    d.update(kw)
+    return B.ctr_config(*[d[f[0]] for f in B.ctr_config._fields_])
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "ctr_sparse.h")).read()
+    declared = set(re.findall(r"^\s*(?:int|size_t)\s+(ctr_\w+)\s*\(", header, re.M))
+    assert declared == set(B.EXPORTED)
+    lib = C.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_config_struct_matches_header_layout():
+    # uint64, uint32, float, uint32, 4 floats, uint64, float, uint32 with natural alignment
+    assert C.sizeof(B.ctr_config) == 56
+    assert B.ctr_config.init_seed.offset == 40 and B.ctr_config.flags.offset == 52
+
+
+def test_table_bytes_accounts_for_every_array():
+    R, D = 1 << 16, 8
+    n = B.ctr_table_bytes(_cfg())
+    slots = (1 << 17) * 16
+    assert n >= slots + R * 8 + R * 4 + R * 3 * D * 4
+    assert n < slots + R * 8 + R * 4 + R * 3 * D * 4 + 4096
+    k = B.ctr_table_bytes(_cfg(n_replicas=8, flags=B.CTR_F_KSTEP))
+    assert k - n >= 7 * R * 3 * D * 4 + R * D * 4
+    # load factor decides the number of index slots (next power of two of R / lf)
+    assert B.ctr_table_bytes(_cfg(load_factor=0.25)) - n == (1 << 17) * 16
+    assert B.ctr_table_bytes(_cfg(load_factor=0.0)) == n            # 0 selects 0.5
+
+
+@pytest.mark.parametrize("bad", [
+    dict(dim=0), dict(dim=6), dict(dim=260), dict(capacity_rows=0), dict(capacity_rows=(1 << 30) + 1),
+    dict(n_replicas=0), dict(n_replicas=32), dict(load_factor=0.95), dict(load_factor=-1.0),
+    dict(flags=8), dict(lr=0.0), dict(beta1=1.0), dict(beta2=-0.1), dict(eps=0.0),
+])
+def test_invalid_configurations_are_rejected(bad):
+    assert B.ctr_table_bytes(_cfg(**bad)) == 0
+    assert B.ctr_workspace_bytes(_cfg(**bad), 1000, 10) == 0
+    out = C.c_void_p()
+    st = B.lib().ctr_table_create(C.byref(_cfg(**bad)), 256, 1 << 30, None, C.byref(out))
+    assert st == B.CTR_E_INVAL
+
+
+def test_workspace_bytes_grow_with_keys_and_dim():
+    a = B.ctr_workspace_bytes(_cfg(), 10000, 100)
+    b = B.ctr_workspace_bytes(_cfg(), 20000, 100)
+    c = B.ctr_workspace_bytes(_cfg(dim=64), 10000, 100)
+    assert 0 < a < b and a < c
+    assert B.ctr_workspace_bytes(_cfg(), 0, 0) >= 256
+    assert B.ctr_workspace_bytes(_cfg(), 1 << 31, 10) == 0           # n_keys limit
+
+
+def test_null_and_misaligned_arguments():
+    L = B.lib()
+    out = C.c_void_p()
+    assert L.ctr_table_create(None, 256, 1 << 30, None, C.byref(out)) == B.CTR_E_INVAL
+    assert L.ctr_table_create(C.byref(_cfg()), None, 1 << 30, None, C.byref(out)) == B.CTR_E_INVAL
+    assert L.ctr_table_create(C.byref(_cfg()), 264, 1 << 30, None, C.byref(out)) == B.CTR_E_INVAL
+    assert L.ctr_table_create(C.byref(_cfg()), 256, 1024, None, C.byref(out)) == B.CTR_E_NOMEM
+    assert L.ctr_table_destroy(None) == B.CTR_E_INVAL
+    assert L.ctr_kstep_merge(None, None) == B.CTR_E_INVAL
+    assert L.ctr_push_adam(None, 0, None, None, 0, None) == B.CTR_E_INVAL
+    assert L.ctr_last_status(None, None) == B.CTR_E_INVAL

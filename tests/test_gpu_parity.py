@@ -1,0 +1,264 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+
+from oracle import ctr_oracle as O
+from paper_2201_05500_amd import workloads as WL
+from tests.parity_util import (assert_close, compare_batch, compare_tables, run_step, to_device)
+
+pytestmark = pytest.mark.gpu
+
+
+def make_tables(w, seed=1234, **kw):
+    from paper_2201_05500_amd.binding import CtrTable
+    hp = dict(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, init_seed=seed, init_std=w.init_std)
+    hp.update(kw)
+    kstep = w.k_step > 0
+    gt = CtrTable(w.capacity_rows, w.dim, n_replicas=w.n_replicas, kstep=kstep,
+                  load_factor=w.load_factor, **hp)
+    ot = O.OracleTable(w.capacity_rows, w.dim, n_replicas=w.n_replicas, kstep=kstep, **hp)
+    return gt, ot
+
+
+def run_workload(w, steps, **kw):
+    gt, ot = make_tables(w, **kw)
+    for s in range(steps):
+        bn = WL.as_numpy(WL.make_batch(w, s))
+        print("step", s, "L", bn["keys"].size, flush=True)
+        run_step(gt, ot, to_device(bn), bn, what="%s step %d" % (w.name, s))
+        compare_tables(gt, ot, what="%s after step %d" % (w.name, s))
+    return gt, ot
+
+
+def test_tiny_config_exact():
+    """Configuration 1 as stated: 2^16 rows, dim 8, 1024 x 16 slots, uniform 1-8 ids, Zipf 1.1."""
+    run_workload(WL.WORKLOADS["tiny"], 3)
+
+
+def test_tiny_beta1_zero():
+    """beta1 = 0, the paper's production setting for k-step Adam (Section 5)."""
+    run_workload(WL.WORKLOADS["tiny"], 2, beta1=0.0)
+
+
+def test_mid_shape_reduced():
+    """Configuration 2's shape (dim 16, Poisson(3) min 1, Zipf 1.05, 40-bit ids) at 1/64 size."""
+    w = WL.scaled(WL.WORKLOADS["mid"], capacity_rows=1 << 16, zipf_universe=1 << 16, batch=512)
+    run_workload(w, 4)
+
+
+def test_large_shape_reduced():
+    """Configuration 3's shape (dim 64, Poisson(4) with empty slots, Zipf 1.0, 48-bit ids): the hot
+    key spans many work spans, the sort takes three passes (17 row bits)."""
+    w = WL.scaled(WL.WORKLOADS["large"], capacity_rows=(1 << 17) - 5, zipf_universe=100000, batch=256)
+    run_workload(w, 3)
+
+
+@pytest.mark.parametrize("dim", [4, 12, 100, 128, 256])
+def test_other_dims(dim):
+    w = WL.scaled(WL.WORKLOADS["tiny"], dim=dim, batch=64, capacity_rows=5000, zipf_universe=3000)
+    run_workload(w, 2)
+
+
+def _kstep_rounds(w, rounds, k):
+    gt, ot = make_tables(w)
+    step = 0
+    for r in range(rounds):
+        for i in range(1, k + 1):
+            mode = O.STEP_MERGE_PENDING if i == k else O.STEP_LOCAL
+            for j in range(w.n_replicas):
+                bn = WL.as_numpy(WL.make_batch(w, step, replica=j))
+                run_step(gt, ot, to_device(bn), bn, replica=j, mode=mode,
+                         what="round %d step %d replica %d" % (r, i, j))
+            step += 1
+        compare_tables(gt, ot, what="before merge %d" % r)
+        assert gt.kstep_merge() == 0 and ot.kstep_merge() == 0
+        assert gt.last_status() == 0
+        compare_tables(gt, ot, what="after merge %d" % r)
+    return gt, ot
+
+
+def test_kstep_merge_reduced():
+    """Configuration 4's shape (W = 8 replicas, k = 4, dim 16) at reduced size, 3 merge rounds."""
+    w = WL.scaled(WL.WORKLOADS["kstep"], capacity_rows=1 << 14, zipf_universe=1 << 14, batch=64)
+    gt, _ = _kstep_rounds(w, 3, 4)
+    xs = [gt.table_export(j)["x"] for j in range(w.n_replicas)]
+    st = gt.table_export(0)
+    # rows merged in the last round are identical across replicas (zero consensus error after a merge)
+    same = np.all([np.all(xs[0] == x, axis=1) for x in xs[1:]], axis=0)
+    assert same.mean() > 0.2 and st["keys"].size == gt.n_rows
+
+
+def test_kstep_three_replicas_k1():
+    """W = 3 (an average that is not exact in binary), k = 1: every step is a merge step."""
+    w = WL.scaled(WL.WORKLOADS["kstep"], capacity_rows=4096, zipf_universe=3000, batch=16, n_replicas=3,
+                  k_step=1)
+    _kstep_rounds(w, 4, 1)
+
+
+def test_kstep_one_replica_k1_equals_single_table():
+    """Algorithm 2 with N = 1, k = 1 is plain Adam: the two GPU code paths agree to tolerance."""
+    from paper_2201_05500_amd.binding import CtrTable
+    w = WL.scaled(WL.WORKLOADS["tiny"], batch=64, capacity_rows=4096, zipf_universe=3000)
+    a = CtrTable(w.capacity_rows, w.dim, init_seed=5)
+    b = CtrTable(w.capacity_rows, w.dim, init_seed=5, kstep=True)
+    for s in range(3):
+        bt = to_device(WL.as_numpy(WL.make_batch(w, s)))
+        st, ba, pa = a.pull_pool(0, bt["keys"], bt["offsets"])
+        st2, bb, pb = b.pull_pool(0, bt["keys"], bt["offsets"])
+        assert st == 0 and st2 == 0
+        assert a.push_adam(0, ba, bt["grad"]) == 0
+        assert b.push_adam(0, bb, bt["grad"], O.STEP_MERGE_PENDING) == 0
+        assert b.kstep_merge() == 0
+    ea, eb = a.table_export(), b.table_export()
+    assert np.array_equal(ea["keys"], eb["keys"])
+    assert np.array_equal(ea["m"], eb["m"]) and np.array_equal(ea["v"], eb["v"])
+    assert_close(eb["x"], ea["x"], "k=1 one replica vs single table")
+    assert np.array_equal(eb["vhat"], eb["v"])
+
+
+def _manual_batch(keys, offsets, D, seed=0):
+    rng = np.random.default_rng(seed)
+    keys = np.asarray(keys, np.uint64)
+    offsets = np.asarray(offsets, np.uint32)
+    return {"keys": keys, "offsets": offsets,
+            "grad": rng.standard_normal((offsets.size - 1, D)).astype(np.float32)}
+
+
+def _tables(R, D, W=1, kstep=False, seed=3):
+    from paper_2201_05500_amd.binding import CtrTable
+    return (CtrTable(R, D, n_replicas=W, kstep=kstep, init_seed=seed),
+            O.OracleTable(R, D, n_replicas=W, kstep=kstep, init_seed=seed))
+
+
+def test_one_key_repeated_spans_many_work_spans():
+    """Degenerate batch: a single key fills every occurrence (one row crossing every span)."""
+    D = 64
+    for n in (1, 127, 128, 129, 4096, 4097, 20000):
+        gt, ot = _tables(64, D)
+        G = max(1, n // 3)
+        off = np.linspace(0, n, G + 1).astype(np.uint32)
+        bn = _manual_batch(np.full(n, 0xABCDEF123, np.uint64), off, D, seed=n)
+        for s in range(2):
+            run_step(gt, ot, to_device(bn), bn, what="one key n=%d" % n)
+        compare_tables(gt, ot, what="one key n=%d" % n)
+
+
+def test_all_keys_distinct_and_ragged_tail():
+    D = 16
+    for n in (1, 3, 255, 257, 4095, 4099, 12345):
+        gt, ot = _tables(1 << 14, D)
+        keys = (np.arange(n, dtype=np.uint64) + np.uint64(1)) * np.uint64(0x9E3779B97F4A7C15)
+        off = np.unique(np.concatenate([[0, n], np.random.default_rng(n).integers(0, n + 1, n // 2)]))
+        bn = _manual_batch(keys, off, D, seed=n)
+        run_step(gt, ot, to_device(bn), bn, what="distinct n=%d" % n)
+        run_step(gt, ot, to_device(bn), bn, what="distinct again n=%d" % n)
+        compare_tables(gt, ot, what="distinct n=%d" % n)
+
+
+def test_empty_batch_and_empty_segments():
+    D = 8
+    gt, ot = _tables(64, D)
+    bn = _manual_batch([], [0, 0, 0, 0], D)
+    gp = run_step(gt, ot, to_device(bn), bn, what="empty batch")
+    assert np.all(gp == 0) and gt.n_rows == 0
+    bn = _manual_batch([5, 9, 5], [0, 0, 2, 2, 3, 3], D)
+    gp = run_step(gt, ot, to_device(bn), bn, what="empty segments")
+    assert np.all(gp[[0, 2, 4]] == 0)
+    compare_tables(gt, ot, what="empty segments")
+
+
+def test_capacity_edge_full_and_rollback():
+    """Exactly R distinct keys fit; one more gives CTR_E_FULL and leaves table and index as they were."""
+    from paper_2201_05500_amd import binding as B
+    D, R = 8, 300
+    gt, ot = _tables(R, D)
+    keys = np.arange(1, R + 1, dtype=np.uint64) * np.uint64(7919)
+    bn = _manual_batch(keys, [0, R // 2, R], D)
+    run_step(gt, ot, to_device(bn), bn, what="fill to capacity")
+    assert gt.n_rows == R
+    before = gt.table_export()
+    # 40 known keys + 25 new ones: must fail as a whole
+    k2 = np.concatenate([keys[:40], np.arange(1, 26, dtype=np.uint64) * np.uint64(104729) + np.uint64(1 << 40)])
+    b2 = _manual_batch(k2, [0, 10, k2.size], D, seed=2)
+    bt = to_device(b2)
+    st, gb, _ = gt.pull_pool(0, bt["keys"], bt["offsets"])
+    assert st == B.CTR_OK                       # device-detected: deferred
+    assert ot.pull_pool(0, b2["keys"], b2["offsets"])[0] == O.E_FULL
+    assert gt.push_adam(0, gb, bt["grad"]) == B.CTR_OK      # no-op while the status is set
+    assert gt.last_status() == B.CTR_E_FULL
+    assert gt.last_status() == B.CTR_OK                      # cleared by the read
+    assert gt.n_rows == R
+    after = gt.table_export()
+    for f in ("keys", "x", "m", "v"):
+        assert np.array_equal(before[f], after[f]), f
+    # the index is intact: the old keys still resolve, and the table still works
+    run_step(gt, ot, to_device(bn), bn, what="after rollback")
+    compare_tables(gt, ot, what="after rollback")
+    # many more distinct keys than index slots
+    k3 = np.arange(1, 5000, dtype=np.uint64) * np.uint64(15485863)
+    b3 = to_device(_manual_batch(k3, [0, k3.size], D))
+    st, gb, _ = gt.pull_pool(0, b3["keys"], b3["offsets"])
+    assert st == B.CTR_OK and gt.last_status() == B.CTR_E_FULL
+    run_step(gt, ot, to_device(bn), bn, what="after second rollback")
+    compare_tables(gt, ot, what="after second rollback")
+
+
+def test_bad_key_and_bad_offsets_are_deferred_errors_without_side_effects():
+    from paper_2201_05500_amd import binding as B
+    D = 8
+    gt, ot = _tables(128, D)
+    bn = _manual_batch([11, 12, 13, 11], [0, 2, 4], D)
+    run_step(gt, ot, to_device(bn), bn, what="warm")
+    bad = to_device(_manual_batch([21, 2 ** 64 - 1, 22], [0, 3], D))
+    st, gb, _ = gt.pull_pool(0, bad["keys"], bad["offsets"])
+    assert st == B.CTR_OK and gt.last_status() == B.CTR_E_BADKEY and gt.n_rows == 3
+    for offs in ([0, 2], [1, 3], [0, 3, 2, 3]):
+        bo = to_device(_manual_batch([31, 32, 33], offs, D))
+        st, gb, _ = gt.pull_pool(0, bo["keys"], bo["offsets"])
+        assert st == B.CTR_OK and gt.last_status() == B.CTR_E_INVAL and gt.n_rows == 3, offs
+    ok = _manual_batch([21, 31, 11], [0, 3], D)
+    run_step(gt, ot, to_device(ok), ok, what="after errors")     # 21 and 31 were rolled back: new rows 3, 4
+    compare_tables(gt, ot, what="after errors")
+
+
+def test_host_detected_errors():
+    from paper_2201_05500_amd import binding as B
+    import torch
+    D = 8
+    gt, ot = _tables(128, D, W=2, kstep=True)
+    bt = to_device(_manual_batch([1, 2], [0, 2], D))
+    st, b1, _ = gt.pull_pool(0, bt["keys"], bt["offsets"])
+    assert st == B.CTR_OK
+    st, b2, _ = gt.pull_pool(1, bt["keys"], bt["offsets"])          # b1 goes stale
+    assert gt.push_adam(0, b1, bt["grad"]) == B.CTR_E_STATE
+    assert gt.push_adam(0, b2, bt["grad"]) == B.CTR_E_STATE          # wrong replica
+    assert gt.push_adam(1, b2, bt["grad"], 9) == B.CTR_E_INVAL
+    assert gt.push_adam(1, b2, bt["grad"]) == B.CTR_OK
+    assert gt.push_adam(1, b2, bt["grad"]) == B.CTR_E_STATE          # consumed
+    assert gt.pull_pool(2, bt["keys"], bt["offsets"])[0] == B.CTR_E_INVAL
+    st, _ = B.ctr_pull_pool(gt._handle, 0, bt["keys"].data_ptr(), 2, bt["offsets"].data_ptr(), 1,
+                            torch.empty(8, device="cuda").data_ptr(), gt._ws.data_ptr(), 16, gt.stream)
+    assert st == B.CTR_E_NOMEM
+    single = _tables(16, D)[0]
+    assert single.kstep_merge() == B.CTR_E_INVAL
+    torch.cuda.synchronize()
+
+
+def test_same_calls_give_bit_identical_results():
+    w = WL.scaled(WL.WORKLOADS["large"], capacity_rows=1 << 15, zipf_universe=20000, batch=64)
+    outs = []
+    for rep in range(2):
+        gt, _ = make_tables(w)
+        pooled = []
+        for s in range(3):
+            bt = to_device(WL.as_numpy(WL.make_batch(w, s)))
+            st, gb, p = gt.pull_pool(0, bt["keys"], bt["offsets"])
+            exp = gt.batch_export(gb, bt["keys"].numel())
+            assert gt.push_adam(0, gb, bt["grad"]) == 0
+            pooled.append((p.cpu().numpy(),) + exp)
+        outs.append((pooled, gt.table_export()))
+    for a, b in zip(outs[0][0], outs[1][0]):
+        for x, y in zip(a, b):
+            assert np.array_equal(x, y)
+    for f in ("keys", "x", "m", "v"):
+        assert np.array_equal(outs[0][1][f], outs[1][1][f]), f
