@@ -1,0 +1,228 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse embedding cycle on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic mini-batch: ctr_pull_pool (probe with
+insert-on-miss, row gather + per-slot sum, grouping of occurrences by row) followed by
+ctr_push_adam (gradient segment-reduce fused with sparse Adam).  All inputs of all steps are
+generated on the device before the timed region starts.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload large|mid|tiny|kstep]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes_step(L, G, U, n_new, D, kstep):
+    """Bytes one step must move (no sort scratch, no re-reads of hot rows)."""
+    b = 8 * L                   # keys read
+    b += 2 * 4 * (G + 1)        # offsets read by pull and by push-side bookkeeping
+    b += 2 * 8 * U              # distinct set written and read
+    b += 3 * 4 * L              # occurrence -> distinct map written, read by pool, read by push
+    b += 16 * U + 16 * n_new    # index probe (key + row id) per distinct key, plus inserts
+    b += 4 * D * U              # compulsory row reads for pooling
+    b += 4 * D * G              # pooled write
+    b += 4 * D * G              # pooled-gradient read
+    b += 6 * 4 * D * U          # Adam: read + write x, m, v
+    if kstep:
+        b += 4 * D * U          # shared denominator read
+    return b
+
+
+def algorithmic_bytes_push_kernel(L, G, U, D, kstep):
+    """The push kernel's share: occurrence map read, pooled-gradient read, Adam read + write."""
+    return 4 * L + 4 * D * G + 6 * 4 * D * U + (4 * D * U if kstep else 0)
+
+
+def algorithmic_bytes_pool_kernel(L, G, U, D):
+    """The pool kernel's share: offsets and occurrence map read, compulsory row reads, pooled write."""
+    return 4 * (G + 1) + 4 * L + 4 * D * U + 4 * D * G
+
+
+def cpu_baseline(w, WL, seconds_hint=20.0):
+    """The oracle as it stands, one thread, on a bounded sample of the same workload."""
+    from oracle import ctr_oracle as O
+    frac = {"large": 8, "mid": 1, "tiny": 1, "kstep": 1}.get(w.name, 1)
+    ws = WL.scaled(w, batch=max(1, w.batch // frac))
+    ot = O.OracleTable(ws.capacity_rows, ws.dim, n_replicas=1, lr=ws.lr, beta1=ws.beta1, beta2=ws.beta2,
+                       eps=ws.eps, init_seed=1, init_std=ws.init_std)
+    n_steps, keys_done, t_spent = 0, 0, 0.0
+    while t_spent < seconds_hint / 2 and n_steps < 3:
+        bn = WL.as_numpy(WL.make_batch(ws, n_steps))
+        t0 = time.perf_counter()
+        st, _ = ot.pull_pool(0, bn["keys"], bn["offsets"])
+        assert st == 0
+        assert ot.push_adam(0, bn["grad"]) == 0
+        t_spent += time.perf_counter() - t0
+        keys_done += bn["keys"].size
+        n_steps += 1
+    ot.close()
+    return {
+        "value": keys_done / t_spent, "unit": "keys/s", "cores": 1, "kind": "oracle",
+        "sample": "%d step(s) of the first %d of %d samples per batch (%d key occurrences), table "
+                  "starting empty, %.1f s" % (n_steps, ws.batch, w.batch, keys_done, t_spent),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="large")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device copy, so that a counter run has a kernel of known traffic")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (one shard of the parameter server); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2201_05500_amd import workloads as WL
+    from paper_2201_05500_amd.binding import (CTR_OK, CTR_STEP_LOCAL, CTR_STEP_MERGE_PENDING, CtrTable)
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    w = WL.WORKLOADS[args.workload]
+    kstep = w.k_step > 0
+    K, Wm = args.steps, args.warmup
+    total_steps = K + Wm
+
+    table = CtrTable(w.capacity_rows, w.dim, n_replicas=w.n_replicas, lr=w.lr, beta1=w.beta1,
+                     beta2=w.beta2, eps=w.eps, init_seed=1, init_std=w.init_std, kstep=kstep,
+                     load_factor=w.load_factor, device=dev)
+
+    # every input of every step resident in HBM before timing; for the k-step workload a "step"
+    # is one local step of every replica (plus the merge on every k-th)
+    reps = w.n_replicas if kstep else 1
+    batches = []
+    max_keys = 1
+    for s in range(total_steps):
+        for j in range(reps):
+            b = WL.make_batch(w, s, replica=j, device=dev)
+            batches.append(b)
+            max_keys = max(max_keys, b["keys"].numel())
+    G = w.n_segments
+    table.reserve(max_keys, G)
+    pooled = torch.empty((G, w.dim), dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    def run_step(s):
+        mode = CTR_STEP_LOCAL
+        if kstep and (s + 1) % w.k_step == 0:
+            mode = CTR_STEP_MERGE_PENDING
+        for j in range(reps):
+            b = batches[s * reps + j]
+            st, h, _ = table.pull_pool(j, b["keys"], b["offsets"], pooled)
+            if st != CTR_OK:
+                raise RuntimeError("ctr_pull_pool: %d" % st)
+            st = table.push_adam(j, h, b["grad"], mode)
+            if st != CTR_OK:
+                raise RuntimeError("ctr_push_adam: %d" % st)
+        if mode == CTR_STEP_MERGE_PENDING:
+            st = table.kstep_merge()
+            if st != CTR_OK:
+                raise RuntimeError("ctr_kstep_merge: %d" % st)
+
+    table.profile_enable(True)
+    for s in range(Wm):
+        run_step(s)
+    torch.cuda.synchronize()
+    if table.last_status() != CTR_OK:
+        raise RuntimeError("device status after warmup")
+    table.profile_read()                       # drop the warmup records
+    rows_before = table.n_rows
+
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(Wm, total_steps):
+        run_step(s)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    stages = table.profile_read()              # HIP events recorded on the launch stream, timed steps only
+    status = table.last_status()
+    if status != CTR_OK:
+        raise RuntimeError("device status %d after the timed steps" % status)
+    rows_after = table.n_rows
+    elapsed = t1 - t0
+    keys_total = sum(batches[i]["keys"].numel() for i in range(Wm * reps, total_steps * reps))
+    L_mean = keys_total / (K * reps)
+
+    # distinct keys per batch, measured on the timed batches (not timed)
+    uniq = [int(torch.unique(batches[i]["keys"]).numel()) for i in range(Wm * reps, total_steps * reps)]
+    U_mean = sum(uniq) / len(uniq)
+    n_new_mean = (rows_after - rows_before) / (K * reps)
+
+    D = w.dim
+    step_bytes = algorithmic_bytes_step(L_mean, G, U_mean, n_new_mean, D, kstep)
+    ms_step = elapsed * 1e3 / K
+    stage_ms = {n: (ms / c if c else 0.0) for n, (ms, c) in stages.items()}
+    kernel_bytes = {
+        "push": algorithmic_bytes_push_kernel(L_mean, G, U_mean, D, kstep),
+        "pool": algorithmic_bytes_pool_kernel(L_mean, G, U_mean, D),
+    }
+    dominant = max(kernel_bytes, key=lambda n: stage_ms[n])
+    achieved = kernel_bytes[dominant] / (stage_ms[dominant] * 1e-3) / 1e9 if stage_ms[dominant] else 0.0
+
+    out = {
+        "metric": "pulled+updated keys/sec per step and achieved HBM GB/s vs peak (1 GPU)",
+        "value": keys_total / elapsed,
+        "unit": "keys/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": Wm,
+        "ms_per_step": ms_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": "%s: R=%d rows, dim %d, batch %d x %d slots, Zipf s=%g over %d ranks, %d-bit keys%s" % (
+                w.name, w.capacity_rows, w.dim, w.batch, w.slots, w.zipf_s, w.zipf_universe, w.key_bits,
+                (", W=%d replicas, k=%d" % (w.n_replicas, w.k_step)) if kstep else ""),
+            "keys_per_batch": L_mean,
+            "distinct_keys_per_batch": U_mean,
+            "new_rows_per_batch": n_new_mean,
+            "rows_in_table": rows_after,
+        },
+        "rows_per_s": U_mean * K * reps / elapsed,
+        "step_algorithmic_GBps": step_bytes * reps / (ms_step * 1e-3) / 1e9,
+        "step_frac_of_hbm_peak": step_bytes * reps / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "stage_ms": stage_ms,
+        "roofline": {
+            "bound": "hbm",
+            "kernel": {"push": "k_push_span", "pool": "k_pool"}[dominant],
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBPS,
+            "traffic": None,
+        },
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, WL)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
