@@ -67,16 +67,17 @@ bool table_layout(const ctr_config* c, TableLayout* L) {
 }
 
 struct WorkLayout {
-  u32 n_rank_tiles, n_spans;
+  u32 n_rank_tiles, n_spans, n_span_blocks;
   SortGeom geo;
   size_t off_occ_row, off_seg_of, off_ka, off_va, off_kb, off_vb, off_hist, off_digit_total, off_tile_count,
-      off_head, off_tail, off_span_flags, off_span_rows, total;
+      off_head, off_tail, off_block_head, off_span_flags, off_span_rows, total;
 };
 
 void work_layout(u32 D, u64 n_keys, WorkLayout* L) {
   const u64 n = n_keys;
   L->n_rank_tiles = (u32)((n + RANK_TILE - 1) / RANK_TILE);
   L->n_spans = (u32)((n + SPAN - 1) / SPAN);
+  L->n_span_blocks = (L->n_spans + SPANS_PER_BLOCK - 1) / SPANS_PER_BLOCK;
   u64 tiles = (n + SORT_TILE - 1) / SORT_TILE;
   u64 chunks = std::min<u64>(std::max<u64>(tiles, 1), SORT_MAX_CHUNKS);
   u64 per = (n + chunks - 1) / chunks;
@@ -97,6 +98,7 @@ void work_layout(u32 D, u64 n_keys, WorkLayout* L) {
   L->off_tile_count = o; o += align256(((size_t)L->n_rank_tiles + 1) * sizeof(u32));
   L->off_head = o; o += align256((size_t)L->n_spans * D * sizeof(double));
   L->off_tail = o; o += align256((size_t)L->n_spans * D * sizeof(double));
+  L->off_block_head = o; o += align256((size_t)L->n_span_blocks * D * sizeof(double));
   L->off_span_flags = o; o += align256((size_t)L->n_spans * sizeof(u32));
   L->off_span_rows = o; o += align256((size_t)L->n_spans * sizeof(u32));
   L->total = std::max<size_t>(o, 256);
@@ -328,8 +330,9 @@ int ctr_pull_pool(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint64
   if (n_segments > 0) {
     StageTimer tm(t, CTR_STAGE_POOL, st);
     const float* vals = t->values + (u64)replica * t->tl.replica_stride;
-    LPR_DISPATCH(t->lpr, k_pool, blocks_for((u64)n_segments * t->lpr), st, t->hdr, occ_row, seg_of, d_offsets,
-                 n_segments, vals, t->D, d_pooled);
+    const u32 segs_per_block = (BLOCK / t->lpr) * POOL_NS * POOL_ROUNDS;
+    LPR_DISPATCH(t->lpr, k_pool, (n_segments + segs_per_block - 1) / segs_per_block, st, t->hdr, occ_row, seg_of,
+                 d_offsets, n_segments, vals, t->D, d_pooled);
   }
   if (n > 0) {
     StageTimer tm(t, CTR_STAGE_SORT, st);
@@ -397,6 +400,7 @@ int ctr_push_adam(ctr_table* t, uint32_t replica, ctr_batch* batch, const float*
     float* vals = t->values + (u64)replica * t->tl.replica_stride;
     double* head = (double*)(batch->ws + wl.off_head);
     double* tail = (double*)(batch->ws + wl.off_tail);
+    double* block_head = (double*)(batch->ws + wl.off_block_head);
     u32* span_flags = (u32*)(batch->ws + wl.off_span_flags);
     u32* span_rows = (u32*)(batch->ws + wl.off_span_rows);
     {
@@ -407,8 +411,10 @@ int ctr_push_adam(ctr_table* t, uint32_t replica, ctr_batch* batch, const float*
     }
     {
       StageTimer tm(t, CTR_STAGE_FIXUP, st);
+      LPR_DISPATCH(t->lpr, k_push_block_heads, blocks_for((u64)wl.n_span_blocks * WAVE), st, t->hdr,
+                   batch->sorted_rows, wl.n_spans, t->D, head, block_head);
       LPR_DISPATCH(t->lpr, k_push_fixup, blocks_for((u64)wl.n_spans * WAVE), st, t->hdr, batch->sorted_rows, n,
-                   wl.n_spans, vals, t->vhat, t->row_state, t->D, P, head, tail, span_flags);
+                   wl.n_spans, vals, t->vhat, t->row_state, t->D, P, head, tail, block_head, span_flags);
       const u32 grid = std::min<u32>(blocks_for(wl.n_spans), 128);
       hipLaunchKernelGGL(k_count_unique, dim3(grid), dim3(BLOCK), 0, st, t->hdr, span_rows, wl.n_spans);
     }

@@ -10,17 +10,21 @@
 // lane owns 4 columns) walks one span, summing grad[ss[i], :] in binary64.  A
 // row that lies wholly inside a span is updated on the spot.  A row that
 // crosses a span boundary leaves binary64 partial sums (the span where it
-// starts writes a "tail", every later span it reaches writes a "head"); a
-// second launch adds them up in a fixed order and updates the row.  Work per
-// group is bounded by SPAN whatever the popularity of a key, and the summation
-// order is fixed, so results do not depend on scheduling.
+// starts writes a "tail", every later span it reaches writes a "head").  Heads
+// of runs of spans that continue one row are pre-summed per block of
+// SPANS_PER_BLOCK spans, and a last launch adds tail + heads + block sums in a
+// fixed order and updates the row.  Work per group is bounded by SPAN whatever
+// the popularity of a key, and the summation order is fixed, so results do not
+// depend on scheduling.
 #pragma once
 #include "common.h"
 
 namespace ctr {
 
 constexpr u32 SPAN = 128;
+constexpr u32 SPANS_PER_BLOCK = 64;  // one wave lane per span when scanning a block
 constexpr u32 SF_HEAD = 1u, SF_TAIL = 2u;
+constexpr u32 NO_ROW = 0xFFFFFFFFu;
 
 struct AdamParams {
   double b1, omb1, b2, omb2;  // beta and (1 - beta) promoted from binary32
@@ -30,13 +34,27 @@ struct AdamParams {
   u32 pend_bit;  // (1 << replica) when mode == 2, else 0
 };
 
-// One Adam step on 4 columns of one row.  m and v are formed in binary64 from
-// the stored binary32 values and rounded once; the model step is binary32 with
-// correctly rounded sqrt and divide.
-__device__ __forceinline__ void adam_row4(float* __restrict__ row_base, const float* __restrict__ vhat_row,
-                                          u32 D, u32 c, d4 g, const AdamParams& P) {
+struct RowState4 {
+  f4 x, m, v;
+};
+
+__device__ __forceinline__ RowState4 load_row4(const float* __restrict__ row_base, u32 D, u32 c) {
+  RowState4 s;
+  const float* px = row_base + 4 * c;
+  s.x = ldg4(px);
+  s.m = ldg4(px + D);
+  s.v = ldg4(px + 2 * D);
+  return s;
+}
+
+// One Adam step on 4 columns of one row whose state is already in registers.
+// m and v are formed in binary64 from the stored binary32 values and rounded
+// once; the model step is binary32 with correctly rounded sqrt and divide.
+__device__ __forceinline__ void adam_apply4(RowState4 s, float* __restrict__ row_base,
+                                            const float* __restrict__ vhat_row, u32 D, u32 c, d4 g,
+                                            const AdamParams& P) {
   float* px = row_base + 4 * c;
-  f4 x = ldg4(px), m = ldg4(px + D), v = ldg4(px + 2 * D);
+  f4 x = s.x, m = s.m, v = s.v;
   m.x = (float)(P.b1 * (double)m.x + P.omb1 * g.x);
   m.y = (float)(P.b1 * (double)m.y + P.omb1 * g.y);
   m.z = (float)(P.b1 * (double)m.z + P.omb1 * g.z);
@@ -58,13 +76,35 @@ __device__ __forceinline__ void adam_row4(float* __restrict__ row_base, const fl
   }
 }
 
-__device__ __forceinline__ void finish_row(u32 row, d4 g, u32 c, bool col_ok, float* __restrict__ values,
-                                           const float* __restrict__ vhat, u32* __restrict__ row_state, u32 D,
-                                           const AdamParams& P) {
-  if (col_ok) adam_row4(values + (u64)row * 3 * D, vhat ? vhat + (u64)row * D : nullptr, D, c, g, P);
+__device__ __forceinline__ void finish_row_loaded(u32 row, RowState4 s, d4 g, u32 c, bool col_ok,
+                                                  float* __restrict__ values, const float* __restrict__ vhat,
+                                                  u32* __restrict__ row_state, u32 D, const AdamParams& P) {
+  if (col_ok) adam_apply4(s, values + (u64)row * 3 * D, vhat ? vhat + (u64)row * D : nullptr, D, c, g, P);
   if (P.kstep && c == 0) atomicOr(&row_state[row], RS_TOUCHED | P.pend_bit);
 }
 
+__device__ __forceinline__ void finish_row(u32 row, d4 g, u32 c, bool col_ok, float* __restrict__ values,
+                                           const float* __restrict__ vhat, u32* __restrict__ row_state, u32 D,
+                                           const AdamParams& P) {
+  RowState4 s;
+  if (col_ok) s = load_row4(values + (u64)row * 3 * D, D, c);
+  finish_row_loaded(row, s, g, c, col_ok, values, vhat, row_state, D, P);
+}
+
+__device__ __forceinline__ void store_partial(double* __restrict__ part, u32 s, u32 D, u32 c, d4 a) {
+  double* p = part + ((u64)s * D + 4 * c);
+  p[0] = a.x; p[1] = a.y; p[2] = a.z; p[3] = a.w;
+}
+
+__device__ __forceinline__ void add_partial(const double* __restrict__ part, u32 s, u32 D, u32 c, d4& a) {
+  const double* p = part + ((u64)s * D + 4 * c);
+  a.x += p[0]; a.y += p[1]; a.z += p[2]; a.w += p[3];
+}
+
+// Span walk.  Each batch of PB occurrences issues, before anything is consumed,
+// the PB gradient-row loads and the x/m/v loads of every row that ends inside
+// the batch, so that a group keeps several KB in flight instead of one
+// dependent row at a time.
 template <int LPR>
 __global__ void __launch_bounds__(BLOCK)
 k_push_span(const DevHeader* hdr, const u32* __restrict__ sr, const u32* __restrict__ ss, u32 n,
@@ -72,6 +112,7 @@ k_push_span(const DevHeader* hdr, const u32* __restrict__ sr, const u32* __restr
             u32* __restrict__ row_state, u32 D, AdamParams P, double* __restrict__ head_part,
             double* __restrict__ tail_part, u32* __restrict__ span_flags, u32* __restrict__ span_rows) {
   if (hdr->status) return;
+  constexpr int PB = 4;
   const u32 s = (blockIdx.x * BLOCK + threadIdx.x) / LPR;
   const u32 c = threadIdx.x % LPR;
   const u32 b = s * SPAN;
@@ -79,114 +120,169 @@ k_push_span(const DevHeader* hdr, const u32* __restrict__ sr, const u32* __restr
   const u32 e = min(b + SPAN, n);
   const bool col_ok = c * 4 < D;
 
-  u32 cur = sr[b];
-  bool open_left = (b > 0) && (sr[b - 1] == cur);
-  u32 flags = 0, finished = 0;
+  bool first_row_open = (b > 0) && (sr[b - 1] == sr[b]);  // the span starts inside a row begun earlier
+  u32 flags = 0, started = 0;
   d4 acc = {0.0, 0.0, 0.0, 0.0};
 
-  for (u32 i0 = b; i0 < e; i0 += 4) {
-    u32 r[4], g[4];
-    f4 gv[4];
+  for (u32 i0 = b; i0 < e; i0 += PB) {
+    u32 r[PB + 1], g[PB];
+    if constexpr (LPR > PB) {  // one coalesced index load per group, then broadcast
+      const u32 mine_r = (c <= PB && i0 + c < n) ? sr[i0 + c] : NO_ROW;
+      const u32 mine_g = (c < PB && i0 + c < e) ? ss[i0 + c] : 0u;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const bool ok = i0 + i < e;
-      r[i] = ok ? sr[i0 + i] : cur;
-      g[i] = ok ? ss[i0 + i] : 0u;
+      for (int i = 0; i <= PB; ++i) r[i] = __shfl(mine_r, i, LPR);
+#pragma unroll
+      for (int i = 0; i < PB; ++i) g[i] = __shfl(mine_g, i, LPR);
+    } else {
+#pragma unroll
+      for (int i = 0; i <= PB; ++i) r[i] = (i0 + i < n) ? sr[i0 + i] : NO_ROW;
+#pragma unroll
+      for (int i = 0; i < PB; ++i) g[i] = (i0 + i < e) ? ss[i0 + i] : 0u;
     }
+    bool valid[PB], ends[PB], whole[PB];
+    bool fo = first_row_open;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < PB; ++i) {
+      valid[i] = i0 + i < e;
+      ends[i] = valid[i] && r[i + 1] != r[i];  // last occurrence of its row (r[i+1] is NO_ROW past the end)
+      whole[i] = ends[i] && !fo;               // and the row began inside this span
+      if (ends[i]) fo = false;
+    }
+    f4 gv[PB];
+    RowState4 st[PB];
+#pragma unroll
+    for (int i = 0; i < PB; ++i) {
       gv[i].x = gv[i].y = gv[i].z = gv[i].w = 0.0f;
-      if (i0 + i < e && col_ok) gv[i] = ldg4(grad + (u64)g[i] * D + 4 * c);
+      if (valid[i] && col_ok) gv[i] = ldg4(grad + (u64)g[i] * D + 4 * c);
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (i0 + i < e) {
-        if (r[i] != cur) {  // the row `cur` ends here
-          if (open_left) {
-            if (col_ok) {
-              double* hp = head_part + ((u64)s * D + 4 * c);
-              hp[0] = acc.x; hp[1] = acc.y; hp[2] = acc.z; hp[3] = acc.w;
-            }
-            flags |= SF_HEAD;
-            open_left = false;
-          } else {
-            finish_row(cur, acc, c, col_ok, values, vhat, row_state, D, P);
-            ++finished;
-          }
-          cur = r[i];
-          acc.x = acc.y = acc.z = acc.w = 0.0;
-        }
+    for (int i = 0; i < PB; ++i)
+      if (whole[i] && col_ok) st[i] = load_row4(values + (u64)r[i] * 3 * D, D, c);
+#pragma unroll
+    for (int i = 0; i < PB; ++i) {
+      if (valid[i]) {
         acc.x += (double)gv[i].x;
         acc.y += (double)gv[i].y;
         acc.z += (double)gv[i].z;
         acc.w += (double)gv[i].w;
+        if (ends[i]) {
+          if (whole[i]) {
+            finish_row_loaded(r[i], st[i], acc, c, col_ok, values, vhat, row_state, D, P);
+            ++started;
+          } else {  // end of the row that was open on entry
+            if (col_ok) store_partial(head_part, s, D, c, acc);
+            flags |= SF_HEAD;
+            first_row_open = false;
+          }
+          acc.x = acc.y = acc.z = acc.w = 0.0;
+        }
       }
     }
   }
 
-  const bool open_right = (e < n) && (sr[e] == cur);
-  if (open_left) {  // the whole span belongs to a row that began earlier
-    if (col_ok) {
-      double* hp = head_part + ((u64)s * D + 4 * c);
-      hp[0] = acc.x; hp[1] = acc.y; hp[2] = acc.z; hp[3] = acc.w;
+  // the last occurrence did not end its row: the row goes on in the next span
+  if (sr[e - 1] == ((e < n) ? sr[e] : NO_ROW)) {
+    if (first_row_open) {  // the whole span lies inside one row that began earlier
+      if (col_ok) store_partial(head_part, s, D, c, acc);
+      flags |= SF_HEAD;
+    } else {
+      if (col_ok) store_partial(tail_part, s, D, c, acc);
+      flags |= SF_TAIL;
+      ++started;
     }
-    flags |= SF_HEAD;
-  } else if (open_right) {  // the row began in this span and goes on
-    if (col_ok) {
-      double* tp = tail_part + ((u64)s * D + 4 * c);
-      tp[0] = acc.x; tp[1] = acc.y; tp[2] = acc.z; tp[3] = acc.w;
-    }
-    flags |= SF_TAIL;
-  } else {
-    finish_row(cur, acc, c, col_ok, values, vhat, row_state, D, P);
-    ++finished;
   }
   if (c == 0) {
     span_flags[s] = flags;
-    span_rows[s] = finished + ((flags & SF_TAIL) ? 1u : 0u);  // rows that START in this span
+    span_rows[s] = started;  // rows that START in this span
   }
 }
 
-// One wave per span that holds a tail: adds the tail and the heads of the
-// following spans that continue the same row (its groups take the spans in
-// turn, then combine), and updates the row.
+// Number of leading lanes (from lane 0) whose predicate holds; wave-uniform.
+__device__ __forceinline__ u32 leading_true(bool pred) {
+  const u64 inv = ~__ballot(pred);
+  return inv ? (u32)(__ffsll((long long)inv) - 1) : 64u;
+}
+
+// Combines per-group binary64 partial sums of a wave (groups of LPR lanes, same column layout).
+template <int LPR>
+__device__ __forceinline__ void combine_groups(d4& a) {
+#pragma unroll
+  for (int off = LPR; off < WAVE; off <<= 1) {
+    a.x += __shfl_xor(a.x, off, WAVE);
+    a.y += __shfl_xor(a.y, off, WAVE);
+    a.z += __shfl_xor(a.z, off, WAVE);
+    a.w += __shfl_xor(a.w, off, WAVE);
+  }
+}
+
+// One wave per block of SPANS_PER_BLOCK spans (block j >= 1): sums the heads of the
+// block's leading spans that continue the row open at the block's start.
+template <int LPR>
+__global__ void __launch_bounds__(BLOCK)
+k_push_block_heads(const DevHeader* hdr, const u32* __restrict__ sr, u32 n_spans, u32 D,
+                   const double* __restrict__ head_part, double* __restrict__ block_head) {
+  if (hdr->status) return;
+  constexpr int GPW = WAVE / LPR;
+  const u32 j = (blockIdx.x * BLOCK + threadIdx.x) / WAVE;  // wave-uniform
+  const u32 first = j * SPANS_PER_BLOCK;
+  if (j == 0 || first >= n_spans) return;
+  const int lane = lane_id();
+  const u32 c = lane % LPR, grp = lane / LPR;
+  const bool col_ok = c * 4 < D;
+  const u32 row = sr[first * SPAN - 1];
+  const u32 t = first + lane;
+  const u32 n_lead = leading_true(t < n_spans && sr[t * SPAN] == row);
+  if (n_lead == 0) return;
+  d4 acc = {0.0, 0.0, 0.0, 0.0};
+  if (col_ok)
+    for (u32 k = grp; k < n_lead; k += GPW) add_partial(head_part, first + k, D, c, acc);
+  combine_groups<LPR>(acc);
+  if (grp == 0 && col_ok) store_partial(block_head, j, D, c, acc);
+}
+
+// One wave per span that holds a tail: tail + heads of the following spans of
+// the same block + block sums of the following blocks, while they continue
+// the same row; then the row update.
 template <int LPR>
 __global__ void __launch_bounds__(BLOCK)
 k_push_fixup(const DevHeader* hdr, const u32* __restrict__ sr, u32 n, u32 n_spans, float* __restrict__ values,
              const float* __restrict__ vhat, u32* __restrict__ row_state, u32 D, AdamParams P,
              const double* __restrict__ head_part, const double* __restrict__ tail_part,
-             const u32* __restrict__ span_flags) {
+             const double* __restrict__ block_head, const u32* __restrict__ span_flags) {
   if (hdr->status) return;
   constexpr int GPW = WAVE / LPR;
   const u32 s = (blockIdx.x * BLOCK + threadIdx.x) / WAVE;  // wave-uniform
   if (s >= n_spans) return;
   if (!(span_flags[s] & SF_TAIL)) return;
   const int lane = lane_id();
-  const u32 c = lane % LPR;
-  const u32 grp = lane / LPR;
+  const u32 c = lane % LPR, grp = lane / LPR;
   const bool col_ok = c * 4 < D;
-  const u32 row = sr[min((s + 1) * SPAN, n) - 1];
+  const u32 row = sr[(s + 1) * SPAN - 1];  // a tail means the span is full and the list goes on
+  const u32 n_blocks = (n_spans + SPANS_PER_BLOCK - 1) / SPANS_PER_BLOCK;
+  const u32 blk_end = min((s / SPANS_PER_BLOCK + 1) * SPANS_PER_BLOCK, n_spans);
 
   d4 acc = {0.0, 0.0, 0.0, 0.0};
+  RowState4 st;
   if (grp == 0 && col_ok) {
-    const double* tp = tail_part + ((u64)s * D + 4 * c);
-    acc.x = tp[0]; acc.y = tp[1]; acc.z = tp[2]; acc.w = tp[3];
+    add_partial(tail_part, s, D, c, acc);
+    st = load_row4(values + (u64)row * 3 * D, D, c);
   }
-  for (u32 t = s + 1 + grp; t < n_spans; t += GPW) {
-    if (sr[t * SPAN] != row) break;
-    if (col_ok) {
-      const double* hp = head_part + ((u64)t * D + 4 * c);
-      acc.x += hp[0]; acc.y += hp[1]; acc.z += hp[2]; acc.w += hp[3];
+  // spans after s inside its block (at most SPANS_PER_BLOCK - 1 = one per lane)
+  const u32 t = s + 1 + lane;
+  const u32 n_in = leading_true(t < blk_end && sr[t * SPAN] == row);
+  if (col_ok)
+    for (u32 k = grp; k < n_in; k += GPW) add_partial(head_part, s + 1 + k, D, c, acc);
+  if (s + 1 + n_in == blk_end) {  // the row reaches the end of the block: go on block by block
+    for (u32 jb = s / SPANS_PER_BLOCK + 1; jb < n_blocks; jb += WAVE) {
+      const u32 jj = jb + lane;
+      const u32 nb = leading_true(jj < n_blocks && sr[jj * SPANS_PER_BLOCK * SPAN] == row);
+      if (col_ok)
+        for (u32 k = grp; k < nb; k += GPW) add_partial(block_head, jb + k, D, c, acc);
+      if (nb < WAVE) break;
     }
   }
-#pragma unroll
-  for (int off = LPR; off < WAVE; off <<= 1) {
-    acc.x += __shfl_xor(acc.x, off, WAVE);
-    acc.y += __shfl_xor(acc.y, off, WAVE);
-    acc.z += __shfl_xor(acc.z, off, WAVE);
-    acc.w += __shfl_xor(acc.w, off, WAVE);
-  }
-  if (grp == 0) finish_row(row, acc, c, col_ok, values, vhat, row_state, D, P);
+  combine_groups<LPR>(acc);
+  if (grp == 0) finish_row_loaded(row, st, acc, c, col_ok, values, vhat, row_state, D, P);
 }
 
 // Sum of the per-span counts of rows that start in the span = distinct keys of the batch.
