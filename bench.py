@@ -111,7 +111,7 @@ def main():
     max_keys = 1
     for s in range(total_steps):
         for j in range(reps):
-            b = WL.make_batch(w, s, replica=j, device=dev)
+            b = WL.make_batch(w, s % w.steps, replica=j, device=dev)   # the configuration's own step count, then repeat
             batches.append(b)
             max_keys = max(max_keys, b["keys"].numel())
     G = w.n_segments

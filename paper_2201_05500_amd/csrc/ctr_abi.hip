@@ -67,16 +67,19 @@ bool table_layout(const ctr_config* c, TableLayout* L) {
 }
 
 struct WorkLayout {
-  u32 n_rank_tiles, n_spans, n_span_blocks;
+  u32 n_bit_words, n_bit_tiles, probe_items, probe_tile, n_probe_tiles, span, n_spans, n_span_blocks;
   SortGeom geo;
-  size_t off_occ_row, off_seg_of, off_ka, off_va, off_kb, off_vb, off_hist, off_digit_total, off_tile_count,
+  size_t off_occ_row, off_seg_of, off_ka, off_va, off_kb, off_vb, off_hist, off_digit_total, off_tile_count, off_first_bits, off_pend_list, off_tile_pending,
       off_head, off_tail, off_block_head, off_span_flags, off_span_rows, total;
 };
 
 void work_layout(u32 D, u64 n_keys, WorkLayout* L) {
   const u64 n = n_keys;
-  L->n_rank_tiles = (u32)((n + RANK_TILE - 1) / RANK_TILE);
-  L->n_spans = (u32)((n + SPAN - 1) / SPAN);
+  L->n_bit_words = (u32)((n + 31) / 32);
+  L->n_bit_tiles = (L->n_bit_words + BITS_TILE_WORDS - 1) / BITS_TILE_WORDS;
+  // shorter spans for smaller batches: the span walk is sequential, so parallelism = n / span groups
+  L->span = n >= (8u << 20) ? 128u : n >= (4u << 20) ? 64u : n >= (2u << 20) ? 32u : 16u;
+  L->n_spans = (u32)((n + L->span - 1) / L->span);
   L->n_span_blocks = (L->n_spans + SPANS_PER_BLOCK - 1) / SPANS_PER_BLOCK;
   u64 tiles = (n + SORT_TILE - 1) / SORT_TILE;
   u64 chunks = std::min<u64>(std::max<u64>(tiles, 1), SORT_MAX_CHUNKS);
@@ -95,7 +98,13 @@ void work_layout(u32 D, u64 n_keys, WorkLayout* L) {
   L->off_vb = o; o += arr;
   L->off_hist = o; o += align256((size_t)RADIX * SORT_MAX_CHUNKS * sizeof(u32));
   L->off_digit_total = o; o += align256(RADIX * sizeof(u32));
-  L->off_tile_count = o; o += align256(((size_t)L->n_rank_tiles + 1) * sizeof(u32));
+  L->off_tile_count = o; o += align256(((size_t)L->n_bit_tiles + 1) * sizeof(u32));
+  L->off_first_bits = o; o += align256(((size_t)L->n_bit_words + 1) * sizeof(u32));
+  L->probe_items = n >= (4u << 20) ? PROBE_MAX_ITEMS : 1;
+  L->probe_tile = BLOCK * L->probe_items;
+  L->n_probe_tiles = (u32)((n + L->probe_tile - 1) / L->probe_tile);
+  L->off_pend_list = o; o += align256(((size_t)L->n_probe_tiles + 1) * L->probe_tile * sizeof(u32));
+  L->off_tile_pending = o; o += align256(((size_t)L->n_probe_tiles + 1) * sizeof(u32));
   L->off_head = o; o += align256((size_t)L->n_spans * D * sizeof(double));
   L->off_tail = o; o += align256((size_t)L->n_spans * D * sizeof(double));
   L->off_block_head = o; o += align256((size_t)L->n_span_blocks * D * sizeof(double));
@@ -304,27 +313,34 @@ int ctr_pull_pool(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint64
   u32* tile_count = (u32*)(b->ws + wl.off_tile_count);
   const u32 slot_mask = (u32)(t->tl.n_slots - 1);
 
+  u32* first_bits = (u32*)(b->ws + wl.off_first_bits);
+  u32* pend_list = (u32*)(b->ws + wl.off_pend_list);
+  u32* tile_pending = (u32*)(b->ws + wl.off_tile_pending);
   {
     StageTimer tm(t, CTR_STAGE_PROBE, st);
     const u64 work = std::max<u64>(n, (u64)n_segments + 1);
-    hipLaunchKernelGGL(k_probe_insert, dim3(blocks_for(work)), dim3(BLOCK), 0, st, t->hdr, t->slots, slot_mask,
-                       (const u64*)d_keys, n, d_offsets, n_segments, occ_row);
+    const u32 grid = (u32)((work + wl.probe_tile - 1) / wl.probe_tile);  // >= n_probe_tiles
+    hipLaunchKernelGGL(k_probe_insert, dim3(grid), dim3(BLOCK), 0, st, t->hdr, t->slots, slot_mask,
+                       (const u64*)d_keys, n, d_offsets, n_segments, occ_row, first_bits, pend_list, tile_pending,
+                       wl.probe_items);
   }
   {
     StageTimer tm(t, CTR_STAGE_INSERT, st);
-    if (wl.n_rank_tiles > 0)
-      hipLaunchKernelGGL(k_count_first, dim3(wl.n_rank_tiles), dim3(BLOCK), 0, st, t->hdr, t->slots, occ_row, n,
-                         tile_count);
-    hipLaunchKernelGGL(k_scan_tiles, dim3(1), dim3(BLOCK), 0, st, t->hdr, tile_count, wl.n_rank_tiles, t->R);
-    if (wl.n_rank_tiles > 0) {
-      hipLaunchKernelGGL(k_assign_rows, dim3(wl.n_rank_tiles), dim3(BLOCK), 0, st, t->hdr, t->slots, occ_row, n,
-                         tile_count, t->row_key);
-      const u32 groups_per_block = BLOCK / t->lpr;
+    if (n > 0) {
+      hipLaunchKernelGGL(k_flag_first, dim3(wl.n_probe_tiles), dim3(BLOCK), 0, st, t->hdr, t->slots, occ_row,
+                         pend_list, tile_pending, wl.probe_tile, first_bits);
+      hipLaunchKernelGGL(k_count_first, dim3(wl.n_bit_tiles), dim3(BLOCK), 0, st, t->hdr, first_bits,
+                         wl.n_bit_words, tile_count);
+    }
+    hipLaunchKernelGGL(k_scan_tiles, dim3(1), dim3(BLOCK), 0, st, t->hdr, tile_count, wl.n_bit_tiles, t->R);
+    if (n > 0) {
+      hipLaunchKernelGGL(k_assign_rows, dim3(wl.n_bit_tiles), dim3(BLOCK), 0, st, t->hdr, t->slots, occ_row,
+                         first_bits, wl.n_bit_words, tile_count, t->row_key);
       const u32 grid = std::min<u32>(blocks_for((u64)n * t->lpr), 4096);
-      (void)groups_per_block;
       LPR_DISPATCH(t->lpr, k_init_rows, grid, st, t->hdr, t->row_key, t->values, t->tl.replica_stride, t->W,
                    t->vhat, t->D, t->seed_mul, t->init_scale, t->cfg.eps);
-      hipLaunchKernelGGL(k_resolve, dim3(blocks_for(n)), dim3(BLOCK), 0, st, t->hdr, t->slots, occ_row, n);
+      hipLaunchKernelGGL(k_resolve, dim3(wl.n_probe_tiles), dim3(BLOCK), 0, st, t->hdr, t->slots, occ_row,
+                         pend_list, tile_pending, wl.probe_tile);
     }
   }
   if (n_segments > 0) {
@@ -403,18 +419,30 @@ int ctr_push_adam(ctr_table* t, uint32_t replica, ctr_batch* batch, const float*
     double* block_head = (double*)(batch->ws + wl.off_block_head);
     u32* span_flags = (u32*)(batch->ws + wl.off_span_flags);
     u32* span_rows = (u32*)(batch->ws + wl.off_span_rows);
+    const bool den = P.mode == 1u;  // kernels that fetch the shared denominator
     {
       StageTimer tm(t, CTR_STAGE_PUSH, st);
-      LPR_DISPATCH(t->lpr, k_push_span, blocks_for((u64)wl.n_spans * t->lpr), st, t->hdr, batch->sorted_rows,
-                   batch->sorted_segs, n, d_grad_pooled, vals, t->vhat, t->row_state, t->D, P, head, tail,
-                   span_flags, span_rows);
+      const u32 grid = blocks_for((u64)wl.n_spans * t->lpr);
+      if (den) {
+        LPR_DISPATCH(t->lpr, k_push_span_den, grid, st, t->hdr, batch->sorted_rows, batch->sorted_segs, n, wl.span,
+                     d_grad_pooled, vals, t->vhat, t->row_state, t->D, P, head, tail, span_flags, span_rows);
+      } else {
+        LPR_DISPATCH(t->lpr, k_push_span, grid, st, t->hdr, batch->sorted_rows, batch->sorted_segs, n, wl.span,
+                     d_grad_pooled, vals, t->vhat, t->row_state, t->D, P, head, tail, span_flags, span_rows);
+      }
     }
     {
       StageTimer tm(t, CTR_STAGE_FIXUP, st);
       LPR_DISPATCH(t->lpr, k_push_block_heads, blocks_for((u64)wl.n_span_blocks * WAVE), st, t->hdr,
-                   batch->sorted_rows, wl.n_spans, t->D, head, block_head);
-      LPR_DISPATCH(t->lpr, k_push_fixup, blocks_for((u64)wl.n_spans * WAVE), st, t->hdr, batch->sorted_rows, n,
-                   wl.n_spans, vals, t->vhat, t->row_state, t->D, P, head, tail, block_head, span_flags);
+                   batch->sorted_rows, wl.n_spans, wl.span, t->D, head, block_head);
+      const u32 fgrid = blocks_for((u64)wl.n_spans * WAVE);
+      if (den) {
+        LPR_DISPATCH(t->lpr, k_push_fixup_den, fgrid, st, t->hdr, batch->sorted_rows, n, wl.n_spans, wl.span, vals,
+                     t->vhat, t->row_state, t->D, P, head, tail, block_head, span_flags);
+      } else {
+        LPR_DISPATCH(t->lpr, k_push_fixup, fgrid, st, t->hdr, batch->sorted_rows, n, wl.n_spans, wl.span, vals,
+                     t->vhat, t->row_state, t->D, P, head, tail, block_head, span_flags);
+      }
       const u32 grid = std::min<u32>(blocks_for(wl.n_spans), 128);
       hipLaunchKernelGGL(k_count_unique, dim3(grid), dim3(BLOCK), 0, st, t->hdr, span_rows, wl.n_spans);
     }

@@ -6,14 +6,14 @@
 // branch.
 //
 // Input is the occurrence list sorted by row id: sr[i] = row, ss[i] = segment.
-// The list is cut into spans of SPAN occurrences; a group of LPR lanes (each
+// The list is cut into spans of `span` occurrences (chosen by the host from the batch size); a group of LPR lanes (each
 // lane owns 4 columns) walks one span, summing grad[ss[i], :] in binary64.  A
 // row that lies wholly inside a span is updated on the spot.  A row that
 // crosses a span boundary leaves binary64 partial sums (the span where it
 // starts writes a "tail", every later span it reaches writes a "head").  Heads
 // of runs of spans that continue one row are pre-summed per block of
 // SPANS_PER_BLOCK spans, and a last launch adds tail + heads + block sums in a
-// fixed order and updates the row.  Work per group is bounded by SPAN whatever
+// fixed order and updates the row.  Work per group is bounded by the span whatever
 // the popularity of a key, and the summation order is fixed, so results do not
 // depend on scheduling.
 #pragma once
@@ -21,10 +21,16 @@
 
 namespace ctr {
 
-constexpr u32 SPAN = 128;
+constexpr u32 MAX_SPAN = 128;  // spans are 16..128 occurrences: shorter for small batches, to keep the chip busy
 constexpr u32 SPANS_PER_BLOCK = 64;  // one wave lane per span when scanning a block
 constexpr u32 SF_HEAD = 1u, SF_TAIL = 2u;
 constexpr u32 NO_ROW = 0xFFFFFFFFu;
+#ifndef CTR_PUSH_PB
+#define CTR_PUSH_PB 2  // occurrences per batch of the span walk (2: 71 VGPRs, 7 waves/SIMD; measured best)
+#endif
+#ifndef CTR_PUSH_MIN_WAVES
+#define CTR_PUSH_MIN_WAVES 1  // waves per SIMD the span kernel is compiled for
+#endif
 
 struct AdamParams {
   double b1, omb1, b2, omb2;  // beta and (1 - beta) promoted from binary32
@@ -35,23 +41,28 @@ struct AdamParams {
 };
 
 struct RowState4 {
-  f4 x, m, v;
+  f4 x, m, v, den;  // den: the shared denominator of the row (k-step local step only)
 };
 
-__device__ __forceinline__ RowState4 load_row4(const float* __restrict__ row_base, u32 D, u32 c) {
+// DEN (compile time) == the step divides by the shared denominator (P.mode == 1): only then is it
+// fetched, so the single-table path carries no registers for it.
+template <bool DEN>
+__device__ __forceinline__ RowState4 load_row4(const float* __restrict__ values, const float* __restrict__ vhat,
+                                               u32 row, u32 D, u32 c) {
   RowState4 s;
-  const float* px = row_base + 4 * c;
+  const float* px = values + (u64)row * 3 * D + 4 * c;
   s.x = ldg4(px);
   s.m = ldg4(px + D);
   s.v = ldg4(px + 2 * D);
+  if constexpr (DEN) s.den = ldg4(vhat + (u64)row * D + 4 * c);
   return s;
 }
 
 // One Adam step on 4 columns of one row whose state is already in registers.
 // m and v are formed in binary64 from the stored binary32 values and rounded
 // once; the model step is binary32 with correctly rounded sqrt and divide.
-__device__ __forceinline__ void adam_apply4(RowState4 s, float* __restrict__ row_base,
-                                            const float* __restrict__ vhat_row, u32 D, u32 c, d4 g,
+template <bool DEN>
+__device__ __forceinline__ void adam_apply4(RowState4 s, float* __restrict__ row_base, u32 D, u32 c, d4 g,
                                             const AdamParams& P) {
   float* px = row_base + 4 * c;
   f4 x = s.x, m = s.m, v = s.v;
@@ -67,7 +78,7 @@ __device__ __forceinline__ void adam_apply4(RowState4 s, float* __restrict__ row
   stg4(px + 2 * D, v);
   if (P.mode != 2u) {
     f4 den = v;
-    if (P.mode == 1u) den = ldg4(vhat_row + 4 * c);
+    if constexpr (DEN) den = s.den;
     x.x = x.x - P.lr * (m.x / sqrtf(den.x));
     x.y = x.y - P.lr * (m.y / sqrtf(den.y));
     x.z = x.z - P.lr * (m.z / sqrtf(den.z));
@@ -76,19 +87,12 @@ __device__ __forceinline__ void adam_apply4(RowState4 s, float* __restrict__ row
   }
 }
 
+template <bool DEN>
 __device__ __forceinline__ void finish_row_loaded(u32 row, RowState4 s, d4 g, u32 c, bool col_ok,
-                                                  float* __restrict__ values, const float* __restrict__ vhat,
-                                                  u32* __restrict__ row_state, u32 D, const AdamParams& P) {
-  if (col_ok) adam_apply4(s, values + (u64)row * 3 * D, vhat ? vhat + (u64)row * D : nullptr, D, c, g, P);
+                                                  float* __restrict__ values, u32* __restrict__ row_state, u32 D,
+                                                  const AdamParams& P) {
+  if (col_ok) adam_apply4<DEN>(s, values + (u64)row * 3 * D, D, c, g, P);
   if (P.kstep && c == 0) atomicOr(&row_state[row], RS_TOUCHED | P.pend_bit);
-}
-
-__device__ __forceinline__ void finish_row(u32 row, d4 g, u32 c, bool col_ok, float* __restrict__ values,
-                                           const float* __restrict__ vhat, u32* __restrict__ row_state, u32 D,
-                                           const AdamParams& P) {
-  RowState4 s;
-  if (col_ok) s = load_row4(values + (u64)row * 3 * D, D, c);
-  finish_row_loaded(row, s, g, c, col_ok, values, vhat, row_state, D, P);
 }
 
 __device__ __forceinline__ void store_partial(double* __restrict__ part, u32 s, u32 D, u32 c, d4 a) {
@@ -105,19 +109,21 @@ __device__ __forceinline__ void add_partial(const double* __restrict__ part, u32
 // the PB gradient-row loads and the x/m/v loads of every row that ends inside
 // the batch, so that a group keeps several KB in flight instead of one
 // dependent row at a time.
-template <int LPR>
-__global__ void __launch_bounds__(BLOCK)
-k_push_span(const DevHeader* hdr, const u32* __restrict__ sr, const u32* __restrict__ ss, u32 n,
-            const float* __restrict__ grad, float* __restrict__ values, const float* __restrict__ vhat,
-            u32* __restrict__ row_state, u32 D, AdamParams P, double* __restrict__ head_part,
-            double* __restrict__ tail_part, u32* __restrict__ span_flags, u32* __restrict__ span_rows) {
+template <int LPR, bool DEN>
+__device__ __forceinline__ void push_span_body(const DevHeader* hdr, const u32* __restrict__ sr,
+                                               const u32* __restrict__ ss, u32 n, u32 span,
+                                               const float* __restrict__ grad, float* __restrict__ values,
+                                               const float* __restrict__ vhat, u32* __restrict__ row_state, u32 D,
+                                               const AdamParams& P, double* __restrict__ head_part,
+                                               double* __restrict__ tail_part, u32* __restrict__ span_flags,
+                                               u32* __restrict__ span_rows) {
   if (hdr->status) return;
-  constexpr int PB = 4;
+  constexpr int PB = CTR_PUSH_PB;
   const u32 s = (blockIdx.x * BLOCK + threadIdx.x) / LPR;
   const u32 c = threadIdx.x % LPR;
-  const u32 b = s * SPAN;
+  const u32 b = s * span;
   if (b >= n) return;
-  const u32 e = min(b + SPAN, n);
+  const u32 e = min(b + span, n);
   const bool col_ok = c * 4 < D;
 
   bool first_row_open = (b > 0) && (sr[b - 1] == sr[b]);  // the span starts inside a row begun earlier
@@ -157,7 +163,7 @@ k_push_span(const DevHeader* hdr, const u32* __restrict__ sr, const u32* __restr
     }
 #pragma unroll
     for (int i = 0; i < PB; ++i)
-      if (whole[i] && col_ok) st[i] = load_row4(values + (u64)r[i] * 3 * D, D, c);
+      if (whole[i] && col_ok) st[i] = load_row4<DEN>(values, vhat, r[i], D, c);
 #pragma unroll
     for (int i = 0; i < PB; ++i) {
       if (valid[i]) {
@@ -167,7 +173,7 @@ k_push_span(const DevHeader* hdr, const u32* __restrict__ sr, const u32* __restr
         acc.w += (double)gv[i].w;
         if (ends[i]) {
           if (whole[i]) {
-            finish_row_loaded(r[i], st[i], acc, c, col_ok, values, vhat, row_state, D, P);
+            finish_row_loaded<DEN>(r[i], st[i], acc, c, col_ok, values, row_state, D, P);
             ++started;
           } else {  // end of the row that was open on entry
             if (col_ok) store_partial(head_part, s, D, c, acc);
@@ -197,6 +203,24 @@ k_push_span(const DevHeader* hdr, const u32* __restrict__ sr, const u32* __restr
   }
 }
 
+#define CTR_PUSH_SPAN_ARGS                                                                                      \
+  const DevHeader *hdr, const u32 *__restrict__ sr, const u32 *__restrict__ ss, u32 n, u32 span,               \
+      const float *__restrict__ grad, float *__restrict__ values, const float *__restrict__ vhat,              \
+      u32 *__restrict__ row_state, u32 D, AdamParams P, double *__restrict__ head_part,                        \
+      double *__restrict__ tail_part, u32 *__restrict__ span_flags, u32 *__restrict__ span_rows
+#define CTR_PUSH_SPAN_PASS \
+  hdr, sr, ss, n, span, grad, values, vhat, row_state, D, P, head_part, tail_part, span_flags, span_rows
+
+template <int LPR>
+__global__ void __launch_bounds__(BLOCK, CTR_PUSH_MIN_WAVES) k_push_span(CTR_PUSH_SPAN_ARGS) {
+  push_span_body<LPR, false>(CTR_PUSH_SPAN_PASS);
+}
+// the k-step local step: divides by the shared denominator
+template <int LPR>
+__global__ void __launch_bounds__(BLOCK) k_push_span_den(CTR_PUSH_SPAN_ARGS) {
+  push_span_body<LPR, true>(CTR_PUSH_SPAN_PASS);
+}
+
 // Number of leading lanes (from lane 0) whose predicate holds; wave-uniform.
 __device__ __forceinline__ u32 leading_true(bool pred) {
   const u64 inv = ~__ballot(pred);
@@ -219,7 +243,7 @@ __device__ __forceinline__ void combine_groups(d4& a) {
 // block's leading spans that continue the row open at the block's start.
 template <int LPR>
 __global__ void __launch_bounds__(BLOCK)
-k_push_block_heads(const DevHeader* hdr, const u32* __restrict__ sr, u32 n_spans, u32 D,
+k_push_block_heads(const DevHeader* hdr, const u32* __restrict__ sr, u32 n_spans, u32 span, u32 D,
                    const double* __restrict__ head_part, double* __restrict__ block_head) {
   if (hdr->status) return;
   constexpr int GPW = WAVE / LPR;
@@ -229,9 +253,9 @@ k_push_block_heads(const DevHeader* hdr, const u32* __restrict__ sr, u32 n_spans
   const int lane = lane_id();
   const u32 c = lane % LPR, grp = lane / LPR;
   const bool col_ok = c * 4 < D;
-  const u32 row = sr[first * SPAN - 1];
+  const u32 row = sr[first * span - 1];
   const u32 t = first + lane;
-  const u32 n_lead = leading_true(t < n_spans && sr[t * SPAN] == row);
+  const u32 n_lead = leading_true(t < n_spans && sr[t * span] == row);
   if (n_lead == 0) return;
   d4 acc = {0.0, 0.0, 0.0, 0.0};
   if (col_ok)
@@ -243,12 +267,14 @@ k_push_block_heads(const DevHeader* hdr, const u32* __restrict__ sr, u32 n_spans
 // One wave per span that holds a tail: tail + heads of the following spans of
 // the same block + block sums of the following blocks, while they continue
 // the same row; then the row update.
-template <int LPR>
-__global__ void __launch_bounds__(BLOCK)
-k_push_fixup(const DevHeader* hdr, const u32* __restrict__ sr, u32 n, u32 n_spans, float* __restrict__ values,
-             const float* __restrict__ vhat, u32* __restrict__ row_state, u32 D, AdamParams P,
-             const double* __restrict__ head_part, const double* __restrict__ tail_part,
-             const double* __restrict__ block_head, const u32* __restrict__ span_flags) {
+template <int LPR, bool DEN>
+__device__ __forceinline__ void push_fixup_body(const DevHeader* hdr, const u32* __restrict__ sr, u32 n, u32 n_spans,
+                                                u32 span, float* __restrict__ values,
+                                                const float* __restrict__ vhat, u32* __restrict__ row_state, u32 D,
+                                                const AdamParams& P, const double* __restrict__ head_part,
+                                                const double* __restrict__ tail_part,
+                                                const double* __restrict__ block_head,
+                                                const u32* __restrict__ span_flags) {
   if (hdr->status) return;
   constexpr int GPW = WAVE / LPR;
   const u32 s = (blockIdx.x * BLOCK + threadIdx.x) / WAVE;  // wave-uniform
@@ -257,7 +283,7 @@ k_push_fixup(const DevHeader* hdr, const u32* __restrict__ sr, u32 n, u32 n_span
   const int lane = lane_id();
   const u32 c = lane % LPR, grp = lane / LPR;
   const bool col_ok = c * 4 < D;
-  const u32 row = sr[(s + 1) * SPAN - 1];  // a tail means the span is full and the list goes on
+  const u32 row = sr[(s + 1) * span - 1];  // a tail means the span is full and the list goes on
   const u32 n_blocks = (n_spans + SPANS_PER_BLOCK - 1) / SPANS_PER_BLOCK;
   const u32 blk_end = min((s / SPANS_PER_BLOCK + 1) * SPANS_PER_BLOCK, n_spans);
 
@@ -265,24 +291,41 @@ k_push_fixup(const DevHeader* hdr, const u32* __restrict__ sr, u32 n, u32 n_span
   RowState4 st;
   if (grp == 0 && col_ok) {
     add_partial(tail_part, s, D, c, acc);
-    st = load_row4(values + (u64)row * 3 * D, D, c);
+    st = load_row4<DEN>(values, vhat, row, D, c);
   }
   // spans after s inside its block (at most SPANS_PER_BLOCK - 1 = one per lane)
   const u32 t = s + 1 + lane;
-  const u32 n_in = leading_true(t < blk_end && sr[t * SPAN] == row);
+  const u32 n_in = leading_true(t < blk_end && sr[t * span] == row);
   if (col_ok)
     for (u32 k = grp; k < n_in; k += GPW) add_partial(head_part, s + 1 + k, D, c, acc);
   if (s + 1 + n_in == blk_end) {  // the row reaches the end of the block: go on block by block
     for (u32 jb = s / SPANS_PER_BLOCK + 1; jb < n_blocks; jb += WAVE) {
       const u32 jj = jb + lane;
-      const u32 nb = leading_true(jj < n_blocks && sr[jj * SPANS_PER_BLOCK * SPAN] == row);
+      const u32 nb = leading_true(jj < n_blocks && sr[jj * SPANS_PER_BLOCK * span] == row);
       if (col_ok)
         for (u32 k = grp; k < nb; k += GPW) add_partial(block_head, jb + k, D, c, acc);
       if (nb < WAVE) break;
     }
   }
   combine_groups<LPR>(acc);
-  if (grp == 0) finish_row_loaded(row, st, acc, c, col_ok, values, vhat, row_state, D, P);
+  if (grp == 0) finish_row_loaded<DEN>(row, st, acc, c, col_ok, values, row_state, D, P);
+}
+
+#define CTR_PUSH_FIXUP_ARGS                                                                                     \
+  const DevHeader *hdr, const u32 *__restrict__ sr, u32 n, u32 n_spans, u32 span, float *__restrict__ values,  \
+      const float *__restrict__ vhat, u32 *__restrict__ row_state, u32 D, AdamParams P,                        \
+      const double *__restrict__ head_part, const double *__restrict__ tail_part,                              \
+      const double *__restrict__ block_head, const u32 *__restrict__ span_flags
+#define CTR_PUSH_FIXUP_PASS \
+  hdr, sr, n, n_spans, span, values, vhat, row_state, D, P, head_part, tail_part, block_head, span_flags
+
+template <int LPR>
+__global__ void __launch_bounds__(BLOCK) k_push_fixup(CTR_PUSH_FIXUP_ARGS) {
+  push_fixup_body<LPR, false>(CTR_PUSH_FIXUP_PASS);
+}
+template <int LPR>
+__global__ void __launch_bounds__(BLOCK) k_push_fixup_den(CTR_PUSH_FIXUP_ARGS) {
+  push_fixup_body<LPR, true>(CTR_PUSH_FIXUP_PASS);
 }
 
 // Sum of the per-span counts of rows that start in the span = distinct keys of the batch.

@@ -20,9 +20,15 @@
 
 namespace ctr {
 
-constexpr int SORT_ITEMS = 16;
+#ifndef CTR_SORT_ITEMS
+#define CTR_SORT_ITEMS 16
+#endif
+constexpr int SORT_ITEMS = CTR_SORT_ITEMS;
 constexpr int SORT_TILE = BLOCK * SORT_ITEMS;  // 4096
-constexpr int SORT_MAX_CHUNKS = 1024;
+#ifndef CTR_SORT_MAX_CHUNKS
+#define CTR_SORT_MAX_CHUNKS 4096
+#endif
+constexpr int SORT_MAX_CHUNKS = CTR_SORT_MAX_CHUNKS;
 constexpr int RADIX = 256;
 
 struct SortGeom {
@@ -34,14 +40,27 @@ struct SortGeom {
 __global__ void k_sort_hist(const DevHeader* hdr, const u32* __restrict__ keys, SortGeom geo, u32 shift,
                             u32 digit_mask, u32* __restrict__ hist) {
   if (hdr->status) return;
-  __shared__ u32 h[RADIX];
-  h[threadIdx.x] = 0;
+  __shared__ u32 h[4][RADIX];  // one histogram per wave: fewer same-address LDS atomics
+#pragma unroll
+  for (int i = 0; i < 4; ++i) h[i][threadIdx.x] = 0;
   __syncthreads();
-  const u32 beg = blockIdx.x * geo.chunk_elems;
+  const u32 beg = blockIdx.x * geo.chunk_elems;  // multiple of SORT_TILE, so 16-byte aligned
   const u32 end = min(beg + geo.chunk_elems, geo.n);
-  for (u32 e = beg + threadIdx.x; e < end; e += BLOCK) atomicAdd(&h[(keys[e] >> shift) & digit_mask], 1u);
+  u32* mine = h[wave_id()];
+  for (u32 e = beg + threadIdx.x * 4; e < end; e += BLOCK * 4) {
+    if (e + 4 <= end) {
+      const uint4 k4 = *reinterpret_cast<const uint4*>(keys + e);
+      atomicAdd(&mine[(k4.x >> shift) & digit_mask], 1u);
+      atomicAdd(&mine[(k4.y >> shift) & digit_mask], 1u);
+      atomicAdd(&mine[(k4.z >> shift) & digit_mask], 1u);
+      atomicAdd(&mine[(k4.w >> shift) & digit_mask], 1u);
+    } else {
+      for (u32 j = e; j < end; ++j) atomicAdd(&mine[(keys[j] >> shift) & digit_mask], 1u);
+    }
+  }
   __syncthreads();
-  hist[threadIdx.x * geo.n_chunks + blockIdx.x] = h[threadIdx.x];
+  hist[threadIdx.x * geo.n_chunks + blockIdx.x] =
+      h[0][threadIdx.x] + h[1][threadIdx.x] + h[2][threadIdx.x] + h[3][threadIdx.x];
 }
 
 // grid = RADIX blocks; block d turns hist[d][0..n_chunks) into exclusive prefix sums.
@@ -50,19 +69,17 @@ __global__ void k_sort_scan(const DevHeader* hdr, u32* __restrict__ hist, u32 n_
   if (hdr->status) return;
   __shared__ u32 lds[4];
   u32* row = hist + blockIdx.x * n_chunks;
-  const u32 c0 = threadIdx.x * 4;  // n_chunks <= 1024 = 4 per thread
-  u32 v[4], s = 0;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    v[i] = (c0 + i < n_chunks) ? row[c0 + i] : 0u;
-    s += v[i];
-  }
+  const u32 per = (n_chunks + BLOCK - 1) / BLOCK;  // consecutive entries per thread
+  const u32 c0 = threadIdx.x * per;
+  const u32 c1 = min(c0 + per, n_chunks);
+  u32 s = 0;
+  for (u32 i = c0; i < c1; ++i) s += row[i];
   u32 total;
   u32 ex = block_exclusive_scan(s, lds, total);
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    if (c0 + i < n_chunks) row[c0 + i] = ex;
-    ex += v[i];
+  for (u32 i = c0; i < c1; ++i) {
+    const u32 v = row[i];
+    row[i] = ex;
+    ex += v;
   }
   if (threadIdx.x == 0) digit_total[blockIdx.x] = total;
 }

@@ -8,8 +8,6 @@
 
 namespace ctr {
 
-constexpr int RANK_ITEMS = 8;                     // occurrences per thread when ranking new keys
-constexpr int RANK_TILE = BLOCK * RANK_ITEMS;     // 2048 occurrences per tile
 
 // ---------------------------------------------------------------- table creation
 
@@ -29,90 +27,128 @@ __global__ void k_table_clear(DevHeader* hdr, Slot* slots, u64 n_slots, u32* row
 
 // ---------------------------------------------------------------- probe / tentative insert
 
-// One thread per key occurrence: linear probing from hash(key).  A hit on a
-// committed slot yields the row id.  A miss claims the first free slot with a
-// 64-bit compare-and-swap; the row id of such a slot is assigned later, so the
-// occurrence records the slot index instead and lowers the slot's first_p to
-// its own position (the smallest position wins: new rows are numbered in order
-// of first occurrence).  The same launch checks the CSR offsets.
-__global__ void k_probe_insert(DevHeader* hdr, Slot* slots, u32 slot_mask, const u64* __restrict__ keys,
-                               u32 n_keys, const u32* __restrict__ offsets, u32 n_seg,
-                               u32* __restrict__ occ_row) {
+// One thread per key occurrence (a block takes a tile of 256 * items consecutive ones):
+// linear probing from hash(key).  A hit on a committed slot yields the row id.  A miss claims
+// the first free slot with a 64-bit compare-and-swap; the row id of such a slot is assigned
+// later, so the occurrence records the slot index instead, lowers the slot's first_p to its
+// own position (the smallest position wins: new rows are numbered in order of first
+// occurrence) and is appended to its tile's list of pending occurrences (counted in LDS, so no
+// global atomic is shared between blocks).  The same launch checks the CSR offsets and clears
+// the bitmap of first occurrences.
+constexpr int PROBE_MAX_ITEMS = 8;  // occurrences per thread: 8 for large batches, 1 for small ones (host's choice)
+
+__global__ void __launch_bounds__(BLOCK)
+k_probe_insert(DevHeader* hdr, Slot* slots, u32 slot_mask, const u64* __restrict__ keys, u32 n_keys,
+               const u32* __restrict__ offsets, u32 n_seg, u32* __restrict__ occ_row,
+               u32* __restrict__ first_bits, u32* __restrict__ pend_list, u32* __restrict__ tile_pending,
+               u32 items) {
   if (hdr->status) return;
-  const u32 tid = blockIdx.x * BLOCK + threadIdx.x;
-  const u32 stride = gridDim.x * BLOCK;
+  __shared__ u32 n_pend;
+  if (threadIdx.x == 0) n_pend = 0;
+  __syncthreads();
+  const u32 tile0 = blockIdx.x * (BLOCK * items);
+  const int lane = lane_id();
 
-  for (u32 g = tid; g <= n_seg; g += stride) {
-    const u32 a = offsets[g];
-    bool bad = (g == 0 && a != 0);
-    if (g == n_seg)
-      bad = bad || (a != n_keys);
-    else
-      bad = bad || (offsets[g + 1] < a);
-    if (bad) atomicOr(&hdr->pull_err, ST_INVAL);
-  }
+#pragma unroll 1
+  for (u32 it = 0; it < items; ++it) {
+    const u32 p = tile0 + it * BLOCK + threadIdx.x;
+    if (p <= n_seg) {
+      const u32 a = offsets[p];
+      bool bad = (p == 0 && a != 0);
+      if (p == n_seg)
+        bad = bad || (a != n_keys);
+      else
+        bad = bad || (offsets[p + 1] < a);
+      if (bad) atomicOr(&hdr->pull_err, ST_INVAL);
+    }
 
-  for (u32 p = tid; p < n_keys; p += stride) {
-    const u64 key = keys[p];
-    if (key == KEY_EMPTY) {
-      atomicOr(&hdr->pull_err, ST_BADKEY);
-      occ_row[p] = OCC_INVALID;
-      continue;
-    }
-    u32 h = (u32)hash_key(key) & slot_mask;
-    bool found = false;
-    for (u32 probe = 0; probe <= slot_mask; ++probe) {
-      // A plain (cacheable) load: slots only ever go from free to taken inside this launch, so
-      // the worst a stale copy can show is "free", and the compare-and-swap below then returns
-      // the key that is really there.
-      u64 k = slots[h].key;
-      if (k == KEY_EMPTY) {
-        const u64 old = atomicCAS(&slots[h].key, KEY_EMPTY, key);
-        k = (old == KEY_EMPTY) ? key : old;
+    bool pending = false;
+    if (p < n_keys) {
+      if ((p & 31u) == 0) first_bits[p >> 5] = 0;
+      const u64 key = keys[p];
+      u32 out = OCC_INVALID;
+      if (key == KEY_EMPTY) {
+        atomicOr(&hdr->pull_err, ST_BADKEY);
+      } else {
+        u32 h = (u32)hash_key(key) & slot_mask;
+        bool found = false;
+        for (u32 probe = 0; probe <= slot_mask; ++probe) {
+          // A plain (cacheable) load: slots only ever go from free to taken inside this launch,
+          // so the worst a stale copy can show is "free", and the compare-and-swap below then
+          // returns the key that is really there.
+          u64 k = slots[h].key;
+          if (k == KEY_EMPTY) {
+            const u64 old = atomicCAS(&slots[h].key, KEY_EMPTY, key);
+            k = (old == KEY_EMPTY) ? key : old;
+          }
+          if (k == key) {
+            found = true;
+            break;
+          }
+          h = (h + 1) & slot_mask;
+          if ((probe & 63u) == 63u && (ld_relaxed(&hdr->pull_err) & ST_FULL)) break;
+        }
+        if (!found) {  // every slot holds another key: more distinct keys than slots
+          atomicOr(&hdr->pull_err, ST_FULL);
+        } else {
+          const u32 r = slots[h].row;  // rows are assigned between launches, never inside this one
+          if (r == ROW_PENDING) {
+            // a popular new key has millions of occurrences: only those that can still lower
+            // the minimum go to the atomic unit, the rest see a smaller value and pass
+            if (ld_relaxed(&slots[h].first_p) > p) atomicMin(&slots[h].first_p, p);
+            out = OCC_PEND_FLAG | h;
+            pending = true;
+          } else {
+            out = r;
+          }
+        }
       }
-      if (k == key) {
-        found = true;
-        break;
-      }
-      h = (h + 1) & slot_mask;
-      if ((probe & 63u) == 63u && (ld_relaxed(&hdr->pull_err) & ST_FULL)) break;
+      occ_row[p] = out;
     }
-    if (!found) {  // every slot holds another key: more distinct keys than slots
-      atomicOr(&hdr->pull_err, ST_FULL);
-      occ_row[p] = OCC_INVALID;
-      continue;
-    }
-    const u32 r = slots[h].row;  // rows are assigned between launches, never inside this one
-    if (r == ROW_PENDING) {
-      // a popular new key has millions of occurrences: only those that can still lower the
-      // minimum go to the atomic unit, the rest see a smaller value and pass
-      if (ld_relaxed(&slots[h].first_p) > p) atomicMin(&slots[h].first_p, p);
-      occ_row[p] = OCC_PEND_FLAG | h;
-    } else {
-      occ_row[p] = r;
+
+    // every lane of the wave is here again: one LDS atomic per wave reserves list entries
+    const u64 bal = __ballot(pending);
+    if (bal) {
+      const int leader = __ffsll((long long)bal) - 1;
+      u32 base = 0;
+      if (lane == leader) base = atomicAdd(&n_pend, (u32)__popcll(bal));
+      base = __shfl(base, leader, WAVE);
+      if (pending) pend_list[tile0 + base + (u32)__popcll(bal & ((1ull << lane) - 1ull))] = p;
     }
   }
+  __syncthreads();
+  if (threadIdx.x == 0 && tile0 < n_keys) tile_pending[blockIdx.x] = n_pend;  // blocks past the keys only check offsets
 }
 
 // ---------------------------------------------------------------- ranking of new keys
 
-__device__ __forceinline__ bool is_first_occurrence(const Slot* slots, u32 occ, u32 p) {
-  if (occ == OCC_INVALID || !(occ & OCC_PEND_FLAG)) return false;
-  return slots[occ & ~OCC_PEND_FLAG].first_p == p;
+constexpr int BITS_WORDS_PER_THREAD = 8;
+constexpr int BITS_TILE_WORDS = BLOCK * BITS_WORDS_PER_THREAD;  // 2048 words = 65536 occurrences per tile
+
+// Over the pending occurrences (one block per probe tile): marks those that are the first
+// occurrence of their (new) key.
+__global__ void k_flag_first(const DevHeader* hdr, const Slot* __restrict__ slots, const u32* __restrict__ occ_row,
+                             const u32* __restrict__ pend_list, const u32* __restrict__ tile_pending,
+                             u32 probe_tile, u32* __restrict__ first_bits) {
+  if (hdr->status) return;
+  const u32 cnt = tile_pending[blockIdx.x];
+  for (u32 i = threadIdx.x; i < cnt; i += BLOCK) {
+    const u32 p = pend_list[blockIdx.x * probe_tile + i];
+    const u32 h = occ_row[p] & ~OCC_PEND_FLAG;
+    if (slots[h].first_p == p) atomicOr(&first_bits[p >> 5], 1u << (p & 31u));
+  }
 }
 
-// Counts, per tile of RANK_TILE occurrences, those that are the first occurrence of a new key.
-__global__ void k_count_first(const DevHeader* hdr, const Slot* __restrict__ slots,
-                              const u32* __restrict__ occ_row, u32 n_keys, u32* __restrict__ tile_count) {
+// Number of first occurrences per tile of the bitmap.
+__global__ void k_count_first(const DevHeader* hdr, const u32* __restrict__ first_bits, u32 n_words,
+                              u32* __restrict__ tile_count) {
   if (hdr->status) return;
   __shared__ u32 lds[4];
-  const u32 base = blockIdx.x * RANK_TILE + threadIdx.x * RANK_ITEMS;
+  const u32 w0 = blockIdx.x * BITS_TILE_WORDS + threadIdx.x * BITS_WORDS_PER_THREAD;
   u32 cnt = 0;
 #pragma unroll
-  for (int i = 0; i < RANK_ITEMS; ++i) {
-    const u32 p = base + i;
-    if (p < n_keys) cnt += is_first_occurrence(slots, occ_row[p], p) ? 1u : 0u;
-  }
+  for (int i = 0; i < BITS_WORDS_PER_THREAD; ++i)
+    if (w0 + i < n_words) cnt += (u32)__popc(first_bits[w0 + i]);
   u32 total;
   block_exclusive_scan(cnt, lds, total);
   if (threadIdx.x == 0) tile_count[blockIdx.x] = total;
@@ -156,41 +192,40 @@ __global__ void k_scan_tiles(DevHeader* hdr, u32* __restrict__ tile_count, u32 n
 // Gives the first occurrence of every new key its row id (tile base + rank in
 // occurrence order), or, when the pull failed, frees the slot again: clearing
 // exactly the slots claimed by this pull restores the index as it was.
-__global__ void k_assign_rows(const DevHeader* hdr, Slot* slots, const u32* __restrict__ occ_row, u32 n_keys,
-                              const u32* __restrict__ tile_base, u64* __restrict__ row_key) {
+__global__ void k_assign_rows(const DevHeader* hdr, Slot* slots, const u32* __restrict__ occ_row,
+                              const u32* __restrict__ first_bits, u32 n_words, const u32* __restrict__ tile_base,
+                              u64* __restrict__ row_key) {
   const u32 rollback = hdr->rollback;
   if (hdr->status && !rollback) return;
   __shared__ u32 lds[4];
-  const u32 base = blockIdx.x * RANK_TILE + threadIdx.x * RANK_ITEMS;
-  u32 slot_of[RANK_ITEMS];
+  const u32 w0 = blockIdx.x * BITS_TILE_WORDS + threadIdx.x * BITS_WORDS_PER_THREAD;
+  u32 bits[BITS_WORDS_PER_THREAD];
   u32 cnt = 0;
 #pragma unroll
-  for (int i = 0; i < RANK_ITEMS; ++i) {
-    const u32 p = base + i;
-    slot_of[i] = 0xFFFFFFFFu;
-    if (p < n_keys) {
-      const u32 occ = occ_row[p];
-      if (is_first_occurrence(slots, occ, p)) {
-        slot_of[i] = occ & ~OCC_PEND_FLAG;
-        ++cnt;
-      }
-    }
+  for (int i = 0; i < BITS_WORDS_PER_THREAD; ++i) {
+    bits[i] = (w0 + i < n_words) ? first_bits[w0 + i] : 0u;
+    cnt += (u32)__popc(bits[i]);
   }
   u32 total;
   u32 rank = block_exclusive_scan(cnt, lds, total);
   if (total == 0) return;
   const u32 row0 = hdr->n_rows_base + tile_base[blockIdx.x];
 #pragma unroll
-  for (int i = 0; i < RANK_ITEMS; ++i) {
-    if (slot_of[i] == 0xFFFFFFFFu) continue;
-    Slot* s = &slots[slot_of[i]];
-    if (rollback) {
-      s->first_p = 0xFFFFFFFFu;
-      s->key = KEY_EMPTY;
-    } else {
-      const u32 row = row0 + rank++;
-      s->row = row;
-      row_key[row] = s->key;
+  for (int i = 0; i < BITS_WORDS_PER_THREAD; ++i) {
+    u32 b = bits[i];
+    while (b) {
+      const u32 bit = (u32)__ffs((int)b) - 1u;
+      b &= b - 1u;
+      const u32 p = (w0 + i) * 32u + bit;
+      Slot* s = &slots[occ_row[p] & ~OCC_PEND_FLAG];
+      if (rollback) {
+        s->first_p = 0xFFFFFFFFu;
+        s->key = KEY_EMPTY;
+      } else {
+        const u32 row = row0 + rank++;
+        s->row = row;
+        row_key[row] = s->key;
+      }
     }
   }
 }
@@ -226,14 +261,17 @@ __global__ void k_init_rows(const DevHeader* hdr, const u64* __restrict__ row_ke
   }
 }
 
-// Replaces "slot index, row pending" entries by the row id now that rows are assigned.
+// Replaces "slot index, row pending" entries by the row id now that rows are assigned
+// (one block per probe tile, over its list of pending occurrences).
 __global__ void k_resolve(const DevHeader* hdr, const Slot* __restrict__ slots, u32* __restrict__ occ_row,
-                          u32 n_keys) {
+                          const u32* __restrict__ pend_list, const u32* __restrict__ tile_pending,
+                          u32 probe_tile) {
   if (hdr->status) return;
-  const u32 p = blockIdx.x * BLOCK + threadIdx.x;
-  if (p >= n_keys) return;
-  const u32 occ = occ_row[p];
-  if (occ & OCC_PEND_FLAG) occ_row[p] = slots[occ & ~OCC_PEND_FLAG].row;
+  const u32 cnt = tile_pending[blockIdx.x];
+  for (u32 i = threadIdx.x; i < cnt; i += BLOCK) {
+    const u32 p = pend_list[blockIdx.x * probe_tile + i];
+    occ_row[p] = slots[occ_row[p] & ~OCC_PEND_FLAG].row;
+  }
 }
 
 // ---------------------------------------------------------------- gather + per-segment sum
