@@ -20,6 +20,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 
+# HBM traffic of the dominant kernel per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this script (profiles/large_step_kernels.txt), each counter scaled by what it reads for a 1 GiB
+# device copy in the same run (fetch x2.0, write x1.0).  Only known for the workload it was taken on.
+MEASURED_TRAFFIC_BYTES = {("large", "k_push_span"): 7798648 * 1024 * 2.0 + 4455159 * 1024 * 1.0}
+
 
 def algorithmic_bytes_step(L, G, U, n_new, D, kstep):
     """Bytes one step must move (no sort scratch, no re-reads of hot rows)."""
@@ -216,7 +221,7 @@ def main():
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBPS,
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, {"push": "k_push_span", "pool": "k_pool"}[dominant])),
         },
     }
     if not args.no_cpu_baseline:
