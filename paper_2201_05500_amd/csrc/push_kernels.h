@@ -58,9 +58,14 @@ __device__ __forceinline__ RowState4 load_row4(const float* __restrict__ values,
   return s;
 }
 
+__device__ __forceinline__ double rsqrt_refined(float a) {
+  const double y = (double)rsqrtf(a), d = (double)a;
+  return y * (1.5 - 0.5 * d * y * y);
+}
+
 // One Adam step on 4 columns of one row whose state is already in registers.
 // m and v are formed in binary64 from the stored binary32 values and rounded
-// once; the model step is binary32 with correctly rounded sqrt and divide.
+// once, and so is the model step.
 template <bool DEN>
 __device__ __forceinline__ void adam_apply4(RowState4 s, float* __restrict__ row_base, u32 D, u32 c, d4 g,
                                             const AdamParams& P) {
@@ -79,10 +84,15 @@ __device__ __forceinline__ void adam_apply4(RowState4 s, float* __restrict__ row
   if (P.mode != 2u) {
     f4 den = v;
     if constexpr (DEN) den = s.den;
-    x.x = x.x - P.lr * (m.x / sqrtf(den.x));
-    x.y = x.y - P.lr * (m.y / sqrtf(den.y));
-    x.z = x.z - P.lr * (m.z / sqrtf(den.z));
-    x.w = x.w - P.lr * (m.w / sqrtf(den.w));
+    // binary64 like the moments: a step can be orders of magnitude larger than the parameter it
+    // lands on (shared denominator still at eps), and a binary32 quotient would leave an error
+    // proportional to the step, not to the result.  1/sqrt(den): binary32 estimate refined by one
+    // Newton step in binary64 (relative error ~1e-13), cheaper than a binary64 sqrt and divide.
+    const double lr = (double)P.lr;
+    x.x = (float)((double)x.x - lr * (double)m.x * rsqrt_refined(den.x));
+    x.y = (float)((double)x.y - lr * (double)m.y * rsqrt_refined(den.y));
+    x.z = (float)((double)x.z - lr * (double)m.z * rsqrt_refined(den.z));
+    x.w = (float)((double)x.w - lr * (double)m.w * rsqrt_refined(den.w));
     stg4(px, x);
   }
 }
@@ -366,18 +376,18 @@ k_merge(const DevHeader* hdr, float* __restrict__ values, u64 replica_stride, u3
       f4 vh;
       vh.x = (float)(vs.x / w); vh.y = (float)(vs.y / w); vh.z = (float)(vs.z / w); vh.w = (float)(vs.w / w);
       stg4(vhat + (u64)row * D + 4 * c, vh);
-      f4 den;
-      den.x = sqrtf(vh.x); den.y = sqrtf(vh.y); den.z = sqrtf(vh.z); den.w = sqrtf(vh.w);
+      const d4 rs = {rsqrt_refined(vh.x), rsqrt_refined(vh.y), rsqrt_refined(vh.z), rsqrt_refined(vh.w)};
+      const double lrd = (double)lr;
       d4 xs = {0.0, 0.0, 0.0, 0.0};
       for (u32 j = 0; j < W; ++j) {
         const f4 x = ldg4(base + j * replica_stride);
         d4 y = {(double)x.x, (double)x.y, (double)x.z, (double)x.w};
         if (st & (1u << j)) {
           const f4 m = ldg4(base + j * replica_stride + D);
-          y.x -= (double)(lr * (m.x / den.x));
-          y.y -= (double)(lr * (m.y / den.y));
-          y.z -= (double)(lr * (m.z / den.z));
-          y.w -= (double)(lr * (m.w / den.w));
+          y.x -= lrd * (double)m.x * rs.x;
+          y.y -= lrd * (double)m.y * rs.y;
+          y.z -= lrd * (double)m.z * rs.z;
+          y.w -= lrd * (double)m.w * rs.w;
         }
         xs.x += y.x; xs.y += y.y; xs.z += y.z; xs.w += y.w;
       }

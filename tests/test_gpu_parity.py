@@ -262,3 +262,40 @@ def test_same_calls_give_bit_identical_results():
             assert np.array_equal(x, y)
     for f in ("keys", "x", "m", "v"):
         assert np.array_equal(outs[0][1][f], outs[1][1][f]), f
+
+
+def test_random_small_cases_differential():
+    """Seeded random shapes: dims, replicas, k, ragged segments with empties, heavy duplication, table
+    sizes that are not powers of two, several steps and merges - every state compared with the oracle."""
+    rng = np.random.default_rng(2024)
+    for case in range(24):
+        D = int(rng.choice([4, 8, 16, 20, 32, 64, 96]))
+        W = int(rng.choice([1, 1, 2, 3, 5]))
+        kstep = W > 1 or bool(rng.integers(0, 2))
+        k = int(rng.integers(1, 4))
+        R = int(rng.integers(50, 3000))
+        universe = int(rng.integers(1, R))           # never more distinct keys than rows
+        beta1 = float(rng.choice([0.0, 0.9]))
+        gt, ot = _tables(R, D, W=W, kstep=kstep, seed=case)
+        gt.close()
+        from paper_2201_05500_amd.binding import CtrTable
+        gt = CtrTable(R, D, n_replicas=W, kstep=kstep, init_seed=case, beta1=beta1, lr=3e-3)
+        ot = O.OracleTable(R, D, n_replicas=W, kstep=kstep, init_seed=case, beta1=beta1, lr=3e-3)
+        t = 0
+        for step in range(int(rng.integers(2, 6))):
+            t += 1
+            mode = O.STEP_MERGE_PENDING if (kstep and t % k == 0) else O.STEP_LOCAL
+            for j in range(W):
+                G = int(rng.integers(1, 400))
+                counts = rng.poisson(rng.uniform(0.3, 6.0), G)
+                off = np.concatenate([[0], np.cumsum(counts)]).astype(np.uint32)
+                ranks = np.minimum((universe ** rng.random(int(off[-1]))).astype(np.uint64), np.uint64(universe - 1))
+                keys = (ranks + np.uint64(1)) * np.uint64(0x9E3779B97F4A7C15)
+                bn = {"keys": keys, "offsets": off,
+                      "grad": (rng.standard_normal((G, D)) * rng.choice([1e-3, 1.0, 30.0])).astype(np.float32)}
+                what = "case %d step %d replica %d (D=%d W=%d k=%d R=%d)" % (case, step, j, D, W, k, R)
+                run_step(gt, ot, to_device(bn), bn, replica=j, mode=mode, what=what)
+            if mode == O.STEP_MERGE_PENDING:
+                assert gt.kstep_merge() == 0 and ot.kstep_merge() == 0
+            compare_tables(gt, ot, what="case %d after step %d" % (case, step))
+        gt.close()
