@@ -26,7 +26,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 MEASURED_TRAFFIC_BYTES = {("large", "k_push_span"): 7798648 * 1024 * 2.0 + 4455159 * 1024 * 1.0}
 
 
-def algorithmic_bytes_step(L, G, U, n_new, D, kstep):
+def algorithmic_bytes_step(L, G, U, n_new, D, kstep, n_state=3):
     """Bytes one step must move (no sort scratch, no re-reads of hot rows)."""
     b = 8 * L                   # keys read
     b += 2 * 4 * (G + 1)        # offsets read by pull and by push-side bookkeeping
@@ -36,15 +36,15 @@ def algorithmic_bytes_step(L, G, U, n_new, D, kstep):
     b += 4 * D * U              # compulsory row reads for pooling
     b += 4 * D * G              # pooled write
     b += 4 * D * G              # pooled-gradient read
-    b += 6 * 4 * D * U          # Adam: read + write x, m, v
+    b += 2 * n_state * 4 * D * U  # optimizer: read + write x, m, v (x, G for AdaGrad)
     if kstep:
         b += 4 * D * U          # shared denominator read
     return b
 
 
-def algorithmic_bytes_push_kernel(L, G, U, D, kstep):
-    """The push kernel's share: occurrence map read, pooled-gradient read, Adam read + write."""
-    return 4 * L + 4 * D * G + 6 * 4 * D * U + (4 * D * U if kstep else 0)
+def algorithmic_bytes_push_kernel(L, G, U, D, kstep, n_state=3):
+    """The push kernel's share: occurrence map read, pooled-gradient read, row state read + write."""
+    return 4 * L + 4 * D * G + 2 * n_state * 4 * D * U + (4 * D * U if kstep else 0)
 
 
 def algorithmic_bytes_pool_kernel(L, G, U, D):
@@ -83,6 +83,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="large")
+    ap.add_argument("--variant", default="alg2", choices=["alg2", "adagrad", "prose", "kingma"],
+                    help="row update: Algorithm 2's Adam (default), AdaGrad, the prose reading of the merge, "
+                         "bias-corrected Adam")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy, so that a counter run has a kernel of known traffic")
@@ -102,12 +105,18 @@ def main():
     dev = "cuda:0"
     w = WL.WORKLOADS[args.workload]
     kstep = w.k_step > 0
+    if (args.variant == "prose") != kstep and args.variant != "alg2":
+        print("bench.py: --variant prose needs the kstep workload, adagrad/kingma a single-table one", file=sys.stderr)
+        sys.exit(2)
+    n_state = 2 if args.variant == "adagrad" else 3
+    shared_den = kstep and args.variant == "alg2"
     K, Wm = args.steps, args.warmup
     total_steps = K + Wm
 
     table = CtrTable(w.capacity_rows, w.dim, n_replicas=w.n_replicas, lr=w.lr, beta1=w.beta1,
                      beta2=w.beta2, eps=w.eps, init_seed=1, init_std=w.init_std, kstep=kstep,
-                     load_factor=w.load_factor, device=dev)
+                     load_factor=w.load_factor, device=dev, adagrad=args.variant == "adagrad",
+                     prose=args.variant == "prose", bias_correction=args.variant == "kingma")
 
     # every input of every step resident in HBM before timing; for the k-step workload a "step"
     # is one local step of every replica (plus the merge on every k-th)
@@ -132,7 +141,8 @@ def main():
 
     def run_step(s):
         mode = CTR_STEP_LOCAL
-        if kstep and (s + 1) % w.k_step == 0:
+        merge_now = kstep and (s + 1) % w.k_step == 0
+        if merge_now and args.variant == "alg2":
             mode = CTR_STEP_MERGE_PENDING
         for j in range(reps):
             b = batches[s * reps + j]
@@ -142,7 +152,7 @@ def main():
             st = table.push_adam(j, h, b["grad"], mode)
             if st != CTR_OK:
                 raise RuntimeError("ctr_push_adam: %d" % st)
-        if mode == CTR_STEP_MERGE_PENDING:
+        if merge_now:
             st = table.kstep_merge()
             if st != CTR_OK:
                 raise RuntimeError("ctr_kstep_merge: %d" % st)
@@ -178,11 +188,11 @@ def main():
     n_new_mean = (rows_after - rows_before) / (K * reps)
 
     D = w.dim
-    step_bytes = algorithmic_bytes_step(L_mean, G, U_mean, n_new_mean, D, kstep)
+    step_bytes = algorithmic_bytes_step(L_mean, G, U_mean, n_new_mean, D, shared_den, n_state)
     ms_step = elapsed * 1e3 / K
     stage_ms = {n: (ms / c if c else 0.0) for n, (ms, c) in stages.items()}
     kernel_bytes = {
-        "push": algorithmic_bytes_push_kernel(L_mean, G, U_mean, D, kstep),
+        "push": algorithmic_bytes_push_kernel(L_mean, G, U_mean, D, shared_den, n_state),
         "pool": algorithmic_bytes_pool_kernel(L_mean, G, U_mean, D),
     }
     dominant = max(kernel_bytes, key=lambda n: stage_ms[n])
@@ -204,7 +214,8 @@ def main():
         "config": {
             "workload": "%s: R=%d rows, dim %d, batch %d x %d slots, Zipf s=%g over %d ranks, %d-bit keys%s" % (
                 w.name, w.capacity_rows, w.dim, w.batch, w.slots, w.zipf_s, w.zipf_universe, w.key_bits,
-                (", W=%d replicas, k=%d" % (w.n_replicas, w.k_step)) if kstep else ""),
+                (", W=%d replicas, k=%d" % (w.n_replicas, w.k_step)) if kstep else "") + (
+                "" if args.variant == "alg2" else ", row update: " + args.variant),
             "keys_per_batch": L_mean,
             "distinct_keys_per_batch": U_mean,
             "new_rows_per_batch": n_new_mean,
@@ -221,7 +232,8 @@ def main():
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBPS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, {"push": "k_push_span", "pool": "k_pool"}[dominant])),
+            "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, {"push": "k_push_span", "pool": "k_pool"}[dominant]))
+            if args.variant == "alg2" else None,
         },
     }
     if not args.no_cpu_baseline:

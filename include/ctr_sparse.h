@@ -62,8 +62,22 @@ typedef enum {
   CTR_E_DEVICE = 6  /* a HIP runtime call failed */
 } ctr_status;
 
-/* flags */
+/* flags (ctr_config.flags) */
 #define CTR_F_KSTEP 1u /* k-step Adam of Algorithm 2: shared frozen denominator + merge */
+/* Rows hold [x | G] and are updated by AdaGrad, the optimizer the paper uses for its sparse
+ * parameters (Section 5, to save the first moment): G += g^2; x -= lr g / sqrt(G), with G = eps
+ * in a new row (eps placed as in Algorithm 2's "Initialize").  Single table only (no other flag,
+ * n_replicas = 1). */
+#define CTR_F_ADAGRAD 2u
+/* With CTR_F_KSTEP: the reading of Section 4's prose instead of the printed Algorithm 2 - every
+ * step, the k-th included, is a local step x -= lr m / sqrt(own v) (CTR_STEP_MERGE_PENDING is
+ * rejected), and the merge sets every replica's x to the mean of the x_j and every v_j to the
+ * mean of the v_j.  There is no shared-denominator array. */
+#define CTR_F_KSTEP_PROSE 4u
+/* The Adam the paper cites (Kingma & Ba) instead of Algorithm 2's form: m = v = 0 in a new row,
+ * x -= lr (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps), t = number of ctr_push_adam calls
+ * accepted by this table so far (rows not in a batch are untouched).  Single table only. */
+#define CTR_F_BIAS_CORRECTION 8u
 
 /* step modes for ctr_push_adam */
 #define CTR_STEP_LOCAL 0u         /* t mod k != 0 (or single-table mode): moments and model */
@@ -74,7 +88,7 @@ typedef struct {
   uint64_t capacity_rows; /* R: value rows; the key index has pow2ceil(R / load_factor) slots */
   uint32_t dim;           /* D: floats per embedding row */
   float load_factor;      /* in (0, 0.9]; 0 selects 0.5 */
-  uint32_t n_replicas;    /* W >= 1 model replicas sharing one key->row index */
+  uint32_t n_replicas;    /* W >= 1 model replicas sharing one key->row index (W > 1 needs CTR_F_KSTEP) */
   float lr, beta1, beta2, eps; /* alpha, beta_1, beta_2, epsilon of Algorithm 2 */
   uint64_t init_seed;     /* seed of the deterministic row initialiser */
   float init_std;         /* spread of a new row's parameters */
@@ -131,7 +145,9 @@ int ctr_pull_pool(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint64
  *   m = b1 m + (1 - b1) g;  v = b2 v + (1 - b2) g^2;  x -= lr m / sqrt(den)
  * with den = v (single-table mode) or the shared denominator frozen at the
  * last merge (CTR_F_KSTEP, CTR_STEP_LOCAL); with CTR_STEP_MERGE_PENDING only
- * m and v change.  Rows not in the batch are untouched.
+ * m and v change.  CTR_F_ADAGRAD, CTR_F_KSTEP_PROSE and CTR_F_BIAS_CORRECTION
+ * select the row updates described at their definitions.  Rows not in the
+ * batch are untouched.
  *   d_grad_pooled[n_seg * D]  device, in
  * `batch` must be the live batch of the last pull on `t` with the same
  * replica; it is consumed (freed) whatever the outcome, unless CTR_E_INVAL.
@@ -143,7 +159,8 @@ int ctr_push_adam(ctr_table* t, uint32_t replica, ctr_batch* batch, const float*
  * by any replica since the previous merge:
  *   vhat = (1/W) sum_j v_j;
  *   x_i  = (1/W) sum_j (x_j - [row pending in j] lr m_j / sqrt(vhat))   for all i.
- * m_j and v_j stay local.  Needs CTR_F_KSTEP.  Errors: CTR_E_INVAL. */
+ * m_j and v_j stay local.  With CTR_F_KSTEP_PROSE instead: x_i = (1/W) sum_j x_j
+ * and v_i = (1/W) sum_j v_j for all i.  Needs CTR_F_KSTEP.  Errors: CTR_E_INVAL. */
 int ctr_kstep_merge(ctr_table* t, void* hip_stream);
 
 /* ---- parity / debug surface (synchronising, not part of the timed path) ---- */
@@ -152,8 +169,10 @@ int ctr_kstep_merge(ctr_table* t, void* hip_stream);
 int ctr_table_size(ctr_table* t, uint64_t* n_rows, void* hip_stream);
 
 /* Table contents in row order into HOST buffers (any may be NULL):
- * h_keys[n_rows], h_x/h_m/h_v[n_rows * D] of one replica, h_vhat[n_rows * D]
- * (CTR_F_KSTEP only, else CTR_E_INVAL if requested). */
+ * h_keys[n_rows], h_x/h_m/h_v[n_rows * D] of one replica (h_v is the AdaGrad
+ * accumulator under CTR_F_ADAGRAD, where asking for h_m is CTR_E_INVAL),
+ * h_vhat[n_rows * D] (Algorithm 2's shared denominator: CTR_F_KSTEP without
+ * CTR_F_KSTEP_PROSE only, else CTR_E_INVAL if requested). */
 int ctr_table_export(ctr_table* t, uint32_t replica, uint64_t* h_keys, float* h_x, float* h_m,
                      float* h_v, float* h_vhat, void* hip_stream);
 

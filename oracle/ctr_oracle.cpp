@@ -44,6 +44,15 @@
 //     and a replica that did not touch a row on the merge step contributes its
 //     x with no step term.
 //
+// Variants (selected at creation; each has its own pins):
+//   * AdaGrad, the optimizer the paper uses for sparse parameters (Section 5): rows hold x and an
+//     accumulator G; G_0 = eps (placed as Algorithm 2 places it), G += g^2, x -= lr g / sqrt(G).
+//   * the prose reading of Section 4 ("standard Adam updates are applied" locally, weights and v
+//     averaged every k steps): every step divides by the worker's own v; the merge sets every x
+//     to the mean of the x_j and every v_j to the mean of the v_j.
+//   * the Adam the paper cites (Kingma & Ba): m_0 = v_0 = 0, bias-corrected moments, eps added to
+//     the root, t = number of pushes accepted so far.
+//
 // Pins (tests/test_oracle_*.py): closed forms of the Adam recurrences for a
 // constant gradient, beta1 = 0, duplicate keys == summed gradient, k = 1 with
 // one replica == single-table Adam bit for bit, the averaged-iterate and
@@ -66,6 +75,7 @@ namespace {
 enum { ORC_OK = 0, ORC_E_INVAL = 1, ORC_E_NOMEM = 2, ORC_E_FULL = 3, ORC_E_BADKEY = 4,
        ORC_E_STATE = 5 };
 enum { STEP_LOCAL = 0, STEP_MERGE_PENDING = 1 };
+enum { VAR_ALG2 = 0, VAR_ADAGRAD = 1, VAR_PROSE = 2, VAR_KINGMA = 3 };
 
 const uint64_t SENTINEL = ~0ULL;
 
@@ -76,6 +86,8 @@ struct Table {
   uint64_t seed = 0;
   float init_std = 0;
   int kstep = 0;
+  int variant = VAR_ALG2;
+  uint64_t n_push = 0;  // pushes accepted so far (step count of the bias-corrected form)
   uint64_t n_rows = 0;
   std::unordered_map<uint64_t, uint32_t> row_of;
   std::vector<uint64_t> key_of_row;
@@ -114,17 +126,21 @@ inline float init_scale(float init_std) { return (float)((double)init_std / 3783
 extern "C" {
 
 void* orc_create(uint64_t R, uint32_t D, uint32_t W, float lr, float b1, float b2, float eps,
-                 uint64_t seed, float init_std, int kstep) {
+                 uint64_t seed, float init_std, int kstep, int variant) {
   if (R == 0 || D == 0 || W == 0) return nullptr;
+  if (variant < VAR_ALG2 || variant > VAR_KINGMA) return nullptr;
+  if (variant == VAR_PROSE && !kstep) return nullptr;
+  if ((variant == VAR_ADAGRAD || variant == VAR_KINGMA) && (kstep || W != 1)) return nullptr;
+  if (!kstep && W != 1) return nullptr;
   Table* t = new Table();
   t->R = R; t->D = D; t->W = W; t->lr = lr; t->b1 = b1; t->b2 = b2; t->eps = eps;
-  t->seed = seed; t->init_std = init_std; t->kstep = kstep;
+  t->seed = seed; t->init_std = init_std; t->kstep = kstep; t->variant = variant;
   t->x.resize(W); t->m.resize(W); t->v.resize(W); t->pending.resize(W);
   // address space only; pages are committed as rows are created
   for (uint32_t j = 0; j < W; ++j) {
     t->x[j].reserve((size_t)R * D); t->m[j].reserve((size_t)R * D); t->v[j].reserve((size_t)R * D);
   }
-  if (kstep) t->vhat.reserve((size_t)R * D);
+  if (kstep && variant != VAR_PROSE) t->vhat.reserve((size_t)R * D);
   return t;
 }
 
@@ -184,11 +200,11 @@ int orc_pull_pool(void* h, uint32_t replica, const uint64_t* keys, uint64_t n_ke
       for (uint32_t d = 0; d < D; ++d) {
         t->x[j].push_back(init_value(t->seed, key, d, scale));
         t->m[j].push_back(0.0f);
-        t->v[j].push_back(t->eps);
+        t->v[j].push_back(t->variant == VAR_KINGMA ? 0.0f : t->eps);
       }
       t->pending[j].push_back(0);
     }
-    if (t->kstep)
+    if (t->kstep && t->variant != VAR_PROSE)
       for (uint32_t d = 0; d < D; ++d) t->vhat.push_back(t->eps);
     t->touched.push_back(0);
   }
@@ -224,9 +240,10 @@ int orc_push_adam(void* h, uint32_t replica, const float* grad_pooled, uint32_t 
   const uint32_t D = t->D;
   if (replica >= t->W) return ORC_E_INVAL;
   if (mode != STEP_LOCAL && mode != STEP_MERGE_PENDING) return ORC_E_INVAL;
-  if (!t->kstep && mode != STEP_LOCAL) return ORC_E_INVAL;
+  if ((!t->kstep || t->variant == VAR_PROSE) && mode != STEP_LOCAL) return ORC_E_INVAL;
   if (!t->batch_valid || t->batch_replica != replica) return ORC_E_STATE;
   t->batch_valid = false;
+  ++t->n_push;
 
   const size_t U = t->uniq.size();
   const uint32_t n_seg = (uint32_t)t->offsets.size() - 1;
@@ -245,9 +262,18 @@ int orc_push_adam(void* h, uint32_t replica, const float* grad_pooled, uint32_t 
     for (uint32_t d = 0; d < D; ++d) {
       const size_t i = r * D + d;
       const double g = gsum[u * D + d];
+      if (t->variant == VAR_ADAGRAD) {  // v holds the accumulator G
+        v[i] = (float)((double)v[i] + g * g);
+        x[i] = (float)((double)x[i] - lr * g / std::sqrt((double)v[i]));
+        continue;
+      }
       m[i] = (float)(b1 * (double)m[i] + (1.0 - b1) * g);
       v[i] = (float)(b2 * (double)v[i] + (1.0 - b2) * (g * g));
-      if (!t->kstep) {
+      if (t->variant == VAR_KINGMA) {
+        const double mhat = (double)m[i] / (1.0 - std::pow(b1, (double)t->n_push));
+        const double vhat = (double)v[i] / (1.0 - std::pow(b2, (double)t->n_push));
+        x[i] = (float)((double)x[i] - lr * mhat / (std::sqrt(vhat) + (double)t->eps));
+      } else if (!t->kstep || t->variant == VAR_PROSE) {
         x[i] = (float)((double)x[i] - lr * (double)m[i] / std::sqrt((double)v[i]));
       } else if (mode == STEP_LOCAL) {
         x[i] = (float)((double)x[i] - lr * (double)m[i] / std::sqrt((double)t->vhat[i]));
@@ -273,7 +299,18 @@ int orc_kstep_merge(void* h) {
       const size_t i = r * D + d;
       double vs = 0.0;
       for (uint32_t j = 0; j < W; ++j) vs += (double)t->v[j][i];
-      t->vhat[i] = (float)(vs / (double)W);
+      const float vbar = (float)(vs / (double)W);
+      if (t->variant == VAR_PROSE) {
+        double xs = 0.0;
+        for (uint32_t j = 0; j < W; ++j) xs += (double)t->x[j][i];
+        const float xbar = (float)(xs / (double)W);
+        for (uint32_t j = 0; j < W; ++j) {
+          t->x[j][i] = xbar;
+          t->v[j][i] = vbar;
+        }
+        continue;
+      }
+      t->vhat[i] = vbar;
       const double den = std::sqrt((double)t->vhat[i]);
       double xs = 0.0;
       for (uint32_t j = 0; j < W; ++j) {
@@ -312,7 +349,7 @@ int orc_table_export(void* h, uint32_t replica, uint64_t* keys, float* x, float*
   if (m) std::memcpy(m, t->m[replica].data(), n * sizeof(float));
   if (v) std::memcpy(v, t->v[replica].data(), n * sizeof(float));
   if (vhat) {
-    if (!t->kstep) return ORC_E_INVAL;
+    if (!t->kstep || t->variant == VAR_PROSE) return ORC_E_INVAL;
     std::memcpy(vhat, t->vhat.data(), n * sizeof(float));
   }
   return ORC_OK;

@@ -18,6 +18,7 @@ _LIB = os.path.join(_HERE, "libctr_oracle.so")
 
 OK, E_INVAL, E_NOMEM, E_FULL, E_BADKEY, E_STATE = 0, 1, 2, 3, 4, 5
 STEP_LOCAL, STEP_MERGE_PENDING = 0, 1
+VAR_ALG2, VAR_ADAGRAD, VAR_PROSE, VAR_KINGMA = 0, 1, 2, 3
 
 
 def build(force: bool = False) -> str:
@@ -37,7 +38,7 @@ def lib():
         L = C.CDLL(build())
         u64, u32, f32, vp = C.c_uint64, C.c_uint32, C.c_float, C.c_void_p
         L.orc_create.restype = vp
-        L.orc_create.argtypes = [u64, u32, u32, f32, f32, f32, f32, u64, f32, C.c_int]
+        L.orc_create.argtypes = [u64, u32, u32, f32, f32, f32, f32, u64, f32, C.c_int, C.c_int]
         L.orc_destroy.argtypes = [vp]
         L.orc_n_rows.restype = u64
         L.orc_n_rows.argtypes = [vp]
@@ -75,10 +76,11 @@ class OracleTable:
     """One table (W replicas sharing a key->row map) held in host memory."""
 
     def __init__(self, capacity_rows, dim, n_replicas=1, lr=1e-3, beta1=0.9, beta2=0.999,
-                 eps=1e-8, init_seed=0, init_std=0.01, kstep=False):
+                 eps=1e-8, init_seed=0, init_std=0.01, kstep=False, variant=VAR_ALG2):
         self.R, self.D, self.W, self.kstep = int(capacity_rows), int(dim), int(n_replicas), bool(kstep)
+        self.variant = int(variant)
         self._h = lib().orc_create(self.R, self.D, self.W, lr, beta1, beta2, eps, init_seed,
-                                   init_std, int(self.kstep))
+                                   init_std, int(self.kstep), self.variant)
         if not self._h:
             raise ValueError("bad oracle table parameters")
 
@@ -139,7 +141,7 @@ class OracleTable:
         x = np.empty((n, self.D), np.float32)
         m = np.empty((n, self.D), np.float32)
         v = np.empty((n, self.D), np.float32)
-        vhat = np.empty((n, self.D), np.float32) if self.kstep else None
+        vhat = np.empty((n, self.D), np.float32) if (self.kstep and self.variant != VAR_PROSE) else None
         st = lib().orc_table_export(self._h, replica, _ptr(keys), _ptr(x), _ptr(m), _ptr(v),
                                     _ptr(vhat) if vhat is not None else None)
         if st != OK:

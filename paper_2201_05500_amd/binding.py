@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libctr_sparse.so")
 
 CTR_OK, CTR_E_INVAL, CTR_E_NOMEM, CTR_E_FULL, CTR_E_BADKEY, CTR_E_STATE, CTR_E_DEVICE = range(7)
-CTR_F_KSTEP = 1
+CTR_F_KSTEP, CTR_F_ADAGRAD, CTR_F_KSTEP_PROSE, CTR_F_BIAS_CORRECTION = 1, 2, 4, 8
 CTR_STEP_LOCAL, CTR_STEP_MERGE_PENDING = 0, 1
 CTR_N_STAGES = 7
 STAGE_NAMES = ("probe", "insert", "pool", "sort", "push", "fixup", "merge")
@@ -141,13 +141,17 @@ class CtrTable:
 
     def __init__(self, capacity_rows, dim, n_replicas=1, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8,
                  init_seed=0, init_std=0.01, kstep=False, load_factor=0.5, max_keys=0, max_segments=0,
-                 device="cuda:0"):
+                 device="cuda:0", adagrad=False, prose=False, bias_correction=False):
         import torch
         self._torch = torch
         self.device = torch.device(device)
         self.cfg = ctr_config(capacity_rows, dim, load_factor, n_replicas, lr, beta1, beta2, eps,
-                              init_seed, init_std, CTR_F_KSTEP if kstep else 0)
+                              init_seed, init_std,
+                              (CTR_F_KSTEP if kstep else 0) | (CTR_F_ADAGRAD if adagrad else 0) |
+                              (CTR_F_KSTEP_PROSE if prose else 0) |
+                              (CTR_F_BIAS_CORRECTION if bias_correction else 0))
         self.D, self.W, self.R, self.kstep = int(dim), int(n_replicas), int(capacity_rows), bool(kstep)
+        self.adagrad, self.prose = bool(adagrad), bool(prose)
         nbytes = ctr_table_bytes(self.cfg)
         if nbytes == 0:
             raise ValueError("invalid table configuration")
@@ -247,9 +251,9 @@ class CtrTable:
         n = self.n_rows
         keys = np.empty(n, np.uint64)
         x = np.empty((n, self.D), np.float32)
-        m = np.empty((n, self.D), np.float32)
+        m = None if self.adagrad else np.empty((n, self.D), np.float32)
         v = np.empty((n, self.D), np.float32)
-        vhat = np.empty((n, self.D), np.float32) if self.kstep else None
+        vhat = np.empty((n, self.D), np.float32) if (self.kstep and not self.prose) else None
         st = lib().ctr_table_export(self._handle, replica, _np_ptr(keys), _np_ptr(x), _np_ptr(m),
                                     _np_ptr(v), _np_ptr(vhat), self.stream)
         if st != CTR_OK:

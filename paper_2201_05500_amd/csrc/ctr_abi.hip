@@ -38,7 +38,12 @@ bool config_ok(const ctr_config* c) {
   if (c->capacity_rows == 0 || c->capacity_rows > (1ull << 30)) return false;
   if (c->n_replicas == 0 || c->n_replicas > 31) return false;
   if (!(c->load_factor >= 0.0f) || c->load_factor > 0.9f) return false;
-  if (c->flags & ~CTR_F_KSTEP) return false;
+  const uint32_t known = CTR_F_KSTEP | CTR_F_ADAGRAD | CTR_F_KSTEP_PROSE | CTR_F_BIAS_CORRECTION;
+  if (c->flags & ~known) return false;
+  if ((c->flags & CTR_F_KSTEP_PROSE) && !(c->flags & CTR_F_KSTEP)) return false;
+  if ((c->flags & CTR_F_ADAGRAD) && (c->flags & ~CTR_F_ADAGRAD)) return false;          // no replicas, no variants
+  if ((c->flags & CTR_F_BIAS_CORRECTION) && (c->flags & ~CTR_F_BIAS_CORRECTION)) return false;
+  if (!(c->flags & CTR_F_KSTEP) && c->n_replicas != 1) return false;                    // replicas exist to be merged
   if (!(c->lr > 0.0f) || !(c->beta1 >= 0.0f && c->beta1 < 1.0f) || !(c->beta2 >= 0.0f && c->beta2 < 1.0f) ||
       !(c->eps > 0.0f) || !(c->init_std >= 0.0f))
     return false;
@@ -58,10 +63,11 @@ bool table_layout(const ctr_config* c, TableLayout* L) {
   L->off_row_key = o; o += align256(R * sizeof(u64));
   L->off_row_state = o; o += align256(R * sizeof(u32));
   L->off_values = o;
-  L->replica_stride = (align256(R * 3 * D * sizeof(float))) / sizeof(float);
+  const u64 n_state = (c->flags & CTR_F_ADAGRAD) ? 2 : 3;  // [x | G] or [x | m | v]
+  L->replica_stride = (align256(R * n_state * D * sizeof(float))) / sizeof(float);
   o += L->replica_stride * sizeof(float) * W;
   L->off_vhat = o;
-  if (c->flags & CTR_F_KSTEP) o += align256(R * D * sizeof(float));
+  if ((c->flags & CTR_F_KSTEP) && !(c->flags & CTR_F_KSTEP_PROSE)) o += align256(R * D * sizeof(float));
   L->total = o;
   return true;
 }
@@ -136,8 +142,9 @@ struct ctr_batch {
 struct ctr_table {
   ctr_config cfg;
   TableLayout tl;
-  u32 D, W, lpr, row_bits;
+  u32 D, W, lpr, row_bits, rf;  // rf: floats per row
   u64 R;
+  u64 n_push;  // pushes so far (the step count t of the bias-corrected form)
   char* mem;
   DevHeader* hdr;
   Slot* slots;
@@ -235,6 +242,8 @@ int ctr_table_create(const ctr_config* cfg, void* d_mem, size_t bytes, void* hip
   t->W = cfg->n_replicas;
   t->R = cfg->capacity_rows;
   t->lpr = lanes_per_row(t->D);
+  t->rf = ((cfg->flags & CTR_F_ADAGRAD) ? 2u : 3u) * t->D;
+  t->n_push = 0;
   t->row_bits = 1;
   while ((1ull << t->row_bits) < t->R) ++t->row_bits;
   t->mem = (char*)d_mem;
@@ -243,7 +252,7 @@ int ctr_table_create(const ctr_config* cfg, void* d_mem, size_t bytes, void* hip
   t->row_key = (u64*)(t->mem + L.off_row_key);
   t->row_state = (u32*)(t->mem + L.off_row_state);
   t->values = (float*)(t->mem + L.off_values);
-  t->vhat = (cfg->flags & CTR_F_KSTEP) ? (float*)(t->mem + L.off_vhat) : nullptr;
+  t->vhat = ((cfg->flags & CTR_F_KSTEP) && !(cfg->flags & CTR_F_KSTEP_PROSE)) ? (float*)(t->mem + L.off_vhat) : nullptr;
   t->seed_mul = cfg->init_seed * 0x9E3779B97F4A7C15ull;
   t->init_scale = (float)((double)cfg->init_std / 37837.2);
   t->generation = 0;
@@ -338,7 +347,8 @@ int ctr_pull_pool(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint64
                          first_bits, wl.n_bit_words, tile_count, t->row_key);
       const u32 grid = std::min<u32>(blocks_for((u64)n * t->lpr), 4096);
       LPR_DISPATCH(t->lpr, k_init_rows, grid, st, t->hdr, t->row_key, t->values, t->tl.replica_stride, t->W,
-                   t->vhat, t->D, t->seed_mul, t->init_scale, t->cfg.eps);
+                   t->vhat, t->D, t->rf, t->seed_mul, t->init_scale,
+                   (t->cfg.flags & CTR_F_BIAS_CORRECTION) ? 0.0f : t->cfg.eps);
       hipLaunchKernelGGL(k_resolve, dim3(wl.n_probe_tiles), dim3(BLOCK), 0, st, t->hdr, t->slots, occ_row,
                          pend_list, tile_pending, wl.probe_tile);
     }
@@ -348,7 +358,7 @@ int ctr_pull_pool(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint64
     const float* vals = t->values + (u64)replica * t->tl.replica_stride;
     const u32 segs_per_block = (BLOCK / t->lpr) * POOL_NS * POOL_ROUNDS;
     LPR_DISPATCH(t->lpr, k_pool, (n_segments + segs_per_block - 1) / segs_per_block, st, t->hdr, occ_row, seg_of,
-                 d_offsets, n_segments, vals, t->D, d_pooled);
+                 d_offsets, n_segments, vals, t->D, t->rf, d_pooled);
   }
   if (n > 0) {
     StageTimer tm(t, CTR_STAGE_SORT, st);
@@ -394,8 +404,10 @@ int ctr_push_adam(ctr_table* t, uint32_t replica, ctr_batch* batch, const float*
   if (!t || !batch) return CTR_E_INVAL;
   if (replica >= t->W) return CTR_E_INVAL;
   if (mode != CTR_STEP_LOCAL && mode != CTR_STEP_MERGE_PENDING) return CTR_E_INVAL;
-  const bool kstep = (t->cfg.flags & CTR_F_KSTEP) != 0;
-  if (!kstep && mode != CTR_STEP_LOCAL) return CTR_E_INVAL;
+  const uint32_t flags = t->cfg.flags;
+  const bool kstep = (flags & CTR_F_KSTEP) != 0;
+  const bool prose = (flags & CTR_F_KSTEP_PROSE) != 0;
+  if ((!kstep || prose) && mode != CTR_STEP_LOCAL) return CTR_E_INVAL;  // only Algorithm 2 as printed defers a step
   if (t->live != batch) return CTR_E_STATE;  // stale, foreign or already consumed
   if (batch->replica != replica) return CTR_E_STATE;
   if (batch->n_seg > 0 && !d_grad_pooled) return CTR_E_INVAL;
@@ -403,32 +415,44 @@ int ctr_push_adam(ctr_table* t, uint32_t replica, ctr_batch* batch, const float*
   hipStream_t st = (hipStream_t)hip_stream;
   const WorkLayout& wl = batch->wl;
   const u32 n = batch->n_keys;
+  ++t->n_push;
   if (n > 0) {
     AdamParams P;
     P.b1 = (double)t->cfg.beta1;
     P.omb1 = 1.0 - P.b1;
     P.b2 = (double)t->cfg.beta2;
     P.omb2 = 1.0 - P.b2;
+    P.eps = (double)t->cfg.eps;
+    P.bc1 = 1.0 / (1.0 - std::pow(P.b1, (double)t->n_push));
+    P.bc2 = 1.0 / (1.0 - std::pow(P.b2, (double)t->n_push));
     P.lr = t->cfg.lr;
     P.kstep = kstep ? 1u : 0u;
-    P.mode = !kstep ? 0u : (mode == CTR_STEP_LOCAL ? 1u : 2u);
+    P.mode = (mode == CTR_STEP_MERGE_PENDING) ? 2u : 0u;
     P.pend_bit = (P.mode == 2u) ? (1u << replica) : 0u;
+    int kind = STEP_ADAM_OWN;
+    if (flags & CTR_F_ADAGRAD) kind = STEP_ADAGRAD;
+    else if (flags & CTR_F_BIAS_CORRECTION) kind = STEP_ADAM_KINGMA;
+    else if (kstep && !prose && mode == CTR_STEP_LOCAL) kind = STEP_ADAM_SHARED;
     float* vals = t->values + (u64)replica * t->tl.replica_stride;
     double* head = (double*)(batch->ws + wl.off_head);
     double* tail = (double*)(batch->ws + wl.off_tail);
     double* block_head = (double*)(batch->ws + wl.off_block_head);
     u32* span_flags = (u32*)(batch->ws + wl.off_span_flags);
     u32* span_rows = (u32*)(batch->ws + wl.off_span_rows);
-    const bool den = P.mode == 1u;  // kernels that fetch the shared denominator
+#define CTR_SPAN_LAUNCH(KERNEL)                                                                                   \
+  LPR_DISPATCH(t->lpr, KERNEL, grid, st, t->hdr, batch->sorted_rows, batch->sorted_segs, n, wl.span, d_grad_pooled, \
+               vals, t->vhat, t->row_state, t->D, t->rf, P, head, tail, span_flags, span_rows)
+#define CTR_FIXUP_LAUNCH(KERNEL)                                                                                 \
+  LPR_DISPATCH(t->lpr, KERNEL, fgrid, st, t->hdr, batch->sorted_rows, n, wl.n_spans, wl.span, vals, t->vhat,       \
+               t->row_state, t->D, t->rf, P, head, tail, block_head, span_flags)
     {
       StageTimer tm(t, CTR_STAGE_PUSH, st);
       const u32 grid = blocks_for((u64)wl.n_spans * t->lpr);
-      if (den) {
-        LPR_DISPATCH(t->lpr, k_push_span_den, grid, st, t->hdr, batch->sorted_rows, batch->sorted_segs, n, wl.span,
-                     d_grad_pooled, vals, t->vhat, t->row_state, t->D, P, head, tail, span_flags, span_rows);
-      } else {
-        LPR_DISPATCH(t->lpr, k_push_span, grid, st, t->hdr, batch->sorted_rows, batch->sorted_segs, n, wl.span,
-                     d_grad_pooled, vals, t->vhat, t->row_state, t->D, P, head, tail, span_flags, span_rows);
+      switch (kind) {
+        case STEP_ADAM_SHARED: CTR_SPAN_LAUNCH(k_push_span_shared); break;
+        case STEP_ADAGRAD: CTR_SPAN_LAUNCH(k_push_span_adagrad); break;
+        case STEP_ADAM_KINGMA: CTR_SPAN_LAUNCH(k_push_span_kingma); break;
+        default: CTR_SPAN_LAUNCH(k_push_span); break;
       }
     }
     {
@@ -436,16 +460,17 @@ int ctr_push_adam(ctr_table* t, uint32_t replica, ctr_batch* batch, const float*
       LPR_DISPATCH(t->lpr, k_push_block_heads, blocks_for((u64)wl.n_span_blocks * WAVE), st, t->hdr,
                    batch->sorted_rows, wl.n_spans, wl.span, t->D, head, block_head);
       const u32 fgrid = blocks_for((u64)wl.n_spans * WAVE);
-      if (den) {
-        LPR_DISPATCH(t->lpr, k_push_fixup_den, fgrid, st, t->hdr, batch->sorted_rows, n, wl.n_spans, wl.span, vals,
-                     t->vhat, t->row_state, t->D, P, head, tail, block_head, span_flags);
-      } else {
-        LPR_DISPATCH(t->lpr, k_push_fixup, fgrid, st, t->hdr, batch->sorted_rows, n, wl.n_spans, wl.span, vals,
-                     t->vhat, t->row_state, t->D, P, head, tail, block_head, span_flags);
+      switch (kind) {
+        case STEP_ADAM_SHARED: CTR_FIXUP_LAUNCH(k_push_fixup_shared); break;
+        case STEP_ADAGRAD: CTR_FIXUP_LAUNCH(k_push_fixup_adagrad); break;
+        case STEP_ADAM_KINGMA: CTR_FIXUP_LAUNCH(k_push_fixup_kingma); break;
+        default: CTR_FIXUP_LAUNCH(k_push_fixup); break;
       }
       const u32 grid = std::min<u32>(blocks_for(wl.n_spans), 128);
       hipLaunchKernelGGL(k_count_unique, dim3(grid), dim3(BLOCK), 0, st, t->hdr, span_rows, wl.n_spans);
     }
+#undef CTR_SPAN_LAUNCH
+#undef CTR_FIXUP_LAUNCH
   }
   t->live = nullptr;
   delete batch;
@@ -458,8 +483,13 @@ int ctr_kstep_merge(ctr_table* t, void* hip_stream) {
   hipStream_t st = (hipStream_t)hip_stream;
   StageTimer tm(t, CTR_STAGE_MERGE, st);
   const u32 grid = std::min<u32>(blocks_for(t->R * t->lpr), 16384);
-  LPR_DISPATCH(t->lpr, k_merge, grid, st, t->hdr, t->values, t->tl.replica_stride, t->W, t->vhat, t->row_state,
-               t->D, t->cfg.lr);
+  if (t->cfg.flags & CTR_F_KSTEP_PROSE) {
+    LPR_DISPATCH(t->lpr, k_merge_prose, grid, st, t->hdr, t->values, t->tl.replica_stride, t->W, t->vhat,
+                 t->row_state, t->D, t->cfg.lr);
+  } else {
+    LPR_DISPATCH(t->lpr, k_merge, grid, st, t->hdr, t->values, t->tl.replica_stride, t->W, t->vhat, t->row_state,
+                 t->D, t->cfg.lr);
+  }
   return launch_status();
 }
 
@@ -477,18 +507,21 @@ int ctr_table_export(ctr_table* t, uint32_t replica, uint64_t* h_keys, float* h_
                      float* h_vhat, void* hip_stream) {
   if (!t || replica >= t->W) return CTR_E_INVAL;
   if (h_vhat && !t->vhat) return CTR_E_INVAL;
+  const bool adagrad = (t->cfg.flags & CTR_F_ADAGRAD) != 0;
+  if (h_m && adagrad) return CTR_E_INVAL;  // AdaGrad rows have no first moment
   hipStream_t st = (hipStream_t)hip_stream;
   uint64_t n = 0;
   int rc = ctr_table_size(t, &n, hip_stream);
   if (rc != CTR_OK) return rc;
   if (n == 0) return CTR_OK;
-  const size_t D = t->D, rowb = D * sizeof(float), pitch = 3 * rowb;
+  const size_t D = t->D, rowb = D * sizeof(float), pitch = (size_t)t->rf * sizeof(float);
   const float* vals = t->values + (u64)replica * t->tl.replica_stride;
+  const float* v_src = vals + (adagrad ? D : 2 * D);
   bool ok = true;
   if (h_keys) ok = ok && hipMemcpyAsync(h_keys, t->row_key, n * sizeof(u64), hipMemcpyDeviceToHost, st) == hipSuccess;
   if (h_x) ok = ok && hipMemcpy2DAsync(h_x, rowb, vals, pitch, rowb, n, hipMemcpyDeviceToHost, st) == hipSuccess;
   if (h_m) ok = ok && hipMemcpy2DAsync(h_m, rowb, vals + D, pitch, rowb, n, hipMemcpyDeviceToHost, st) == hipSuccess;
-  if (h_v) ok = ok && hipMemcpy2DAsync(h_v, rowb, vals + 2 * D, pitch, rowb, n, hipMemcpyDeviceToHost, st) == hipSuccess;
+  if (h_v) ok = ok && hipMemcpy2DAsync(h_v, rowb, v_src, pitch, rowb, n, hipMemcpyDeviceToHost, st) == hipSuccess;
   if (h_vhat) ok = ok && hipMemcpyAsync(h_vhat, t->vhat, n * rowb, hipMemcpyDeviceToHost, st) == hipSuccess;
   ok = ok && hipStreamSynchronize(st) == hipSuccess;
   return ok ? CTR_OK : CTR_E_DEVICE;

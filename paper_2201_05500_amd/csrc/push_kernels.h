@@ -32,29 +32,43 @@ constexpr u32 NO_ROW = 0xFFFFFFFFu;
 #define CTR_PUSH_MIN_WAVES 1  // waves per SIMD the span kernel is compiled for
 #endif
 
+// Which row update a launch performs (compile-time, so that each variant carries only its own
+// registers and loads).
+enum StepKind : int {
+  STEP_ADAM_OWN = 0,     // Algorithm 2's m/v lines, step divided by the row's own v (single table, or the
+                         // "standard Adam locally" reading of Section 4); also the moments-only merge step
+  STEP_ADAM_SHARED = 1,  // Algorithm 2 local branch: step divided by the shared v frozen at the last merge
+  STEP_ADAGRAD = 2,      // the paper's production optimizer for sparse parameters (Section 5): rows [x | G]
+  STEP_ADAM_KINGMA = 3   // the cited Adam of Kingma & Ba: bias-corrected moments, eps added to the root
+};
+
 struct AdamParams {
   double b1, omb1, b2, omb2;  // beta and (1 - beta) promoted from binary32
+  double bc1, bc2, eps;       // STEP_ADAM_KINGMA: 1/(1 - beta1^t), 1/(1 - beta2^t), epsilon
   float lr;
-  u32 mode;      // 0: den = own v   1: den = shared denominator   2: moments only (merge pending)
+  u32 mode;      // 0: moments and model   2: moments only (merge pending)
   u32 kstep;     // maintain the per-row state word
   u32 pend_bit;  // (1 << replica) when mode == 2, else 0
 };
 
 struct RowState4 {
-  f4 x, m, v, den;  // den: the shared denominator of the row (k-step local step only)
+  f4 x, m, v, den;  // v doubles as AdaGrad's accumulator; den: shared denominator (STEP_ADAM_SHARED only)
 };
 
-// DEN (compile time) == the step divides by the shared denominator (P.mode == 1): only then is it
-// fetched, so the single-table path carries no registers for it.
-template <bool DEN>
+// rf = floats per row: 3*D for [x | m | v], 2*D for AdaGrad's [x | G].
+template <int KIND>
 __device__ __forceinline__ RowState4 load_row4(const float* __restrict__ values, const float* __restrict__ vhat,
-                                               u32 row, u32 D, u32 c) {
+                                               u32 row, u32 D, u32 rf, u32 c) {
   RowState4 s;
-  const float* px = values + (u64)row * 3 * D + 4 * c;
+  const float* px = values + (u64)row * rf + 4 * c;
   s.x = ldg4(px);
-  s.m = ldg4(px + D);
-  s.v = ldg4(px + 2 * D);
-  if constexpr (DEN) s.den = ldg4(vhat + (u64)row * D + 4 * c);
+  if constexpr (KIND == STEP_ADAGRAD) {
+    s.v = ldg4(px + D);
+  } else {
+    s.m = ldg4(px + D);
+    s.v = ldg4(px + 2 * D);
+  }
+  if constexpr (KIND == STEP_ADAM_SHARED) s.den = ldg4(vhat + (u64)row * D + 4 * c);
   return s;
 }
 
@@ -63,14 +77,31 @@ __device__ __forceinline__ double rsqrt_refined(float a) {
   return y * (1.5 - 0.5 * d * y * y);
 }
 
-// One Adam step on 4 columns of one row whose state is already in registers.
-// m and v are formed in binary64 from the stored binary32 values and rounded
-// once, and so is the model step.
-template <bool DEN>
-__device__ __forceinline__ void adam_apply4(RowState4 s, float* __restrict__ row_base, u32 D, u32 c, d4 g,
-                                            const AdamParams& P) {
+// One optimizer step on 4 columns of one row whose state is already in registers.  Every
+// assignment is evaluated in binary64 from the stored binary32 values and rounded once.
+// A binary32 quotient for the model step would leave an error proportional to the step, which
+// can be orders of magnitude larger than the parameter it lands on (shared denominator still at
+// eps); 1/sqrt(den) is a binary32 estimate refined by one Newton step in binary64 (relative error
+// ~1e-13), cheaper than a binary64 sqrt and divide.
+template <int KIND>
+__device__ __forceinline__ void row_apply4(RowState4 s, float* __restrict__ row_base, u32 D, u32 c, d4 g,
+                                           const AdamParams& P) {
   float* px = row_base + 4 * c;
   f4 x = s.x, m = s.m, v = s.v;
+  const double lr = (double)P.lr;
+  if constexpr (KIND == STEP_ADAGRAD) {
+    v.x = (float)((double)v.x + g.x * g.x);
+    v.y = (float)((double)v.y + g.y * g.y);
+    v.z = (float)((double)v.z + g.z * g.z);
+    v.w = (float)((double)v.w + g.w * g.w);
+    stg4(px + D, v);
+    x.x = (float)((double)x.x - lr * g.x * rsqrt_refined(v.x));
+    x.y = (float)((double)x.y - lr * g.y * rsqrt_refined(v.y));
+    x.z = (float)((double)x.z - lr * g.z * rsqrt_refined(v.z));
+    x.w = (float)((double)x.w - lr * g.w * rsqrt_refined(v.w));
+    stg4(px, x);
+    return;
+  }
   m.x = (float)(P.b1 * (double)m.x + P.omb1 * g.x);
   m.y = (float)(P.b1 * (double)m.y + P.omb1 * g.y);
   m.z = (float)(P.b1 * (double)m.z + P.omb1 * g.z);
@@ -81,14 +112,15 @@ __device__ __forceinline__ void adam_apply4(RowState4 s, float* __restrict__ row
   v.w = (float)(P.b2 * (double)v.w + P.omb2 * (g.w * g.w));
   stg4(px + D, m);
   stg4(px + 2 * D, v);
-  if (P.mode != 2u) {
+  if constexpr (KIND == STEP_ADAM_KINGMA) {
+    x.x = (float)((double)x.x - lr * ((double)m.x * P.bc1) / (sqrt((double)v.x * P.bc2) + P.eps));
+    x.y = (float)((double)x.y - lr * ((double)m.y * P.bc1) / (sqrt((double)v.y * P.bc2) + P.eps));
+    x.z = (float)((double)x.z - lr * ((double)m.z * P.bc1) / (sqrt((double)v.z * P.bc2) + P.eps));
+    x.w = (float)((double)x.w - lr * ((double)m.w * P.bc1) / (sqrt((double)v.w * P.bc2) + P.eps));
+    stg4(px, x);
+  } else if (P.mode != 2u) {
     f4 den = v;
-    if constexpr (DEN) den = s.den;
-    // binary64 like the moments: a step can be orders of magnitude larger than the parameter it
-    // lands on (shared denominator still at eps), and a binary32 quotient would leave an error
-    // proportional to the step, not to the result.  1/sqrt(den): binary32 estimate refined by one
-    // Newton step in binary64 (relative error ~1e-13), cheaper than a binary64 sqrt and divide.
-    const double lr = (double)P.lr;
+    if constexpr (KIND == STEP_ADAM_SHARED) den = s.den;
     x.x = (float)((double)x.x - lr * (double)m.x * rsqrt_refined(den.x));
     x.y = (float)((double)x.y - lr * (double)m.y * rsqrt_refined(den.y));
     x.z = (float)((double)x.z - lr * (double)m.z * rsqrt_refined(den.z));
@@ -97,11 +129,11 @@ __device__ __forceinline__ void adam_apply4(RowState4 s, float* __restrict__ row
   }
 }
 
-template <bool DEN>
+template <int KIND>
 __device__ __forceinline__ void finish_row_loaded(u32 row, RowState4 s, d4 g, u32 c, bool col_ok,
                                                   float* __restrict__ values, u32* __restrict__ row_state, u32 D,
-                                                  const AdamParams& P) {
-  if (col_ok) adam_apply4<DEN>(s, values + (u64)row * 3 * D, D, c, g, P);
+                                                  u32 rf, const AdamParams& P) {
+  if (col_ok) row_apply4<KIND>(s, values + (u64)row * rf, D, c, g, P);
   if (P.kstep && c == 0) atomicOr(&row_state[row], RS_TOUCHED | P.pend_bit);
 }
 
@@ -119,12 +151,12 @@ __device__ __forceinline__ void add_partial(const double* __restrict__ part, u32
 // the PB gradient-row loads and the x/m/v loads of every row that ends inside
 // the batch, so that a group keeps several KB in flight instead of one
 // dependent row at a time.
-template <int LPR, bool DEN>
+template <int LPR, int KIND>
 __device__ __forceinline__ void push_span_body(const DevHeader* hdr, const u32* __restrict__ sr,
                                                const u32* __restrict__ ss, u32 n, u32 span,
                                                const float* __restrict__ grad, float* __restrict__ values,
                                                const float* __restrict__ vhat, u32* __restrict__ row_state, u32 D,
-                                               const AdamParams& P, double* __restrict__ head_part,
+                                               u32 rf, const AdamParams& P, double* __restrict__ head_part,
                                                double* __restrict__ tail_part, u32* __restrict__ span_flags,
                                                u32* __restrict__ span_rows) {
   if (hdr->status) return;
@@ -173,7 +205,7 @@ __device__ __forceinline__ void push_span_body(const DevHeader* hdr, const u32* 
     }
 #pragma unroll
     for (int i = 0; i < PB; ++i)
-      if (whole[i] && col_ok) st[i] = load_row4<DEN>(values, vhat, r[i], D, c);
+      if (whole[i] && col_ok) st[i] = load_row4<KIND>(values, vhat, r[i], D, rf, c);
 #pragma unroll
     for (int i = 0; i < PB; ++i) {
       if (valid[i]) {
@@ -183,7 +215,7 @@ __device__ __forceinline__ void push_span_body(const DevHeader* hdr, const u32* 
         acc.w += (double)gv[i].w;
         if (ends[i]) {
           if (whole[i]) {
-            finish_row_loaded<DEN>(r[i], st[i], acc, c, col_ok, values, row_state, D, P);
+            finish_row_loaded<KIND>(r[i], st[i], acc, c, col_ok, values, row_state, D, rf, P);
             ++started;
           } else {  // end of the row that was open on entry
             if (col_ok) store_partial(head_part, s, D, c, acc);
@@ -216,20 +248,21 @@ __device__ __forceinline__ void push_span_body(const DevHeader* hdr, const u32* 
 #define CTR_PUSH_SPAN_ARGS                                                                                      \
   const DevHeader *hdr, const u32 *__restrict__ sr, const u32 *__restrict__ ss, u32 n, u32 span,               \
       const float *__restrict__ grad, float *__restrict__ values, const float *__restrict__ vhat,              \
-      u32 *__restrict__ row_state, u32 D, AdamParams P, double *__restrict__ head_part,                        \
+      u32 *__restrict__ row_state, u32 D, u32 rf, AdamParams P, double *__restrict__ head_part,                \
       double *__restrict__ tail_part, u32 *__restrict__ span_flags, u32 *__restrict__ span_rows
 #define CTR_PUSH_SPAN_PASS \
-  hdr, sr, ss, n, span, grad, values, vhat, row_state, D, P, head_part, tail_part, span_flags, span_rows
+  hdr, sr, ss, n, span, grad, values, vhat, row_state, D, rf, P, head_part, tail_part, span_flags, span_rows
 
-template <int LPR>
-__global__ void __launch_bounds__(BLOCK, CTR_PUSH_MIN_WAVES) k_push_span(CTR_PUSH_SPAN_ARGS) {
-  push_span_body<LPR, false>(CTR_PUSH_SPAN_PASS);
-}
-// the k-step local step: divides by the shared denominator
-template <int LPR>
-__global__ void __launch_bounds__(BLOCK) k_push_span_den(CTR_PUSH_SPAN_ARGS) {
-  push_span_body<LPR, true>(CTR_PUSH_SPAN_PASS);
-}
+// one kernel per step kind (the dispatch macro on the host takes kernels templated on LPR only)
+#define CTR_DEFINE_PUSH_SPAN(NAME, KIND)                                                       \
+  template <int LPR>                                                                           \
+  __global__ void __launch_bounds__(BLOCK, CTR_PUSH_MIN_WAVES) NAME(CTR_PUSH_SPAN_ARGS) {      \
+    push_span_body<LPR, KIND>(CTR_PUSH_SPAN_PASS);                                             \
+  }
+CTR_DEFINE_PUSH_SPAN(k_push_span, STEP_ADAM_OWN)
+CTR_DEFINE_PUSH_SPAN(k_push_span_shared, STEP_ADAM_SHARED)
+CTR_DEFINE_PUSH_SPAN(k_push_span_adagrad, STEP_ADAGRAD)
+CTR_DEFINE_PUSH_SPAN(k_push_span_kingma, STEP_ADAM_KINGMA)
 
 // Number of leading lanes (from lane 0) whose predicate holds; wave-uniform.
 __device__ __forceinline__ u32 leading_true(bool pred) {
@@ -277,11 +310,11 @@ k_push_block_heads(const DevHeader* hdr, const u32* __restrict__ sr, u32 n_spans
 // One wave per span that holds a tail: tail + heads of the following spans of
 // the same block + block sums of the following blocks, while they continue
 // the same row; then the row update.
-template <int LPR, bool DEN>
+template <int LPR, int KIND>
 __device__ __forceinline__ void push_fixup_body(const DevHeader* hdr, const u32* __restrict__ sr, u32 n, u32 n_spans,
                                                 u32 span, float* __restrict__ values,
                                                 const float* __restrict__ vhat, u32* __restrict__ row_state, u32 D,
-                                                const AdamParams& P, const double* __restrict__ head_part,
+                                                u32 rf, const AdamParams& P, const double* __restrict__ head_part,
                                                 const double* __restrict__ tail_part,
                                                 const double* __restrict__ block_head,
                                                 const u32* __restrict__ span_flags) {
@@ -301,7 +334,7 @@ __device__ __forceinline__ void push_fixup_body(const DevHeader* hdr, const u32*
   RowState4 st;
   if (grp == 0 && col_ok) {
     add_partial(tail_part, s, D, c, acc);
-    st = load_row4<DEN>(values, vhat, row, D, c);
+    st = load_row4<KIND>(values, vhat, row, D, rf, c);
   }
   // spans after s inside its block (at most SPANS_PER_BLOCK - 1 = one per lane)
   const u32 t = s + 1 + lane;
@@ -318,25 +351,26 @@ __device__ __forceinline__ void push_fixup_body(const DevHeader* hdr, const u32*
     }
   }
   combine_groups<LPR>(acc);
-  if (grp == 0) finish_row_loaded<DEN>(row, st, acc, c, col_ok, values, row_state, D, P);
+  if (grp == 0) finish_row_loaded<KIND>(row, st, acc, c, col_ok, values, row_state, D, rf, P);
 }
 
 #define CTR_PUSH_FIXUP_ARGS                                                                                     \
   const DevHeader *hdr, const u32 *__restrict__ sr, u32 n, u32 n_spans, u32 span, float *__restrict__ values,  \
-      const float *__restrict__ vhat, u32 *__restrict__ row_state, u32 D, AdamParams P,                        \
+      const float *__restrict__ vhat, u32 *__restrict__ row_state, u32 D, u32 rf, AdamParams P,                \
       const double *__restrict__ head_part, const double *__restrict__ tail_part,                              \
       const double *__restrict__ block_head, const u32 *__restrict__ span_flags
 #define CTR_PUSH_FIXUP_PASS \
-  hdr, sr, n, n_spans, span, values, vhat, row_state, D, P, head_part, tail_part, block_head, span_flags
+  hdr, sr, n, n_spans, span, values, vhat, row_state, D, rf, P, head_part, tail_part, block_head, span_flags
 
-template <int LPR>
-__global__ void __launch_bounds__(BLOCK) k_push_fixup(CTR_PUSH_FIXUP_ARGS) {
-  push_fixup_body<LPR, false>(CTR_PUSH_FIXUP_PASS);
-}
-template <int LPR>
-__global__ void __launch_bounds__(BLOCK) k_push_fixup_den(CTR_PUSH_FIXUP_ARGS) {
-  push_fixup_body<LPR, true>(CTR_PUSH_FIXUP_PASS);
-}
+#define CTR_DEFINE_PUSH_FIXUP(NAME, KIND)                                    \
+  template <int LPR>                                                         \
+  __global__ void __launch_bounds__(BLOCK) NAME(CTR_PUSH_FIXUP_ARGS) {       \
+    push_fixup_body<LPR, KIND>(CTR_PUSH_FIXUP_PASS);                         \
+  }
+CTR_DEFINE_PUSH_FIXUP(k_push_fixup, STEP_ADAM_OWN)
+CTR_DEFINE_PUSH_FIXUP(k_push_fixup_shared, STEP_ADAM_SHARED)
+CTR_DEFINE_PUSH_FIXUP(k_push_fixup_adagrad, STEP_ADAGRAD)
+CTR_DEFINE_PUSH_FIXUP(k_push_fixup_kingma, STEP_ADAM_KINGMA)
 
 // Sum of the per-span counts of rows that start in the span = distinct keys of the batch.
 // The counter is zeroed by the pull (k_scan_tiles).
@@ -350,13 +384,16 @@ __global__ void k_count_unique(DevHeader* hdr, const u32* __restrict__ span_rows
   if (threadIdx.x == 0 && total) atomicAdd(&hdr->n_unique, total);
 }
 
-// k-step merge.  One group of LPR lanes per row in use; rows nobody touched
-// since the last merge are skipped.  vhat = mean_j v_j; every replica's x becomes
-// mean_j (x_j - [pending_j] lr m_j / sqrt(vhat)); sums in binary64, rounded once.
-template <int LPR>
-__global__ void __launch_bounds__(BLOCK)
-k_merge(const DevHeader* hdr, float* __restrict__ values, u64 replica_stride, u32 W, float* __restrict__ vhat,
-        u32* __restrict__ row_state, u32 D, float lr) {
+// k-step merge.  One group of LPR lanes per row in use; rows nobody touched since the last merge
+// are skipped.  Sums in binary64, rounded once.
+//   PROSE == false (Algorithm 2 as printed): shared v = mean_j v_j; every replica's x becomes
+//     mean_j (x_j - [pending_j] lr m_j / sqrt(shared v)); local v_j stay.
+//   PROSE == true (Section 4's prose: standard Adam locally, weights and v averaged): every
+//     replica's x becomes mean_j x_j and every v_j becomes mean_j v_j.
+template <int LPR, bool PROSE>
+__device__ __forceinline__ void merge_body(const DevHeader* hdr, float* __restrict__ values, u64 replica_stride,
+                                           u32 W, float* __restrict__ vhat, u32* __restrict__ row_state, u32 D,
+                                           float lr) {
   if (hdr->status) return;
   const u32 n_rows = hdr->n_rows;
   const u32 c = threadIdx.x % LPR;
@@ -375,14 +412,19 @@ k_merge(const DevHeader* hdr, float* __restrict__ values, u64 replica_stride, u3
       const double w = (double)W;
       f4 vh;
       vh.x = (float)(vs.x / w); vh.y = (float)(vs.y / w); vh.z = (float)(vs.z / w); vh.w = (float)(vs.w / w);
-      stg4(vhat + (u64)row * D + 4 * c, vh);
-      const d4 rs = {rsqrt_refined(vh.x), rsqrt_refined(vh.y), rsqrt_refined(vh.z), rsqrt_refined(vh.w)};
+      d4 rs = {0.0, 0.0, 0.0, 0.0};
+      if constexpr (PROSE) {
+        for (u32 j = 0; j < W; ++j) stg4(base + j * replica_stride + 2 * D, vh);
+      } else {
+        stg4(vhat + (u64)row * D + 4 * c, vh);
+        rs = d4{rsqrt_refined(vh.x), rsqrt_refined(vh.y), rsqrt_refined(vh.z), rsqrt_refined(vh.w)};
+      }
       const double lrd = (double)lr;
       d4 xs = {0.0, 0.0, 0.0, 0.0};
       for (u32 j = 0; j < W; ++j) {
         const f4 x = ldg4(base + j * replica_stride);
         d4 y = {(double)x.x, (double)x.y, (double)x.z, (double)x.w};
-        if (st & (1u << j)) {
+        if (!PROSE && (st & (1u << j))) {
           const f4 m = ldg4(base + j * replica_stride + D);
           y.x -= lrd * (double)m.x * rs.x;
           y.y -= lrd * (double)m.y * rs.y;
@@ -397,6 +439,19 @@ k_merge(const DevHeader* hdr, float* __restrict__ values, u64 replica_stride, u3
     }
     if (c == 0) row_state[row] = 0;
   }
+}
+
+template <int LPR>
+__global__ void __launch_bounds__(BLOCK)
+k_merge(const DevHeader* hdr, float* __restrict__ values, u64 replica_stride, u32 W, float* __restrict__ vhat,
+        u32* __restrict__ row_state, u32 D, float lr) {
+  merge_body<LPR, false>(hdr, values, replica_stride, W, vhat, row_state, D, lr);
+}
+template <int LPR>
+__global__ void __launch_bounds__(BLOCK)
+k_merge_prose(const DevHeader* hdr, float* __restrict__ values, u64 replica_stride, u32 W,
+              float* __restrict__ vhat, u32* __restrict__ row_state, u32 D, float lr) {
+  merge_body<LPR, true>(hdr, values, replica_stride, W, vhat, row_state, D, lr);
 }
 
 }  // namespace ctr

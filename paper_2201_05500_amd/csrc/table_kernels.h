@@ -231,11 +231,13 @@ __global__ void k_assign_rows(const DevHeader* hdr, Slot* slots, const u32* __re
 }
 
 // Writes the initial state of the rows created by this pull, in every replica:
-// x = init(key, d), m = 0, v = eps, shared denominator = eps.
+// x = init(key, d); first moment 0 (rows that have one); second moment / AdaGrad accumulator
+// = v0 (eps per Algorithm 2's "Initialize", 0 for the bias-corrected form); shared denominator = v0.
+// rf = floats per row (3*D with a first moment, 2*D without).
 template <int LPR>
 __global__ void k_init_rows(const DevHeader* hdr, const u64* __restrict__ row_key, float* values,
-                            u64 replica_stride, u32 n_replicas, float* vhat, u32 D, u64 seed_mul,
-                            float scale, float eps) {
+                            u64 replica_stride, u32 n_replicas, float* vhat, u32 D, u32 rf, u64 seed_mul,
+                            float scale, float v0) {
   if (hdr->status) return;
   const u32 n_new = hdr->n_new, row_base = hdr->n_rows_base;
   const u32 c = threadIdx.x % LPR;
@@ -250,12 +252,16 @@ __global__ void k_init_rows(const DevHeader* hdr, const u64* __restrict__ row_ke
     x.z = init_value(seed_mul, key, 4 * c + 2, scale);
     x.w = init_value(seed_mul, key, 4 * c + 3, scale);
     z.x = z.y = z.z = z.w = 0.0f;
-    e.x = e.y = e.z = e.w = eps;
+    e.x = e.y = e.z = e.w = v0;
     for (u32 j = 0; j < n_replicas; ++j) {
-      float* b = values + j * replica_stride + (u64)row * 3 * D + 4 * c;
+      float* b = values + j * replica_stride + (u64)row * rf + 4 * c;
       stg4(b, x);
-      stg4(b + D, z);
-      stg4(b + 2 * D, e);
+      if (rf == 3 * D) {
+        stg4(b + D, z);
+        stg4(b + 2 * D, e);
+      } else {
+        stg4(b + D, e);
+      }
     }
     if (vhat) stg4(vhat + (u64)row * D + 4 * c, e);
   }
@@ -283,14 +289,14 @@ __global__ void k_resolve(const DevHeader* hdr, const Slot* __restrict__ slots, 
 // at a time so that up to 8 independent row loads are in flight per group:
 // pooled[g, :] = sum over the segment's occurrences of x[row, :], in CSR order, binary32
 // inside a batch of 4 consecutive occurrences and binary64 across batches, rounded once
-// (error <= 3 * 2^-24 * sum |x|).  Rows are [x | m | v] of 3*D floats.
+// (error <= 3 * 2^-24 * sum |x|).  A row is rf floats and starts with x.
 constexpr int POOL_NS = 2;      // segments a group works on at once
 constexpr int POOL_ROUNDS = 2;  // such pairs per group
 
 template <int LPR>
 __global__ void __launch_bounds__(BLOCK)
 k_pool(const DevHeader* hdr, const u32* __restrict__ occ_row, u32* __restrict__ seg_of,
-       const u32* __restrict__ offsets, u32 n_seg, const float* __restrict__ values, u32 D,
+       const u32* __restrict__ offsets, u32 n_seg, const float* __restrict__ values, u32 D, u32 rf,
        float* __restrict__ pooled) {
   if (hdr->status) return;
   constexpr int GROUPS = BLOCK / LPR;
@@ -338,7 +344,7 @@ k_pool(const DevHeader* hdr, const u32* __restrict__ occ_row, u32* __restrict__ 
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           xv[s][i].x = xv[s][i].y = xv[s][i].z = xv[s][i].w = 0.0f;
-          if (beg[s] + k + i < end[s] && col_ok) xv[s][i] = ldg4(values + (u64)r[s][i] * 3 * D + 4 * c);
+          if (beg[s] + k + i < end[s] && col_ok) xv[s][i] = ldg4(values + (u64)r[s][i] * rf + 4 * c);
         }
 #pragma unroll
       for (int s = 0; s < POOL_NS; ++s) {  // padded entries add +0.0

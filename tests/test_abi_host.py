@@ -44,12 +44,17 @@ def test_table_bytes_accounts_for_every_array():
     # load factor decides the number of index slots (next power of two of R / lf)
     assert B.ctr_table_bytes(_cfg(load_factor=0.25)) - n == (1 << 17) * 16
     assert B.ctr_table_bytes(_cfg(load_factor=0.0)) == n            # 0 selects 0.5
+    # AdaGrad rows hold two arrays instead of three; the prose merge needs no shared-denominator array
+    assert n - B.ctr_table_bytes(_cfg(flags=B.CTR_F_ADAGRAD)) == R * D * 4
+    assert k - B.ctr_table_bytes(_cfg(n_replicas=8, flags=B.CTR_F_KSTEP | B.CTR_F_KSTEP_PROSE)) == R * D * 4
 
 
 @pytest.mark.parametrize("bad", [
     dict(dim=0), dict(dim=6), dict(dim=260), dict(capacity_rows=0), dict(capacity_rows=(1 << 30) + 1),
     dict(n_replicas=0), dict(n_replicas=32), dict(load_factor=0.95), dict(load_factor=-1.0),
-    dict(flags=8), dict(lr=0.0), dict(beta1=1.0), dict(beta2=-0.1), dict(eps=0.0),
+    dict(flags=16), dict(flags=B.CTR_F_KSTEP_PROSE), dict(flags=B.CTR_F_ADAGRAD | B.CTR_F_KSTEP),
+    dict(flags=B.CTR_F_ADAGRAD, n_replicas=2), dict(flags=B.CTR_F_BIAS_CORRECTION | B.CTR_F_KSTEP),
+    dict(n_replicas=2), dict(lr=0.0), dict(beta1=1.0), dict(beta2=-0.1), dict(eps=0.0),
 ])
 def test_invalid_configurations_are_rejected(bad):
     assert B.ctr_table_bytes(_cfg(**bad)) == 0
