@@ -163,6 +163,28 @@ int ctr_push_adam(ctr_table* t, uint32_t replica, ctr_batch* batch, const float*
  * and v_i = (1/W) sum_j v_j for all i.  Needs CTR_F_KSTEP.  Errors: CTR_E_INVAL. */
 int ctr_kstep_merge(ctr_table* t, void* hip_stream);
 
+/* Working-set load (Algorithm 1: partition_parameters_to_GPUs + insert_into_hash_table): places
+ * the parameters of a batch's working set, as handed over by the host-side tiers, in the table.
+ *   d_keys[n_keys]                  device, distinct keys (a repeated key makes its row's
+ *                                   contents unspecified)
+ *   d_x, d_m, d_v[n_keys * D]       device, the rows' state (d_m ignored and may be NULL under
+ *                                   CTR_F_ADAGRAD, where d_v is the accumulator)
+ *   d_workspace                     device, >= ctr_workspace_bytes(cfg, n_keys, 0), 256-byte aligned
+ * Keys not yet in the table get new rows (numbered in the order given); keys already there have
+ * their rows overwritten.  Every replica receives the same state; Algorithm 2's shared denominator
+ * of the row is set to v.  A live batch of this table goes stale.  Enqueues only.
+ * Errors: CTR_E_INVAL, CTR_E_NOMEM; deferred: CTR_E_BADKEY, CTR_E_FULL (nothing is loaded). */
+int ctr_table_load(ctr_table* t, const uint64_t* d_keys, uint64_t n_keys, const float* d_x, const float* d_m,
+                   const float* d_v, void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Collection of updated rows (Algorithm 1: pull_updates_peer_GPU, the step that hands the batch's
+ * parameters back to the host-side tiers): looks up n_keys keys WITHOUT inserting and copies the
+ * rows of replica `replica` to dense device arrays (any of d_x, d_m, d_v, d_found may be NULL;
+ * d_m must be NULL under CTR_F_ADAGRAD).  d_found[p] = 1 if keys[p] is in the table, else 0 and
+ * its output rows are zeros.  Enqueues only.  Errors: CTR_E_INVAL. */
+int ctr_table_collect(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint64_t n_keys, float* d_x,
+                      float* d_m, float* d_v, uint32_t* d_found, void* hip_stream);
+
 /* ---- parity / debug surface (synchronising, not part of the timed path) ---- */
 
 /* Number of rows in use. */

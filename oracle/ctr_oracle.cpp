@@ -327,6 +327,72 @@ int orc_kstep_merge(void* h) {
   return ORC_OK;
 }
 
+// Working-set load (Algorithm 1: insert_into_hash_table of a parameter partition): keys not in the
+// table get new rows in the order given, keys already there are overwritten; every replica gets
+// the same state and the shared denominator of the row is set to v.
+int orc_table_load(void* h, const uint64_t* keys, uint64_t n, const float* x, const float* m, const float* v) {
+  Table* t = (Table*)h;
+  const uint32_t D = t->D;
+  for (uint64_t p = 0; p < n; ++p)
+    if (keys[p] == SENTINEL) return ORC_E_BADKEY;
+  {
+    std::unordered_set<uint64_t> fresh;
+    for (uint64_t p = 0; p < n; ++p)
+      if (t->row_of.find(keys[p]) == t->row_of.end()) fresh.insert(keys[p]);
+    if (t->n_rows + fresh.size() > t->R) return ORC_E_FULL;
+  }
+  t->batch_valid = false;
+  const bool has_vhat = t->kstep && t->variant != VAR_PROSE;
+  for (uint64_t p = 0; p < n; ++p) {
+    auto it = t->row_of.find(keys[p]);
+    uint32_t r;
+    if (it == t->row_of.end()) {
+      r = (uint32_t)t->n_rows++;
+      t->row_of[keys[p]] = r;
+      t->key_of_row.push_back(keys[p]);
+      for (uint32_t j = 0; j < t->W; ++j) {
+        t->x[j].resize((size_t)t->n_rows * D);
+        t->m[j].resize((size_t)t->n_rows * D);
+        t->v[j].resize((size_t)t->n_rows * D);
+        t->pending[j].push_back(0);
+      }
+      if (has_vhat) t->vhat.resize((size_t)t->n_rows * D);
+      t->touched.push_back(0);
+    } else {
+      r = it->second;
+    }
+    for (uint32_t j = 0; j < t->W; ++j)
+      for (uint32_t d = 0; d < D; ++d) {
+        t->x[j][(size_t)r * D + d] = x[p * D + d];
+        t->m[j][(size_t)r * D + d] = (t->variant == VAR_ADAGRAD) ? 0.0f : m[p * D + d];
+        t->v[j][(size_t)r * D + d] = v[p * D + d];
+      }
+    if (has_vhat)
+      for (uint32_t d = 0; d < D; ++d) t->vhat[(size_t)r * D + d] = v[p * D + d];
+  }
+  return ORC_OK;
+}
+
+// Collection of rows by key, without inserting (Algorithm 1: pull_updates_peer_GPU).
+int orc_table_collect(void* h, uint32_t replica, const uint64_t* keys, uint64_t n, float* x, float* m, float* v,
+                      uint32_t* found) {
+  Table* t = (Table*)h;
+  if (replica >= t->W) return ORC_E_INVAL;
+  const uint32_t D = t->D;
+  for (uint64_t p = 0; p < n; ++p) {
+    auto it = t->row_of.find(keys[p]);
+    const bool hit = it != t->row_of.end();
+    if (found) found[p] = hit ? 1u : 0u;
+    for (uint32_t d = 0; d < D; ++d) {
+      const size_t i = hit ? (size_t)it->second * D + d : 0;
+      if (x) x[p * D + d] = hit ? t->x[replica][i] : 0.0f;
+      if (m) m[p * D + d] = hit ? t->m[replica][i] : 0.0f;
+      if (v) v[p * D + d] = hit ? t->v[replica][i] : 0.0f;
+    }
+  }
+  return ORC_OK;
+}
+
 // Dedup result of the last pull: ascending distinct keys, their rows, and the
 // index of every occurrence's key in that list.
 int orc_batch_export(void* h, uint64_t* uniq, uint32_t* rows, uint32_t* inverse) {

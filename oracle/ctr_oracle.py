@@ -60,6 +60,10 @@ def lib():
         L.orc_batch_export.argtypes = [vp, vp, vp, vp]
         L.orc_table_export.restype = C.c_int
         L.orc_table_export.argtypes = [vp, u32, vp, vp, vp, vp, vp]
+        L.orc_table_load.restype = C.c_int
+        L.orc_table_load.argtypes = [vp, vp, u64, vp, vp, vp]
+        L.orc_table_collect.restype = C.c_int
+        L.orc_table_collect.argtypes = [vp, u32, vp, u64, vp, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -122,6 +126,24 @@ class OracleTable:
 
     def kstep_merge(self):
         return lib().orc_kstep_merge(self._h)
+
+    def table_load(self, keys, x, m, v):
+        keys = np.ascontiguousarray(keys, dtype=np.uint64)
+        x = np.ascontiguousarray(x, dtype=np.float32)
+        v = np.ascontiguousarray(v, dtype=np.float32)
+        m = np.zeros_like(x) if m is None else np.ascontiguousarray(m, dtype=np.float32)
+        return lib().orc_table_load(self._h, _ptr(keys), keys.size, _ptr(x), _ptr(m), _ptr(v))
+
+    def table_collect(self, replica, keys):
+        """(status, x, m, v, found) for the given keys, without inserting."""
+        keys = np.ascontiguousarray(keys, dtype=np.uint64)
+        n = keys.size
+        x = np.empty((n, self.D), np.float32)
+        m = np.empty((n, self.D), np.float32)
+        v = np.empty((n, self.D), np.float32)
+        found = np.empty(n, np.uint32)
+        st = lib().orc_table_collect(self._h, replica, _ptr(keys), n, _ptr(x), _ptr(m), _ptr(v), _ptr(found))
+        return st, x, m, v, found
 
     def batch_export(self, n_keys):
         """(uniq ascending, rows, inverse) of the last pull; call before the push."""

@@ -24,7 +24,8 @@ STAGE_NAMES = ("probe", "insert", "pool", "sort", "push", "fixup", "merge")
 
 EXPORTED = (
     "ctr_table_bytes", "ctr_workspace_bytes", "ctr_table_create", "ctr_table_destroy",
-    "ctr_pull_pool", "ctr_push_adam", "ctr_kstep_merge", "ctr_table_size", "ctr_table_export",
+    "ctr_pull_pool", "ctr_push_adam", "ctr_kstep_merge", "ctr_table_load", "ctr_table_collect",
+    "ctr_table_size", "ctr_table_export",
     "ctr_batch_export", "ctr_batch_stats", "ctr_last_status", "ctr_profile_enable",
     "ctr_profile_read",
 )
@@ -75,6 +76,10 @@ def lib():
     L.ctr_push_adam.argtypes = [vp, u32, vp, vp, u32, vp]
     L.ctr_kstep_merge.restype = ci
     L.ctr_kstep_merge.argtypes = [vp, vp]
+    L.ctr_table_load.restype = ci
+    L.ctr_table_load.argtypes = [vp, vp, u64, vp, vp, vp, vp, sz, vp]
+    L.ctr_table_collect.restype = ci
+    L.ctr_table_collect.argtypes = [vp, u32, vp, u64, vp, vp, vp, vp, vp]
     L.ctr_table_size.restype = ci
     L.ctr_table_size.argtypes = [vp, C.POINTER(u64), vp]
     L.ctr_table_export.restype = ci
@@ -126,6 +131,14 @@ def ctr_push_adam(table, replica, batch, d_grad, mode, stream) -> int:
 
 def ctr_kstep_merge(table, stream) -> int:
     return lib().ctr_kstep_merge(table, stream)
+
+
+def ctr_table_load(table, d_keys, n_keys, d_x, d_m, d_v, d_ws, ws_bytes, stream) -> int:
+    return lib().ctr_table_load(table, d_keys, n_keys, d_x, d_m, d_v, d_ws, ws_bytes, stream)
+
+
+def ctr_table_collect(table, replica, d_keys, n_keys, d_x, d_m, d_v, d_found, stream) -> int:
+    return lib().ctr_table_collect(table, replica, d_keys, n_keys, d_x, d_m, d_v, d_found, stream)
 
 
 def ctr_last_status(table, stream) -> int:
@@ -212,6 +225,27 @@ class CtrTable:
 
     def kstep_merge(self):
         return ctr_kstep_merge(self._handle, self.stream)
+
+    def table_load(self, keys, x, m, v):
+        """keys int64/uint64 [n]; x, m, v float32 [n, D] device tensors (m may be None for AdaGrad rows)."""
+        n = keys.numel()
+        self.reserve(max(n, 1), 0)
+        return ctr_table_load(self._handle, keys.data_ptr() if n else None, n, x.data_ptr() if n else None,
+                              m.data_ptr() if (m is not None and n) else None, v.data_ptr() if n else None,
+                              self._ws.data_ptr(), self.ws_bytes, self.stream)
+
+    def table_collect(self, replica, keys):
+        """Returns (status, x, m or None, v, found) device tensors for the given keys (no insert)."""
+        torch = self._torch
+        n = keys.numel()
+        x = torch.empty((n, self.D), dtype=torch.float32, device=self.device)
+        m = None if self.adagrad else torch.empty_like(x)
+        v = torch.empty_like(x)
+        found = torch.empty(n, dtype=torch.int32, device=self.device)
+        st = ctr_table_collect(self._handle, replica, keys.data_ptr() if n else None, n, x.data_ptr(),
+                               m.data_ptr() if m is not None else None, v.data_ptr(), found.data_ptr(),
+                               self.stream)
+        return st, x, m, v, found
 
     # -- debug / parity surface
     def last_status(self) -> int:

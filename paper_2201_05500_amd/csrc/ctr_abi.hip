@@ -212,6 +212,46 @@ int status_code_from_bits(u32 bits) {
 
 }  // namespace
 
+// Key -> row for every occurrence, inserting unseen keys (rows numbered by first occurrence, state
+// initialised); on return of the enqueued work occ_row[p] holds the row of keys[p], or the pull has
+// failed and was rolled back (device status set).  d_offsets may be null (nothing to validate).
+static void enqueue_lookup_insert(ctr_table* t, const WorkLayout& wl, char* ws, const u64* d_keys, u32 n,
+                                  const u32* d_offsets, u32 n_segments, hipStream_t st) {
+  u32* occ_row = (u32*)(ws + wl.off_occ_row);
+  u32* tile_count = (u32*)(ws + wl.off_tile_count);
+  u32* first_bits = (u32*)(ws + wl.off_first_bits);
+  u32* pend_list = (u32*)(ws + wl.off_pend_list);
+  u32* tile_pending = (u32*)(ws + wl.off_tile_pending);
+  const u32 slot_mask = (u32)(t->tl.n_slots - 1);
+  {
+    StageTimer tm(t, CTR_STAGE_PROBE, st);
+    const u64 work = std::max<u64>(n, d_offsets ? (u64)n_segments + 1 : 1);
+    const u32 grid = (u32)((work + wl.probe_tile - 1) / wl.probe_tile);  // >= n_probe_tiles
+    hipLaunchKernelGGL(k_probe_insert, dim3(grid), dim3(BLOCK), 0, st, t->hdr, t->slots, slot_mask, d_keys, n,
+                       d_offsets, n_segments, occ_row, first_bits, pend_list, tile_pending, wl.probe_items);
+  }
+  {
+    StageTimer tm(t, CTR_STAGE_INSERT, st);
+    if (n > 0) {
+      hipLaunchKernelGGL(k_flag_first, dim3(wl.n_probe_tiles), dim3(BLOCK), 0, st, t->hdr, t->slots, occ_row,
+                         pend_list, tile_pending, wl.probe_tile, first_bits);
+      hipLaunchKernelGGL(k_count_first, dim3(wl.n_bit_tiles), dim3(BLOCK), 0, st, t->hdr, first_bits,
+                         wl.n_bit_words, tile_count);
+    }
+    hipLaunchKernelGGL(k_scan_tiles, dim3(1), dim3(BLOCK), 0, st, t->hdr, tile_count, wl.n_bit_tiles, t->R);
+    if (n > 0) {
+      hipLaunchKernelGGL(k_assign_rows, dim3(wl.n_bit_tiles), dim3(BLOCK), 0, st, t->hdr, t->slots, occ_row,
+                         first_bits, wl.n_bit_words, tile_count, t->row_key);
+      const u32 grid = std::min<u32>(blocks_for((u64)n * t->lpr), 4096);
+      LPR_DISPATCH(t->lpr, k_init_rows, grid, st, t->hdr, t->row_key, t->values, t->tl.replica_stride, t->W,
+                   t->vhat, t->D, t->rf, t->seed_mul, t->init_scale,
+                   (t->cfg.flags & CTR_F_BIAS_CORRECTION) ? 0.0f : t->cfg.eps);
+      hipLaunchKernelGGL(k_resolve, dim3(wl.n_probe_tiles), dim3(BLOCK), 0, st, t->hdr, t->slots, occ_row,
+                         pend_list, tile_pending, wl.probe_tile);
+    }
+  }
+}
+
 extern "C" {
 
 size_t ctr_table_bytes(const ctr_config* cfg) {
@@ -319,40 +359,7 @@ int ctr_pull_pool(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint64
   const u32 n = (u32)n_keys;
   u32* occ_row = (u32*)(b->ws + wl.off_occ_row);
   u32* seg_of = (u32*)(b->ws + wl.off_seg_of);
-  u32* tile_count = (u32*)(b->ws + wl.off_tile_count);
-  const u32 slot_mask = (u32)(t->tl.n_slots - 1);
-
-  u32* first_bits = (u32*)(b->ws + wl.off_first_bits);
-  u32* pend_list = (u32*)(b->ws + wl.off_pend_list);
-  u32* tile_pending = (u32*)(b->ws + wl.off_tile_pending);
-  {
-    StageTimer tm(t, CTR_STAGE_PROBE, st);
-    const u64 work = std::max<u64>(n, (u64)n_segments + 1);
-    const u32 grid = (u32)((work + wl.probe_tile - 1) / wl.probe_tile);  // >= n_probe_tiles
-    hipLaunchKernelGGL(k_probe_insert, dim3(grid), dim3(BLOCK), 0, st, t->hdr, t->slots, slot_mask,
-                       (const u64*)d_keys, n, d_offsets, n_segments, occ_row, first_bits, pend_list, tile_pending,
-                       wl.probe_items);
-  }
-  {
-    StageTimer tm(t, CTR_STAGE_INSERT, st);
-    if (n > 0) {
-      hipLaunchKernelGGL(k_flag_first, dim3(wl.n_probe_tiles), dim3(BLOCK), 0, st, t->hdr, t->slots, occ_row,
-                         pend_list, tile_pending, wl.probe_tile, first_bits);
-      hipLaunchKernelGGL(k_count_first, dim3(wl.n_bit_tiles), dim3(BLOCK), 0, st, t->hdr, first_bits,
-                         wl.n_bit_words, tile_count);
-    }
-    hipLaunchKernelGGL(k_scan_tiles, dim3(1), dim3(BLOCK), 0, st, t->hdr, tile_count, wl.n_bit_tiles, t->R);
-    if (n > 0) {
-      hipLaunchKernelGGL(k_assign_rows, dim3(wl.n_bit_tiles), dim3(BLOCK), 0, st, t->hdr, t->slots, occ_row,
-                         first_bits, wl.n_bit_words, tile_count, t->row_key);
-      const u32 grid = std::min<u32>(blocks_for((u64)n * t->lpr), 4096);
-      LPR_DISPATCH(t->lpr, k_init_rows, grid, st, t->hdr, t->row_key, t->values, t->tl.replica_stride, t->W,
-                   t->vhat, t->D, t->rf, t->seed_mul, t->init_scale,
-                   (t->cfg.flags & CTR_F_BIAS_CORRECTION) ? 0.0f : t->cfg.eps);
-      hipLaunchKernelGGL(k_resolve, dim3(wl.n_probe_tiles), dim3(BLOCK), 0, st, t->hdr, t->slots, occ_row,
-                         pend_list, tile_pending, wl.probe_tile);
-    }
-  }
+  enqueue_lookup_insert(t, wl, b->ws, (const u64*)d_keys, n, d_offsets, n_segments, st);
   if (n_segments > 0) {
     StageTimer tm(t, CTR_STAGE_POOL, st);
     const float* vals = t->values + (u64)replica * t->tl.replica_stride;
@@ -490,6 +497,46 @@ int ctr_kstep_merge(ctr_table* t, void* hip_stream) {
     LPR_DISPATCH(t->lpr, k_merge, grid, st, t->hdr, t->values, t->tl.replica_stride, t->W, t->vhat, t->row_state,
                  t->D, t->cfg.lr);
   }
+  return launch_status();
+}
+
+int ctr_table_load(ctr_table* t, const uint64_t* d_keys, uint64_t n_keys, const float* d_x, const float* d_m,
+                   const float* d_v, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!t || !d_workspace) return CTR_E_INVAL;
+  if (n_keys >= (1ull << 31)) return CTR_E_INVAL;
+  const bool has_m = !(t->cfg.flags & CTR_F_ADAGRAD);
+  if (n_keys > 0 && (!d_keys || !d_x || !d_v || (has_m && !d_m))) return CTR_E_INVAL;
+  if (((uintptr_t)d_workspace & 255) != 0) return CTR_E_INVAL;
+  WorkLayout wl;
+  work_layout(t->D, n_keys, &wl);
+  if (workspace_bytes < wl.total) return CTR_E_NOMEM;
+  if (t->live) {  // the workspace of an unpushed batch may be this one: it goes stale
+    delete t->live;
+    t->live = nullptr;
+  }
+  ++t->generation;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const u32 n = (u32)n_keys;
+  enqueue_lookup_insert(t, wl, (char*)d_workspace, (const u64*)d_keys, n, nullptr, 0, st);
+  if (n > 0) {
+    const u32* occ_row = (const u32*)((char*)d_workspace + wl.off_occ_row);
+    LPR_DISPATCH(t->lpr, k_load_rows, blocks_for((u64)n * t->lpr), st, t->hdr, occ_row, n, t->values,
+                 t->tl.replica_stride, t->W, t->vhat, t->D, t->rf, d_x, d_m, d_v);
+  }
+  return launch_status();
+}
+
+int ctr_table_collect(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint64_t n_keys, float* d_x,
+                      float* d_m, float* d_v, uint32_t* d_found, void* hip_stream) {
+  if (!t || replica >= t->W) return CTR_E_INVAL;
+  if (n_keys >= (1ull << 31)) return CTR_E_INVAL;
+  if (n_keys > 0 && !d_keys) return CTR_E_INVAL;
+  if (d_m && (t->cfg.flags & CTR_F_ADAGRAD)) return CTR_E_INVAL;
+  if (n_keys == 0) return CTR_OK;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const float* vals = t->values + (u64)replica * t->tl.replica_stride;
+  LPR_DISPATCH(t->lpr, k_collect_rows, blocks_for(n_keys * t->lpr), st, t->hdr, t->slots,
+               (u32)(t->tl.n_slots - 1), (const u64*)d_keys, (u32)n_keys, vals, t->D, t->rf, d_x, d_m, d_v, d_found);
   return launch_status();
 }
 

@@ -52,7 +52,7 @@ k_probe_insert(DevHeader* hdr, Slot* slots, u32 slot_mask, const u64* __restrict
 #pragma unroll 1
   for (u32 it = 0; it < items; ++it) {
     const u32 p = tile0 + it * BLOCK + threadIdx.x;
-    if (p <= n_seg) {
+    if (offsets != nullptr && p <= n_seg) {  // (a working-set load has no segments)
       const u32 a = offsets[p];
       bool bad = (p == 0 && a != 0);
       if (p == n_seg)
@@ -278,6 +278,83 @@ __global__ void k_resolve(const DevHeader* hdr, const Slot* __restrict__ slots, 
     const u32 p = pend_list[blockIdx.x * probe_tile + i];
     occ_row[p] = slots[occ_row[p] & ~OCC_PEND_FLAG].row;
   }
+}
+
+// ---------------------------------------------------------------- working-set load / collection
+
+// After the keys of a working set have been looked up or inserted (occ_row[p] = row of keys[p]):
+// overwrites the state of those rows, in every replica, with the values supplied by the caller
+// (the shared denominator, where there is one, is set to v).  m_src may be null for rows without
+// a first moment.
+template <int LPR>
+__global__ void k_load_rows(const DevHeader* hdr, const u32* __restrict__ occ_row, u32 n, float* values,
+                            u64 replica_stride, u32 n_replicas, float* vhat, u32 D, u32 rf,
+                            const float* __restrict__ x_src, const float* __restrict__ m_src,
+                            const float* __restrict__ v_src) {
+  if (hdr->status) return;
+  const u32 p = (blockIdx.x * BLOCK + threadIdx.x) / LPR;
+  const u32 c = threadIdx.x % LPR;
+  if (p >= n || c * 4 >= D) return;
+  const u32 row = occ_row[p];
+  const f4 x = ldg4(x_src + (u64)p * D + 4 * c);
+  const f4 v = ldg4(v_src + (u64)p * D + 4 * c);
+  f4 m = {0.0f, 0.0f, 0.0f, 0.0f};
+  if (rf == 3 * D) m = ldg4(m_src + (u64)p * D + 4 * c);
+  for (u32 j = 0; j < n_replicas; ++j) {
+    float* b = values + j * replica_stride + (u64)row * rf + 4 * c;
+    stg4(b, x);
+    if (rf == 3 * D) {
+      stg4(b + D, m);
+      stg4(b + 2 * D, v);
+    } else {
+      stg4(b + D, v);
+    }
+  }
+  if (vhat) stg4(vhat + (u64)row * D + 4 * c, v);
+}
+
+// Pure lookup (no insert) of n keys and copy of their rows of one replica to dense arrays; a key
+// that is not in the table gets found = 0 and zeros.
+template <int LPR>
+__global__ void k_collect_rows(const DevHeader* hdr, const Slot* __restrict__ slots, u32 slot_mask,
+                               const u64* __restrict__ keys, u32 n, const float* __restrict__ values, u32 D,
+                               u32 rf, float* __restrict__ x_dst, float* __restrict__ m_dst,
+                               float* __restrict__ v_dst, u32* __restrict__ found) {
+  if (hdr->status) return;
+  const u32 p = (blockIdx.x * BLOCK + threadIdx.x) / LPR;
+  const u32 c = threadIdx.x % LPR;
+  if (p >= n) return;
+  const u64 key = keys[p];
+  u32 row = ROW_PENDING;
+  if (key != KEY_EMPTY) {
+    u32 h = (u32)hash_key(key) & slot_mask;
+    for (u32 probe = 0; probe <= slot_mask; ++probe) {  // every lane of the group walks the same slots
+      const u64 k = slots[h].key;
+      if (k == key) {
+        row = slots[h].row;
+        break;
+      }
+      if (k == KEY_EMPTY) break;
+      h = (h + 1) & slot_mask;
+    }
+  }
+  const bool hit = row != ROW_PENDING;
+  if (c == 0 && found) found[p] = hit ? 1u : 0u;
+  if (c * 4 >= D) return;
+  f4 x = {0.0f, 0.0f, 0.0f, 0.0f}, m = x, v = x;
+  if (hit) {
+    const float* b = values + (u64)row * rf + 4 * c;
+    x = ldg4(b);
+    if (rf == 3 * D) {
+      m = ldg4(b + D);
+      v = ldg4(b + 2 * D);
+    } else {
+      v = ldg4(b + D);
+    }
+  }
+  if (x_dst) stg4(x_dst + (u64)p * D + 4 * c, x);
+  if (m_dst) stg4(m_dst + (u64)p * D + 4 * c, m);
+  if (v_dst) stg4(v_dst + (u64)p * D + 4 * c, v);
 }
 
 // ---------------------------------------------------------------- gather + per-segment sum

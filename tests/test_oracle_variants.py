@@ -201,3 +201,48 @@ def test_variant_argument_checks():
         O.OracleTable(8, 4, kstep=True, variant=O.VAR_KINGMA)
     with pytest.raises(ValueError):
         O.OracleTable(8, 4, n_replicas=2)                         # replicas exist to be merged
+
+
+# ---------------------------------------------------------------- working-set load / collection
+
+
+def test_load_then_pull_pools_the_loaded_rows_and_collect_returns_them():
+    """Algorithm 1: insert_into_hash_table of a parameter partition, then pulls see those parameters;
+    pull_updates_peer_GPU hands back what the table holds."""
+    rng = np.random.default_rng(8)
+    D = 4
+    for kw in (dict(), dict(n_replicas=3, kstep=True), dict(variant=O.VAR_ADAGRAD)):
+        t = O.OracleTable(8, D, init_seed=1, **kw)
+        keys = np.array([50, 10, 30], np.uint64)
+        x = rng.standard_normal((3, D)).astype(F32)
+        m = rng.standard_normal((3, D)).astype(F32)
+        v = rng.random((3, D)).astype(F32) + 0.1
+        assert t.table_load(keys, x, m, v) == O.OK
+        assert t.n_rows == 3 and [t.lookup(int(k)) for k in keys] == [0, 1, 2]     # rows in the order given
+        st, pooled = t.pull_pool(0, np.array([10, 30, 10, 77], np.uint64), np.array([0, 3, 4], np.uint32))
+        np.testing.assert_allclose(pooled[0], (2 * x[1].astype(np.float64) + x[2]).astype(F32), rtol=1e-6)
+        assert t.n_rows == 4                                        # 77 was new: ordinary insert-on-miss
+        for j in range(t.W):
+            st, cx, cm, cv, found = t.table_collect(j, np.array([30, 99, 50], np.uint64))
+            assert st == O.OK and list(found) == [1, 0, 1]
+            assert np.array_equal(cx[0], x[2]) and np.array_equal(cx[2], x[0]) and not cx[1].any()
+            assert np.array_equal(cv[0], v[2])
+            if t.variant != O.VAR_ADAGRAD:
+                assert np.array_equal(cm[2], m[0])
+        assert t.lookup(99) == -1                                   # collecting never inserts
+        if t.kstep:
+            assert np.array_equal(t.table_export(0)["vhat"][:3], v)    # shared denominator := v
+        # loading an existing key overwrites its row and creates none
+        assert t.table_load(np.array([10], np.uint64), x[:1] + 1, m[:1], v[:1]) == O.OK
+        assert t.n_rows == 4 and np.array_equal(t.table_export(0)["x"][1], x[0] + 1)
+
+
+def test_load_capacity_and_sentinel_leave_the_table_unchanged():
+    D = 2
+    t = O.OracleTable(3, D, init_seed=1)
+    z = np.zeros((4, D), F32)
+    assert t.table_load(np.array([1, 2], np.uint64), z[:2], z[:2], z[:2] + 1) == O.OK
+    assert t.table_load(np.array([2, 3, 4], np.uint64), z[:3], z[:3], z[:3] + 1) == O.E_FULL
+    assert t.table_load(np.array([2, 2 ** 64 - 1], np.uint64), z[:2], z[:2], z[:2] + 1) == O.E_BADKEY
+    assert t.n_rows == 2 and t.lookup(3) == -1
+    assert t.table_load(np.array([2, 3], np.uint64), z[:2], z[:2], z[:2] + 1) == O.OK and t.n_rows == 3
