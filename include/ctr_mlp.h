@@ -1,0 +1,91 @@
+/*
+ * ctr_mlp.h - C ABI of the dense tower that sits between the pull and the push of the sparse
+ * embedding cycle (MI355X / gfx950).
+ *
+ * The paper's training step is pull -> train_mini-batch -> push (Algorithm 1); the dense network
+ * is a fully connected tower over the concatenated slot embeddings (Section 2.1) whose dense
+ * parameters are trained with k-step Adam (Algorithm 2, Section 4; Section 5 for the setting).
+ * This header covers that middle step: forward, sigmoid cross-entropy loss, backward down to the
+ * gradient of the pooled embeddings (the input of ctr_push_adam), and the dense optimizer.
+ *
+ * Arithmetic: matrix products take bf16 operands with fp32 accumulation on the matrix cores
+ * (rocBLAS gemm_ex; everything else is hand-written HIP).  Master parameters, moments and the
+ * optimizer are fp32/fp64 exactly as in the sparse path: m0 = 0, v0 = eps, no bias correction,
+ * x -= lr m / sqrt(den) with den = own v (one replica) or the shared v frozen at the last merge.
+ * Rounding to bf16 (nearest-even) happens at: the input, the weight copies used by the products,
+ * every hidden activation, and every back-propagated hidden gradient.
+ *
+ * Conventions are those of ctr_sparse.h: d_* device pointers owned by the caller, `hip_stream`
+ * a hipStream_t, calls enqueue only, status codes of ctr_status.  The rocBLAS handle the tower
+ * owns keeps its own device workspace.
+ */
+#ifndef CTR_MLP_H
+#define CTR_MLP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ctr_mlp ctr_mlp; /* opaque host-side handle */
+
+#define CTR_MLP_MAX_HIDDEN 6
+
+typedef struct {
+  uint32_t in_dim;                     /* width of the input (slots x embedding dim), multiple of 8 */
+  uint32_t n_hidden;                   /* 1..CTR_MLP_MAX_HIDDEN hidden ReLU layers */
+  uint32_t hidden[CTR_MLP_MAX_HIDDEN]; /* their widths, multiples of 8; the output layer has width 1 */
+  uint32_t n_replicas;                 /* W >= 1 model replicas (W > 1 needs kstep) */
+  uint32_t kstep;                      /* 1: Algorithm 2 with a shared denominator and ctr_mlp_kstep_merge */
+  float lr, beta1, beta2, eps;         /* alpha, beta_1, beta_2, epsilon of Algorithm 2 */
+  uint64_t init_seed;                  /* weights: deterministic stand-in for N(0, 2 / fan_in); biases 0 */
+} ctr_mlp_config;
+
+/* Bytes of device memory for the parameters, moments and bf16 copies of all replicas (0 if the
+ * configuration is invalid), and of per-step workspace for a batch of `batch` samples. */
+size_t ctr_mlp_bytes(const ctr_mlp_config* cfg);
+size_t ctr_mlp_workspace_bytes(const ctr_mlp_config* cfg, uint32_t batch);
+
+/* Creates the tower in caller-provided device memory (256-byte aligned, >= ctr_mlp_bytes) and
+ * enqueues the initialisation of every replica (all replicas start equal: Algorithm 2's x_0).
+ * Errors: CTR_E_INVAL, CTR_E_NOMEM, CTR_E_DEVICE. */
+int ctr_mlp_create(const ctr_mlp_config* cfg, void* d_mem, size_t bytes, void* hip_stream, ctr_mlp** out);
+int ctr_mlp_destroy(ctr_mlp* m);
+
+/* One training step of replica `replica` (Algorithm 1's train_mini-batch; Algorithm 2's m, v and
+ * model lines on the dense parameters):
+ *   d_pooled[batch * in_dim]       device, in: fp32 pooled embeddings (output of ctr_pull_pool)
+ *   d_labels[batch]                device, in: fp32 0/1 click labels
+ *   d_grad_pooled[batch * in_dim]  device, out: d(mean loss)/d(pooled), fp32 (input of ctr_push_adam)
+ *   d_loss                         device, out: one float, the mean sigmoid cross-entropy
+ *   d_workspace                    device, >= ctr_mlp_workspace_bytes(cfg, batch), 256-byte aligned
+ *   mode                           CTR_STEP_LOCAL or CTR_STEP_MERGE_PENDING, as in ctr_push_adam
+ * batch must be a multiple of 8.  Errors: CTR_E_INVAL, CTR_E_NOMEM, CTR_E_DEVICE. */
+int ctr_mlp_step(ctr_mlp* m, uint32_t replica, const float* d_pooled, const float* d_labels, uint32_t batch,
+                 float* d_grad_pooled, float* d_loss, void* d_workspace, size_t workspace_bytes, uint32_t mode,
+                 void* hip_stream);
+
+/* Forward only: d_logits[batch] fp32 (no parameter changes). */
+int ctr_mlp_forward(ctr_mlp* m, uint32_t replica, const float* d_pooled, uint32_t batch, float* d_logits,
+                    void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Algorithm 2's global-averaging branch over all dense parameters of the W replicas:
+ * shared v = mean_j v_j; x_i = mean_j (x_j - [merge step pending in j] lr m_j / sqrt(shared v)). */
+int ctr_mlp_kstep_merge(ctr_mlp* m, void* hip_stream);
+
+/* Number of parameters of one replica (weights and biases of all layers, in layer order:
+ * W_1[in x h_1] row-major, b_1[h_1], W_2, b_2, ..., w_out[h_last x 1], b_out[1]). */
+size_t ctr_mlp_n_params(const ctr_mlp_config* cfg);
+
+/* Debug: copies the flat parameter vector, first and second moments of a replica and the shared
+ * denominator (kstep only) to HOST arrays of ctr_mlp_n_params floats (any may be NULL);
+ * synchronises the stream. */
+int ctr_mlp_export(ctr_mlp* m, uint32_t replica, float* h_params, float* h_m, float* h_v, float* h_vhat,
+                   void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CTR_MLP_H */
