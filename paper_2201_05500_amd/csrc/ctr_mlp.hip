@@ -1,0 +1,339 @@
+// Host side of the dense-tower C ABI (include/ctr_mlp.h): memory layout, the sequence of rocBLAS
+// bf16 GEMMs and hand-written kernels of one training step, the dense optimizer and its merge.
+#include "../../include/ctr_mlp.h"
+#include "../../include/ctr_sparse.h"
+
+#include <rocblas/rocblas.h>
+
+#include <algorithm>
+#include <cmath>
+#include <new>
+
+#include "common.h"
+#include "mlp_kernels.h"
+
+using namespace ctr;
+
+namespace {
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+inline u32 blocks_for(u64 threads) { return (u32)((threads + BLOCK - 1) / BLOCK); }
+
+bool mlp_config_ok(const ctr_mlp_config* c) {
+  if (!c) return false;
+  if (c->in_dim == 0 || c->in_dim % 8 != 0) return false;
+  if (c->n_hidden == 0 || c->n_hidden > CTR_MLP_MAX_HIDDEN) return false;
+  for (u32 i = 0; i < c->n_hidden; ++i)
+    if (c->hidden[i] == 0 || c->hidden[i] % 8 != 0 || c->hidden[i] > 65536) return false;
+  if (c->n_replicas == 0 || c->n_replicas > 31) return false;
+  if (c->kstep > 1) return false;
+  if (!c->kstep && c->n_replicas != 1) return false;
+  if (!(c->lr > 0.0f) || !(c->beta1 >= 0.0f && c->beta1 < 1.0f) || !(c->beta2 >= 0.0f && c->beta2 < 1.0f) ||
+      !(c->eps > 0.0f))
+    return false;
+  return true;
+}
+
+void make_layout(const ctr_mlp_config* c, MlpLayout* L) {
+  L->n_layers = c->n_hidden + 1;
+  u64 off = 0;
+  for (u32 l = 0; l < L->n_layers; ++l) {
+    L->in[l] = l == 0 ? c->in_dim : c->hidden[l - 1];
+    L->out[l] = l < c->n_hidden ? c->hidden[l] : 1;
+    L->w_off[l] = off;
+    off += (u64)L->in[l] * L->out[l] + L->out[l];
+  }
+  L->n_params = off;
+}
+
+struct MemLayout {
+  u64 stride;  // elements between replicas (n_params rounded up to 128)
+  size_t off_params, off_m, off_v, off_pb, off_vhat, total;
+};
+
+void mem_layout(const ctr_mlp_config* c, const MlpLayout& L, MemLayout* M) {
+  M->stride = (L.n_params + 127) & ~(u64)127;
+  const size_t W = c->n_replicas;
+  size_t o = 0;
+  M->off_params = o; o += align256(M->stride * W * sizeof(float));
+  M->off_m = o; o += align256(M->stride * W * sizeof(float));
+  M->off_v = o; o += align256(M->stride * W * sizeof(float));
+  M->off_pb = o; o += align256(M->stride * W * sizeof(bf16_t));
+  M->off_vhat = o;
+  if (c->kstep) o += align256(M->stride * sizeof(float));
+  M->total = o;
+}
+
+struct WsLayout {
+  u32 max_h;
+  size_t off_h0, off_act[CTR_MLP_MAX_HIDDEN], off_z, off_da, off_dz[2], off_logits, off_dlogit, off_grads,
+      off_partial, total;
+};
+
+void ws_layout(const ctr_mlp_config* c, const MlpLayout& L, u32 B, WsLayout* S) {
+  u32 mh = 8;
+  for (u32 i = 0; i < c->n_hidden; ++i) mh = std::max(mh, c->hidden[i]);
+  S->max_h = mh;
+  size_t o = 0;
+  S->off_h0 = o; o += align256((size_t)B * c->in_dim * sizeof(bf16_t));
+  for (u32 i = 0; i < c->n_hidden; ++i) {
+    S->off_act[i] = o;
+    o += align256((size_t)B * c->hidden[i] * sizeof(bf16_t));
+  }
+  S->off_z = o; o += align256((size_t)B * mh * sizeof(float));
+  S->off_da = o; o += align256((size_t)B * mh * sizeof(float));
+  S->off_dz[0] = o; o += align256((size_t)B * mh * sizeof(bf16_t));
+  S->off_dz[1] = o; o += align256((size_t)B * mh * sizeof(bf16_t));
+  S->off_logits = o; o += align256((size_t)B * sizeof(float));
+  S->off_dlogit = o; o += align256((size_t)B * sizeof(float));
+  S->off_grads = o; o += align256((size_t)L.n_params * sizeof(float));
+  S->off_partial = o; o += align256((size_t)COLSUM_SLICES * mh * sizeof(float));
+  S->total = o;
+}
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? CTR_OK : CTR_E_DEVICE; }
+
+}  // namespace
+
+struct ctr_mlp {
+  ctr_mlp_config cfg;
+  MlpLayout L;
+  MemLayout M;
+  char* mem;
+  float *params, *m, *v, *vhat;
+  bf16_t* pb;
+  rocblas_handle blas;
+  u32 pend_mask;  // replicas whose last step was a merge step not merged yet
+};
+
+namespace {
+
+// Row-major C[M x N] = A[M x K] B[K x N] and its two transposed forms, written for a column-major
+// library through (XY)^T = Y^T X^T: a row-major matrix is the column-major matrix of its transpose.
+bool gemm(ctr_mlp* t, rocblas_operation opa, rocblas_operation opb, int m, int n, int k, const void* a, int lda,
+          const void* b, int ldb, float* c, int ldc) {
+  const float alpha = 1.0f, beta = 0.0f;
+  return rocblas_gemm_ex(t->blas, opa, opb, m, n, k, &alpha, a, rocblas_datatype_bf16_r, lda, b,
+                         rocblas_datatype_bf16_r, ldb, &beta, c, rocblas_datatype_f32_r, ldc, c,
+                         rocblas_datatype_f32_r, ldc, rocblas_datatype_f32_r, rocblas_gemm_algo_standard, 0,
+                         0) == rocblas_status_success;
+}
+
+// Forward through the hidden layers and the output layer; activations stay in the workspace.
+bool forward(ctr_mlp* t, u32 replica, const float* d_pooled, u32 B, char* ws, const WsLayout& S, float* logits,
+             hipStream_t st) {
+  const MlpLayout& L = t->L;
+  const float* P = t->params + (u64)replica * t->M.stride;
+  const bf16_t* PB = t->pb + (u64)replica * t->M.stride;
+  bf16_t* h = (bf16_t*)(ws + S.off_h0);
+  float* z = (float*)(ws + S.off_z);
+  const u64 n0 = (u64)B * L.in[0];
+  hipLaunchKernelGGL(k_cast_bf16, dim3(blocks_for(n0 / 4)), dim3(BLOCK), 0, st, d_pooled, h, n0);
+  for (u32 l = 0; l + 1 < L.n_layers; ++l) {
+    const int i = (int)L.in[l], o = (int)L.out[l];
+    // Z[B x o] = H[B x i] W[i x o]
+    if (!gemm(t, rocblas_operation_none, rocblas_operation_none, o, (int)B, i, PB + L.w_off[l], o, h, i, z, o))
+      return false;
+    bf16_t* a = (bf16_t*)(ws + S.off_act[l]);
+    const u64 n = (u64)B * o;
+    hipLaunchKernelGGL(k_bias_relu_bf16, dim3(blocks_for(n / 4)), dim3(BLOCK), 0, st, z,
+                       P + L.w_off[l] + (u64)i * o, (u32)o, n, a);
+    h = a;
+  }
+  const u32 lo = L.n_layers - 1;
+  hipLaunchKernelGGL(k_out_forward, dim3(blocks_for((u64)B * WAVE)), dim3(BLOCK), 0, st, h, PB + L.w_off[lo],
+                     P + L.w_off[lo] + L.in[lo], B, L.in[lo], logits);
+  return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t ctr_mlp_n_params(const ctr_mlp_config* cfg) {
+  if (!mlp_config_ok(cfg)) return 0;
+  MlpLayout L;
+  make_layout(cfg, &L);
+  return (size_t)L.n_params;
+}
+
+size_t ctr_mlp_bytes(const ctr_mlp_config* cfg) {
+  if (!mlp_config_ok(cfg)) return 0;
+  MlpLayout L;
+  MemLayout M;
+  make_layout(cfg, &L);
+  mem_layout(cfg, L, &M);
+  return M.total;
+}
+
+size_t ctr_mlp_workspace_bytes(const ctr_mlp_config* cfg, uint32_t batch) {
+  if (!mlp_config_ok(cfg) || batch == 0 || batch % 8 != 0) return 0;
+  MlpLayout L;
+  WsLayout S;
+  make_layout(cfg, &L);
+  ws_layout(cfg, L, batch, &S);
+  return S.total;
+}
+
+int ctr_mlp_create(const ctr_mlp_config* cfg, void* d_mem, size_t bytes, void* hip_stream, ctr_mlp** out) {
+  if (!cfg || !d_mem || !out) return CTR_E_INVAL;
+  if (!mlp_config_ok(cfg)) return CTR_E_INVAL;
+  if (((uintptr_t)d_mem & 255) != 0) return CTR_E_INVAL;
+  ctr_mlp* t = new (std::nothrow) ctr_mlp();
+  if (!t) return CTR_E_NOMEM;
+  t->cfg = *cfg;
+  make_layout(cfg, &t->L);
+  mem_layout(cfg, t->L, &t->M);
+  if (bytes < t->M.total) {
+    delete t;
+    return CTR_E_NOMEM;
+  }
+  t->mem = (char*)d_mem;
+  t->params = (float*)(t->mem + t->M.off_params);
+  t->m = (float*)(t->mem + t->M.off_m);
+  t->v = (float*)(t->mem + t->M.off_v);
+  t->pb = (bf16_t*)(t->mem + t->M.off_pb);
+  t->vhat = cfg->kstep ? (float*)(t->mem + t->M.off_vhat) : nullptr;
+  t->pend_mask = 0;
+  if (rocblas_create_handle(&t->blas) != rocblas_status_success) {
+    delete t;
+    return CTR_E_DEVICE;
+  }
+  // fixed summation order: no atomics in the products
+  (void)rocblas_set_atomics_mode(t->blas, rocblas_atomics_not_allowed);
+  (void)rocblas_set_pointer_mode(t->blas, rocblas_pointer_mode_host);
+  hipStream_t st = (hipStream_t)hip_stream;
+  hipLaunchKernelGGL(k_mlp_init, dim3(blocks_for(t->L.n_params)), dim3(BLOCK), 0, st, t->L,
+                     cfg->init_seed * 0x9E3779B97F4A7C15ull, cfg->eps, cfg->n_replicas, t->M.stride, t->params, t->m,
+                     t->v, t->vhat, t->pb);
+  if (launch_status() != CTR_OK) {
+    (void)rocblas_destroy_handle(t->blas);
+    delete t;
+    return CTR_E_DEVICE;
+  }
+  *out = t;
+  return CTR_OK;
+}
+
+int ctr_mlp_destroy(ctr_mlp* t) {
+  if (!t) return CTR_E_INVAL;
+  (void)rocblas_destroy_handle(t->blas);
+  delete t;
+  return CTR_OK;
+}
+
+int ctr_mlp_forward(ctr_mlp* t, uint32_t replica, const float* d_pooled, uint32_t batch, float* d_logits,
+                    void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!t || !d_pooled || !d_logits || !d_workspace) return CTR_E_INVAL;
+  if (replica >= t->cfg.n_replicas || batch == 0 || batch % 8 != 0) return CTR_E_INVAL;
+  if (((uintptr_t)d_workspace & 255) != 0) return CTR_E_INVAL;
+  WsLayout S;
+  ws_layout(&t->cfg, t->L, batch, &S);
+  if (workspace_bytes < S.total) return CTR_E_NOMEM;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (rocblas_set_stream(t->blas, st) != rocblas_status_success) return CTR_E_DEVICE;
+  if (!forward(t, replica, d_pooled, batch, (char*)d_workspace, S, d_logits, st)) return CTR_E_DEVICE;
+  return launch_status();
+}
+
+int ctr_mlp_step(ctr_mlp* t, uint32_t replica, const float* d_pooled, const float* d_labels, uint32_t batch,
+                 float* d_grad_pooled, float* d_loss, void* d_workspace, size_t workspace_bytes, uint32_t mode,
+                 void* hip_stream) {
+  if (!t || !d_pooled || !d_labels || !d_grad_pooled || !d_loss || !d_workspace) return CTR_E_INVAL;
+  if (replica >= t->cfg.n_replicas || batch == 0 || batch % 8 != 0) return CTR_E_INVAL;
+  if (mode != CTR_STEP_LOCAL && mode != CTR_STEP_MERGE_PENDING) return CTR_E_INVAL;
+  if (!t->cfg.kstep && mode != CTR_STEP_LOCAL) return CTR_E_INVAL;
+  if (((uintptr_t)d_workspace & 255) != 0) return CTR_E_INVAL;
+  WsLayout S;
+  ws_layout(&t->cfg, t->L, batch, &S);
+  if (workspace_bytes < S.total) return CTR_E_NOMEM;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (rocblas_set_stream(t->blas, st) != rocblas_status_success) return CTR_E_DEVICE;
+
+  const MlpLayout& L = t->L;
+  char* ws = (char*)d_workspace;
+  const u32 B = batch;
+  float* logits = (float*)(ws + S.off_logits);
+  float* dlogit = (float*)(ws + S.off_dlogit);
+  float* grads = (float*)(ws + S.off_grads);
+  float* partial = (float*)(ws + S.off_partial);
+  float* da = (float*)(ws + S.off_da);
+  const bf16_t* PB = t->pb + (u64)replica * t->M.stride;
+
+  if (!forward(t, replica, d_pooled, B, ws, S, logits, st)) return CTR_E_DEVICE;
+  hipLaunchKernelGGL(k_bce, dim3(1), dim3(BLOCK), 0, st, logits, d_labels, B, dlogit, d_loss);
+
+  // output layer: weight and bias gradients, then back through the last ReLU
+  const u32 lo = L.n_layers - 1;
+  const u32 Hl = L.in[lo];
+  const bf16_t* a_last = (const bf16_t*)(ws + S.off_act[lo - 1]);
+  hipLaunchKernelGGL(k_colsum_partial, dim3((Hl + 31) / 32, COLSUM_SLICES), dim3(BLOCK), 0, st, a_last, dlogit, B, Hl,
+                     partial);
+  hipLaunchKernelGGL(k_colsum_final, dim3(blocks_for(Hl)), dim3(BLOCK), 0, st, partial, Hl, grads + L.w_off[lo]);
+  hipLaunchKernelGGL(k_sum_f32, dim3(1), dim3(BLOCK), 0, st, dlogit, B, grads + L.w_off[lo] + Hl);
+  bf16_t* dz = (bf16_t*)(ws + S.off_dz[0]);
+  bf16_t* dz_next = (bf16_t*)(ws + S.off_dz[1]);
+  {
+    const u64 n = (u64)B * Hl;
+    hipLaunchKernelGGL(k_out_backward_dz, dim3(blocks_for(n)), dim3(BLOCK), 0, st, a_last, dlogit, PB + L.w_off[lo],
+                       Hl, n, dz);
+  }
+  // hidden layers, last to first
+  for (int l = (int)lo - 1; l >= 0; --l) {
+    const int i = (int)L.in[l], o = (int)L.out[l];
+    const bf16_t* h_prev = l == 0 ? (const bf16_t*)(ws + S.off_h0) : (const bf16_t*)(ws + S.off_act[l - 1]);
+    // dW[i x o] = H_prev^T[i x B] dZ[B x o]
+    if (!gemm(t, rocblas_operation_none, rocblas_operation_transpose, o, i, (int)B, dz, o, h_prev, i,
+              grads + L.w_off[l], o))
+      return CTR_E_DEVICE;
+    hipLaunchKernelGGL(k_colsum_partial, dim3((o + 31) / 32, COLSUM_SLICES), dim3(BLOCK), 0, st, dz, (const float*)nullptr,
+                       B, (u32)o, partial);
+    hipLaunchKernelGGL(k_colsum_final, dim3(blocks_for(o)), dim3(BLOCK), 0, st, partial, (u32)o,
+                       grads + L.w_off[l] + (u64)i * o);
+    // dH_prev[B x i] = dZ[B x o] W^T[o x i]; for the first layer this is the gradient of the pooled input
+    float* dst = l == 0 ? d_grad_pooled : da;
+    if (!gemm(t, rocblas_operation_transpose, rocblas_operation_none, i, (int)B, o, PB + L.w_off[l], o, dz, o, dst, i))
+      return CTR_E_DEVICE;
+    if (l > 0) {
+      const u64 n = (u64)B * i;
+      hipLaunchKernelGGL(k_relu_bwd_bf16, dim3(blocks_for(n / 4)), dim3(BLOCK), 0, st, da, h_prev, n, dz_next);
+      std::swap(dz, dz_next);
+    }
+  }
+  // dense optimizer
+  const u32 amode = mode == CTR_STEP_MERGE_PENDING ? 2u : (t->cfg.kstep ? 1u : 0u);
+  hipLaunchKernelGGL(k_dense_adam, dim3(blocks_for(L.n_params)), dim3(BLOCK), 0, st,
+                     t->params + (u64)replica * t->M.stride, t->m + (u64)replica * t->M.stride,
+                     t->v + (u64)replica * t->M.stride, t->vhat, grads, t->pb + (u64)replica * t->M.stride,
+                     L.n_params, (double)t->cfg.beta1, (double)t->cfg.beta2, (double)t->cfg.lr, amode);
+  if (mode == CTR_STEP_MERGE_PENDING) t->pend_mask |= 1u << replica;
+  return launch_status();
+}
+
+int ctr_mlp_kstep_merge(ctr_mlp* t, void* hip_stream) {
+  if (!t || !t->cfg.kstep) return CTR_E_INVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  hipLaunchKernelGGL(k_dense_merge, dim3(blocks_for(t->L.n_params)), dim3(BLOCK), 0, st, t->params, t->m, t->v,
+                     t->vhat, t->pb, t->L.n_params, t->M.stride, t->cfg.n_replicas, t->pend_mask,
+                     (double)t->cfg.lr);
+  t->pend_mask = 0;
+  return launch_status();
+}
+
+int ctr_mlp_export(ctr_mlp* t, uint32_t replica, float* h_params, float* h_m, float* h_v, float* h_vhat,
+                   void* hip_stream) {
+  if (!t || replica >= t->cfg.n_replicas) return CTR_E_INVAL;
+  if (h_vhat && !t->vhat) return CTR_E_INVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const size_t nb = (size_t)t->L.n_params * sizeof(float);
+  const u64 off = (u64)replica * t->M.stride;
+  bool ok = true;
+  if (h_params) ok = ok && hipMemcpyAsync(h_params, t->params + off, nb, hipMemcpyDeviceToHost, st) == hipSuccess;
+  if (h_m) ok = ok && hipMemcpyAsync(h_m, t->m + off, nb, hipMemcpyDeviceToHost, st) == hipSuccess;
+  if (h_v) ok = ok && hipMemcpyAsync(h_v, t->v + off, nb, hipMemcpyDeviceToHost, st) == hipSuccess;
+  if (h_vhat) ok = ok && hipMemcpyAsync(h_vhat, t->vhat, nb, hipMemcpyDeviceToHost, st) == hipSuccess;
+  ok = ok && hipStreamSynchronize(st) == hipSuccess;
+  return ok ? CTR_OK : CTR_E_DEVICE;
+}
+
+}  // extern "C"

@@ -19,12 +19,31 @@ def _cfg(**kw):
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "ctr_sparse.h")).read()
-    declared = set(re.findall(r"^\s*(?:int|size_t)\s+(ctr_\w+)\s*\(", header, re.M))
-    assert declared == set(B.EXPORTED)
+    from paper_2201_05500_amd import binding_mlp as BM
     lib = C.CDLL(B.LIB_PATH)
-    for name in declared:
-        assert hasattr(lib, name), name
+    for hdr, exported in (("ctr_sparse.h", B.EXPORTED), ("ctr_mlp.h", BM.EXPORTED)):
+        header = open(os.path.join(ROOT, "include", hdr)).read()
+        declared = set(re.findall(r"^\s*(?:int|size_t)\s+(ctr_\w+)\s*\(", header, re.M))
+        assert declared == set(exported), hdr
+        for name in declared:
+            assert hasattr(lib, name), name
+
+
+def test_mlp_host_logic():
+    from paper_2201_05500_amd import binding_mlp as BM
+    L = BM.lib()
+    cfg = BM.make_config(19200, [1024, 512, 256])
+    n = 19200 * 1024 + 1024 + 1024 * 512 + 512 + 512 * 256 + 256 + 256 + 1
+    assert L.ctr_mlp_n_params(C.byref(cfg)) == n == 20318209
+    assert L.ctr_mlp_bytes(C.byref(cfg)) >= n * (4 * 3 + 2)
+    assert L.ctr_mlp_workspace_bytes(C.byref(cfg), 16384) >= 16384 * 19200 * 2
+    assert L.ctr_mlp_workspace_bytes(C.byref(cfg), 100) == 0          # batch must be a multiple of 8
+    for bad in (BM.make_config(100, [8]), BM.make_config(64, []), BM.make_config(64, [12]),
+                BM.make_config(64, [8], n_replicas=2), BM.make_config(64, [8], lr=0.0)):
+        assert L.ctr_mlp_bytes(C.byref(bad)) == 0
+    out = C.c_void_p()
+    assert L.ctr_mlp_create(C.byref(BM.make_config(64, [12])), 256, 1 << 30, None, C.byref(out)) == B.CTR_E_INVAL
+    assert L.ctr_mlp_destroy(None) == B.CTR_E_INVAL
 
 
 def test_config_struct_matches_header_layout():

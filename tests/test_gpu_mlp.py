@@ -1,0 +1,112 @@
+"""GPU parity of the dense tower against the numpy oracle.
+
+Tolerances (bf16 operands, fp32 accumulation on the matrix cores against exact products in the
+oracle): a product of K terms accumulated in fp32 differs from the exact one by about 1e-6 of the sum
+of magnitudes; where such a value is then rounded to bf16 (activations, hidden gradients) it may
+land on the neighbouring bf16 value (2^-8 relative), and a pre-activation within that error of zero
+may flip its ReLU mask.  So: logits, loss, gradients and updated parameters are compared with
+|gpu - ref| <= atol + rtol |ref| where atol is 2e-3 of the tensor's RMS and rtol 1e-2, allowing at
+most 1e-4 of the elements outside it, plus a norm-wise bound of 2e-3 on every tensor.
+"""
+import numpy as np
+import pytest
+
+from oracle import mlp_oracle as M
+
+pytestmark = pytest.mark.gpu
+
+
+def close_enough(gpu, ref, what, rtol=1e-2, frac_atol=2e-3, norm_tol=2e-3, outliers=1e-4):
+    gpu = np.asarray(gpu, np.float64).reshape(-1)
+    ref = np.asarray(ref, np.float64).reshape(-1)
+    assert gpu.shape == ref.shape, what
+    rms = np.sqrt(np.mean(ref * ref)) + 1e-30
+    bad = np.abs(gpu - ref) > frac_atol * rms + rtol * np.abs(ref)
+    assert bad.mean() <= outliers, "%s: %d of %d elements off" % (what, int(bad.sum()), bad.size)
+    nerr = np.linalg.norm(gpu - ref) / (np.linalg.norm(ref) + 1e-30)
+    assert nerr <= norm_tol, "%s: norm-wise error %.3g" % (what, nerr)
+
+
+def _pair(in_dim, hidden, seed=3, **kw):
+    from paper_2201_05500_amd.binding_mlp import CtrMlp
+    return (CtrMlp(in_dim, hidden, init_seed=seed, **kw), M.MlpOracle(in_dim, hidden, init_seed=seed, **kw))
+
+
+def _batch(rng, B, in_dim, scale=0.05, p=0.2):
+    import torch
+    pooled = (scale * rng.standard_normal((B, in_dim))).astype(np.float32)
+    labels = (rng.random(B) < p).astype(np.float32)
+    return pooled, labels, torch.from_numpy(pooled).cuda(), torch.from_numpy(labels).cuda()
+
+
+def test_initial_parameters_are_bit_identical():
+    g, o = _pair(64, [32, 16])
+    e = g.export()
+    assert np.array_equal(e["params"], o.params[0])
+    assert not e["m"].any() and np.all(e["v"] == np.float32(1e-8))
+
+
+@pytest.mark.parametrize("in_dim,hidden,B", [(64, [32, 16], 64), (192, [128, 64, 32], 256), (512, [256], 1024)])
+def test_steps_match_the_oracle(in_dim, hidden, B):
+    rng = np.random.default_rng(in_dim)
+    g, o = _pair(in_dim, hidden)
+    for s in range(3):
+        pooled, labels, dp, dl = _batch(rng, B, in_dim)
+        st, logits = g.forward(0, dp)
+        assert st == 0
+        close_enough(logits.cpu().numpy(), o.forward(0, pooled), "logits step %d" % s, norm_tol=1e-3)
+        st, loss, gp = g.step(0, dp, dl)
+        assert st == 0
+        oloss, ogp = o.step(0, pooled, labels)
+        assert abs(float(loss.cpu()[0]) - float(oloss)) <= 1e-4 * max(1.0, abs(float(oloss)))
+        close_enough(gp.cpu().numpy(), ogp, "grad of pooled step %d" % s)
+        e = g.export()
+        close_enough(e["m"], o.m[0], "first moment step %d" % s)
+        close_enough(e["v"], o.v[0], "second moment step %d" % s, rtol=2e-2)
+        close_enough(e["params"], o.params[0], "parameters step %d" % s, rtol=1e-3, norm_tol=1e-3)
+
+
+def test_kstep_dense_adam_and_merge():
+    """Algorithm 2 on the dense parameters: W = 3 replicas, k = 2."""
+    from paper_2201_05500_amd.binding import CTR_STEP_LOCAL, CTR_STEP_MERGE_PENDING
+    rng = np.random.default_rng(9)
+    in_dim, hidden, B, W, k = 64, [32, 16], 64, 3, 2
+    g, o = _pair(in_dim, hidden, n_replicas=W, kstep=True)
+    for s in range(1, 5):
+        mode = CTR_STEP_MERGE_PENDING if s % k == 0 else CTR_STEP_LOCAL
+        for j in range(W):
+            pooled, labels, dp, dl = _batch(rng, B, in_dim)
+            st, loss, gp = g.step(j, dp, dl, mode=mode)
+            assert st == 0
+            o.step(j, pooled, labels, mode)
+        if mode == CTR_STEP_MERGE_PENDING:
+            assert g.kstep_merge() == 0
+            o.kstep_merge()
+            es = [g.export(j) for j in range(W)]
+            for j in range(1, W):
+                assert np.array_equal(es[0]["params"], es[j]["params"])     # zero consensus error after a merge
+        for j in range(W):
+            e = g.export(j)
+            close_enough(e["params"], o.params[j], "params replica %d step %d" % (j, s), rtol=1e-3, norm_tol=1e-3)
+            close_enough(e["vhat"], o.vhat, "shared denominator step %d" % s, rtol=2e-2)
+
+
+def test_argument_checks():
+    from paper_2201_05500_amd import binding as B
+    from paper_2201_05500_amd import binding_mlp as BM
+    import ctypes as C
+    import torch
+    g, _ = _pair(64, [32])
+    x = torch.zeros((16, 64), device="cuda")
+    y = torch.zeros(16, device="cuda")
+    assert g.step(1, x, y)[0] == B.CTR_E_INVAL                       # replica out of range
+    assert g.step(0, x, y, mode=B.CTR_STEP_MERGE_PENDING)[0] == B.CTR_E_INVAL
+    assert g.kstep_merge() == B.CTR_E_INVAL
+    g.reserve(16)
+    st = BM.lib().ctr_mlp_step(g._handle, 0, x.data_ptr(), y.data_ptr(), 12, x.data_ptr(), y.data_ptr(),
+                               g._ws.data_ptr(), g.ws_bytes, 0, g.stream)
+    assert st == B.CTR_E_INVAL                                       # batch not a multiple of 8
+    st = BM.lib().ctr_mlp_step(g._handle, 0, x.data_ptr(), y.data_ptr(), 16, x.data_ptr(), y.data_ptr(),
+                               g._ws.data_ptr(), 64, 0, g.stream)
+    assert st == B.CTR_E_NOMEM
+    torch.cuda.synchronize()
