@@ -74,7 +74,19 @@ WORKLOADS: Dict[str, Workload] = {
     "large": Workload(3, "large", 1 << 24, 64, 32768, 300, "poisson4", 1.0, 1 << 24, 48, steps=50),
     "kstep": Workload(4, "kstep", 1 << 22, 16, 4096, 100, "poisson3_min1", 1.05, 1 << 22, 40,
                       n_replicas=8, k_step=4, steps=40),
+    # the full training step: the large table under a dense tower 19200-1024-512-256-1, batch 16384
+    "full": Workload(5, "full", 1 << 24, 64, 16384, 300, "poisson4", 1.0, 1 << 24, 48, steps=50),
 }
+FULL_STEP_HIDDEN = (1024, 512, 256)
+FULL_STEP_CLICK_RATE = 0.05
+
+
+def make_labels(w: Workload, step: int, device="cpu", base_seed: int = 20220105) -> torch.Tensor:
+    """Bernoulli(FULL_STEP_CLICK_RATE) click labels, float32 [B]."""
+    dev = torch.device(device)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(batch_seed(w, step, 7, base_seed))
+    return (torch.rand(w.batch, generator=gen, device=dev) < FULL_STEP_CLICK_RATE).to(torch.float32)
 
 
 def scaled(w: Workload, **kw) -> Workload:
