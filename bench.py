@@ -6,7 +6,10 @@ insert-on-miss, row gather + per-slot sum, grouping of occurrences by row) follo
 ctr_push_adam (gradient segment-reduce fused with sparse Adam).  All inputs of all steps are
 generated on the device before the timed region starts.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload large|mid|tiny|kstep]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload large|mid|tiny|kstep|full]
+
+With --workload full a step is the whole training step of Algorithm 1: pull, the dense tower
+(forward, loss, backward, dense Adam) on the pooled embeddings, push of the tower's gradient.
 """
 import argparse
 import json
@@ -19,6 +22,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix-core rate
 
 # HBM traffic of the dominant kernel per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this script (profiles/large_step_kernels.txt), each counter scaled by what it reads for a 1 GiB
@@ -47,14 +51,59 @@ def algorithmic_bytes_push_kernel(L, G, U, D, kstep, n_state=3):
     return 4 * L + 4 * D * G + 2 * n_state * 4 * D * U + (4 * D * U if kstep else 0)
 
 
-def algorithmic_bytes_pool_kernel(L, G, U, D):
+def algorithmic_bytes_pool_kernel(L, G, U, D, out_bytes=4):
     """The pool kernel's share: offsets and occurrence map read, compulsory row reads, pooled write."""
-    return 4 * (G + 1) + 4 * L + 4 * D * U + 4 * D * G
+    return 4 * (G + 1) + 4 * L + 4 * D * U + out_bytes * D * G
+
+
+def tower_flops(batch, in_dim, hidden):
+    """Multiply-adds x 2 of one tower step: every layer's forward product, weight-gradient product
+    and input-gradient product (the first layer's input gradient is the push's input)."""
+    dims = [in_dim] + list(hidden) + [1]
+    return 3 * 2 * batch * sum(dims[i] * dims[i + 1] for i in range(len(dims) - 1))
+
+
+def cpu_baseline_full(w, WL, seconds_hint=20.0):
+    """Table oracle (one thread) and tower oracle (numpy, the BLAS's threads) chained on a bounded sample."""
+    import numpy as np
+    from oracle import ctr_oracle as O
+    from oracle import mlp_oracle as M
+    ws = WL.scaled(w, batch=max(8, w.batch // 16))
+    in_dim = ws.slots * ws.dim
+    ot = O.OracleTable(ws.capacity_rows, ws.dim, n_replicas=1, lr=ws.lr, beta1=ws.beta1, beta2=ws.beta2,
+                       eps=ws.eps, init_seed=1, init_std=ws.init_std)
+    om = M.MlpOracle(in_dim, WL.FULL_STEP_HIDDEN, lr=ws.lr, beta1=ws.beta1, beta2=ws.beta2, eps=ws.eps, init_seed=3)
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([int(i.get("num_threads", 1)) for i in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    n_steps, keys_done, t_spent = 0, 0, 0.0
+    while t_spent < seconds_hint / 2 and n_steps < 4:
+        bn = WL.as_numpy(WL.make_batch(ws, n_steps, with_grad=False))
+        labels = WL.make_labels(ws, n_steps).numpy()
+        t0 = time.perf_counter()
+        st, pooled = ot.pull_pool(0, bn["keys"], bn["offsets"])
+        assert st == 0
+        _, gp = om.step(0, np.asarray(pooled, np.float32).reshape(ws.batch, in_dim), labels)
+        assert ot.push_adam(0, gp.reshape(ws.n_segments, ws.dim)) == 0
+        t_spent += time.perf_counter() - t0
+        keys_done += bn["keys"].size
+        n_steps += 1
+    ot.close()
+    return {
+        "value": keys_done / t_spent, "unit": "keys/s", "cores": threads, "kind": "oracle",
+        "sample": "%d full step(s) (table oracle on one thread, tower oracle in numpy float64 on %d BLAS threads) of "
+                  "the first %d of %d samples per batch (%d key occurrences), table starting empty, %.1f s" % (
+                      n_steps, threads, ws.batch, w.batch, keys_done, t_spent),
+    }
 
 
 def cpu_baseline(w, WL, seconds_hint=20.0):
     """The oracle as it stands, one thread, on a bounded sample of the same workload."""
     from oracle import ctr_oracle as O
+    if w.name == "full":
+        return cpu_baseline_full(w, WL, seconds_hint)
     frac = {"large": 8, "mid": 1, "tiny": 1, "kstep": 1}.get(w.name, 1)
     ws = WL.scaled(w, batch=max(1, w.batch // frac))
     ot = O.OracleTable(ws.capacity_rows, ws.dim, n_replicas=1, lr=ws.lr, beta1=ws.beta1, beta2=ws.beta2,
@@ -105,6 +154,10 @@ def main():
     dev = "cuda:0"
     w = WL.WORKLOADS[args.workload]
     kstep = w.k_step > 0
+    full = w.name == "full"
+    if full and args.variant != "alg2":
+        print("bench.py: the full step is timed with Algorithm 2's update only", file=sys.stderr)
+        sys.exit(2)
     if (args.variant == "prose") != kstep and args.variant != "alg2":
         print("bench.py: --variant prose needs the kstep workload, adagrad/kingma a single-table one", file=sys.stderr)
         sys.exit(2)
@@ -125,12 +178,25 @@ def main():
     max_keys = 1
     for s in range(total_steps):
         for j in range(reps):
-            b = WL.make_batch(w, s % w.steps, replica=j, device=dev)   # the configuration's own step count, then repeat
+            b = WL.make_batch(w, s % w.steps, replica=j, device=dev, with_grad=not full)   # the configuration's own step count, then repeat
+            if full:
+                b["labels"] = WL.make_labels(w, s % w.steps, device=dev)
             batches.append(b)
             max_keys = max(max_keys, b["keys"].numel())
     G = w.n_segments
     table.reserve(max_keys, G)
     pooled = torch.empty((G, w.dim), dtype=torch.float32, device=dev)
+    tower = None
+    if full:
+        from paper_2201_05500_amd.binding_mlp import CtrMlp
+        in_dim = w.slots * w.dim
+        tower = CtrMlp(in_dim, WL.FULL_STEP_HIDDEN, lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, init_seed=3,
+                       device=dev)
+        tower.reserve(w.batch)
+        grad_pooled = torch.empty((G, w.dim), dtype=torch.float32, device=dev)
+        pooled_bf16 = torch.empty((G, w.dim), dtype=torch.bfloat16, device=dev)
+        loss = torch.empty(1, dtype=torch.float32, device=dev)
+        tower_events = []
     torch.cuda.synchronize()
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
@@ -146,10 +212,24 @@ def main():
             mode = CTR_STEP_MERGE_PENDING
         for j in range(reps):
             b = batches[s * reps + j]
-            st, h, _ = table.pull_pool(j, b["keys"], b["offsets"], pooled)
+            if full:   # the tower's products take bf16: the pull writes that copy itself
+                st, h, _, _ = table.pull_pool_bf16(j, b["keys"], b["offsets"], pooled_bf16)
+            else:
+                st, h, _ = table.pull_pool(j, b["keys"], b["offsets"], pooled)
             if st != CTR_OK:
                 raise RuntimeError("ctr_pull_pool: %d" % st)
-            st = table.push_adam(j, h, b["grad"], mode)
+            grad = None if full else b["grad"]
+            if full:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                st, _, _ = tower.step(0, pooled_bf16.view(w.batch, in_dim), b["labels"],
+                                      grad_pooled.view(w.batch, in_dim), loss=loss)
+                e1.record()
+                tower_events.append((e0, e1))
+                if st != CTR_OK:
+                    raise RuntimeError("ctr_mlp_step: %d" % st)
+                grad = grad_pooled
+            st = table.push_adam(j, h, grad, mode)
             if st != CTR_OK:
                 raise RuntimeError("ctr_push_adam: %d" % st)
         if merge_now:
@@ -164,6 +244,8 @@ def main():
     if table.last_status() != CTR_OK:
         raise RuntimeError("device status after warmup")
     table.profile_read()                       # drop the warmup records
+    if full:
+        tower_events.clear()
     rows_before = table.n_rows
 
     torch.cuda.synchronize()
@@ -193,7 +275,7 @@ def main():
     stage_ms = {n: (ms / c if c else 0.0) for n, (ms, c) in stages.items()}
     kernel_bytes = {
         "push": algorithmic_bytes_push_kernel(L_mean, G, U_mean, D, shared_den, n_state),
-        "pool": algorithmic_bytes_pool_kernel(L_mean, G, U_mean, D),
+        "pool": algorithmic_bytes_pool_kernel(L_mean, G, U_mean, D, 2 if full else 4),
     }
     dominant = max(kernel_bytes, key=lambda n: stage_ms[n])
     achieved = kernel_bytes[dominant] / (stage_ms[dominant] * 1e-3) / 1e9 if stage_ms[dominant] else 0.0
@@ -236,6 +318,21 @@ def main():
             if args.variant == "alg2" else None,
         },
     }
+    if full:
+        tower_ms = sum(a.elapsed_time(b) for a, b in tower_events) / len(tower_events)
+        fl = tower_flops(w.batch, in_dim, WL.FULL_STEP_HIDDEN)
+        out["metric"] = "full training step (pull, dense tower, push): " + out["metric"]
+        out["dtype"] = "f32 table, bf16 x bf16 -> f32 tower products"
+        out["samples_per_s"] = w.batch * K / elapsed
+        out["final_loss"] = float(loss.cpu()[0])
+        out["stage_ms"]["tower"] = tower_ms
+        out["config"]["tower"] = "%d-%s-1, click rate %g" % (in_dim, "-".join(str(h) for h in WL.FULL_STEP_HIDDEN),
+                                                             WL.FULL_STEP_CLICK_RATE)
+        out["roofline_tower"] = {
+            "bound": "mfma", "kernel": "ctr_mlp_step (all products and element-wise kernels of one tower step)",
+            "achieved": fl / (tower_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": fl / (tower_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+        }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, WL)
     print(json.dumps(out))

@@ -71,6 +71,15 @@ int ctr_mlp_step(ctr_mlp* m, uint32_t replica, const float* d_pooled, const floa
 int ctr_mlp_forward(ctr_mlp* m, uint32_t replica, const float* d_pooled, uint32_t batch, float* d_logits,
                     void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The same two calls for an input that is already bfloat16 (d_pooled_bf16[batch * in_dim], the
+ * output of ctr_pull_pool_bf16; read in place, must stay unchanged until the step's work has
+ * run).  The results equal those of the fp32 calls on an input that rounds to these bf16 values. */
+int ctr_mlp_step_bf16(ctr_mlp* m, uint32_t replica, const uint16_t* d_pooled_bf16, const float* d_labels,
+                      uint32_t batch, float* d_grad_pooled, float* d_loss, void* d_workspace,
+                      size_t workspace_bytes, uint32_t mode, void* hip_stream);
+int ctr_mlp_forward_bf16(ctr_mlp* m, uint32_t replica, const uint16_t* d_pooled_bf16, uint32_t batch,
+                         float* d_logits, void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Algorithm 2's global-averaging branch over all dense parameters of the W replicas:
  * shared v = mean_j v_j; x_i = mean_j (x_j - [merge step pending in j] lr m_j / sqrt(shared v)). */
 int ctr_mlp_kstep_merge(ctr_mlp* m, void* hip_stream);

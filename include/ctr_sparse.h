@@ -138,6 +138,18 @@ int ctr_pull_pool(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint64
                   void* d_workspace, size_t workspace_bytes, ctr_batch** batch_out,
                   void* hip_stream);
 
+/* The same pull with the pooled embeddings also (or only) written as bfloat16, the operand type
+ * of the dense tower's matrix products (ctr_mlp_step_bf16), so that no separate conversion pass
+ * over the pooled tensor is needed between pull and train_mini-batch (Algorithm 1).
+ *   d_pooled_bf16[n_seg * D]  device, out, 8-byte aligned: the fp32 pooled value rounded to bf16
+ *                             (nearest-even), bit-identical to converting d_pooled afterwards
+ *   d_pooled                  device, out, may be NULL when only the bf16 copy is wanted
+ * Everything else as ctr_pull_pool. */
+int ctr_pull_pool_bf16(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint64_t n_keys,
+                       const uint32_t* d_offsets, uint32_t n_segments, float* d_pooled,
+                       uint16_t* d_pooled_bf16, void* d_workspace, size_t workspace_bytes,
+                       ctr_batch** batch_out, void* hip_stream);
+
 /* Push (Algorithm 1: push_parameters_updates_back; Algorithm 2: the m, v and
  * model lines).  The gradient of sum pooling hands grad_pooled[g, :] to every
  * key occurrence of segment g; per distinct key the occurrences' gradients are

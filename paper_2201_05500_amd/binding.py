@@ -24,7 +24,7 @@ STAGE_NAMES = ("probe", "insert", "pool", "sort", "push", "fixup", "merge")
 
 EXPORTED = (
     "ctr_table_bytes", "ctr_workspace_bytes", "ctr_table_create", "ctr_table_destroy",
-    "ctr_pull_pool", "ctr_push_adam", "ctr_kstep_merge", "ctr_table_load", "ctr_table_collect",
+    "ctr_pull_pool", "ctr_pull_pool_bf16", "ctr_push_adam", "ctr_kstep_merge", "ctr_table_load", "ctr_table_collect",
     "ctr_table_size", "ctr_table_export",
     "ctr_batch_export", "ctr_batch_stats", "ctr_last_status", "ctr_profile_enable",
     "ctr_profile_read",
@@ -72,6 +72,8 @@ def lib():
     L.ctr_table_destroy.argtypes = [vp]
     L.ctr_pull_pool.restype = ci
     L.ctr_pull_pool.argtypes = [vp, u32, vp, u64, vp, u32, vp, vp, sz, C.POINTER(vp), vp]
+    L.ctr_pull_pool_bf16.restype = ci
+    L.ctr_pull_pool_bf16.argtypes = [vp, u32, vp, u64, vp, u32, vp, vp, vp, sz, C.POINTER(vp), vp]
     L.ctr_push_adam.restype = ci
     L.ctr_push_adam.argtypes = [vp, u32, vp, vp, u32, vp]
     L.ctr_kstep_merge.restype = ci
@@ -122,6 +124,14 @@ def ctr_pull_pool(table, replica, d_keys, n_keys, d_offsets, n_segments, d_poole
     out = C.c_void_p()
     st = lib().ctr_pull_pool(table, replica, d_keys, n_keys, d_offsets, n_segments, d_pooled, d_ws,
                              ws_bytes, C.byref(out), stream)
+    return st, out.value
+
+
+def ctr_pull_pool_bf16(table, replica, d_keys, n_keys, d_offsets, n_segments, d_pooled, d_pooled_bf16, d_ws,
+                       ws_bytes, stream):
+    out = C.c_void_p()
+    st = lib().ctr_pull_pool_bf16(table, replica, d_keys, n_keys, d_offsets, n_segments, d_pooled, d_pooled_bf16,
+                                  d_ws, ws_bytes, C.byref(out), stream)
     return st, out.value
 
 
@@ -218,6 +228,23 @@ class CtrTable:
                                   offsets.data_ptr(), n_seg, pooled.data_ptr() if n_seg else None,
                                   self._ws.data_ptr(), self.ws_bytes, self.stream)
         return st, batch, pooled
+
+    def pull_pool_bf16(self, replica, keys, offsets, pooled_bf16=None, pooled=None, want_f32=False):
+        """As pull_pool with the pooled embeddings as bfloat16 [G, D] (and as fp32 too if `pooled` is given or
+        want_f32).  Returns (status, batch handle, pooled_bf16, pooled or None)."""
+        torch = self._torch
+        n_keys, n_seg = keys.numel(), offsets.numel() - 1
+        self.reserve(max(n_keys, 1), n_seg)
+        if pooled_bf16 is None:
+            pooled_bf16 = torch.empty((n_seg, self.D), dtype=torch.bfloat16, device=self.device)
+        if pooled is None and want_f32:
+            pooled = torch.empty((n_seg, self.D), dtype=torch.float32, device=self.device)
+        st, batch = ctr_pull_pool_bf16(self._handle, replica, keys.data_ptr() if n_keys else None, n_keys,
+                                       offsets.data_ptr(), n_seg,
+                                       pooled.data_ptr() if (pooled is not None and n_seg) else None,
+                                       pooled_bf16.data_ptr() if n_seg else None, self._ws.data_ptr(), self.ws_bytes,
+                                       self.stream)
+        return st, batch, pooled_bf16, pooled
 
     def push_adam(self, replica, batch, grad, mode=CTR_STEP_LOCAL):
         return ctr_push_adam(self._handle, replica, batch, grad.data_ptr() if grad.numel() else None,

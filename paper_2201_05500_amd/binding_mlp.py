@@ -9,7 +9,7 @@ from .binding import CTR_OK, CTR_STEP_LOCAL, lib as _base_lib
 
 CTR_MLP_MAX_HIDDEN = 6
 EXPORTED = ("ctr_mlp_bytes", "ctr_mlp_workspace_bytes", "ctr_mlp_create", "ctr_mlp_destroy", "ctr_mlp_step",
-            "ctr_mlp_forward", "ctr_mlp_kstep_merge", "ctr_mlp_n_params", "ctr_mlp_export")
+            "ctr_mlp_forward", "ctr_mlp_step_bf16", "ctr_mlp_forward_bf16", "ctr_mlp_kstep_merge", "ctr_mlp_n_params", "ctr_mlp_export")
 
 
 class ctr_mlp_config(C.Structure):
@@ -50,6 +50,10 @@ def lib():
         L.ctr_mlp_step.argtypes = [vp, u32, vp, vp, u32, vp, vp, vp, sz, u32, vp]
         L.ctr_mlp_forward.restype = ci
         L.ctr_mlp_forward.argtypes = [vp, u32, vp, u32, vp, vp, sz, vp]
+        L.ctr_mlp_step_bf16.restype = ci
+        L.ctr_mlp_step_bf16.argtypes = L.ctr_mlp_step.argtypes
+        L.ctr_mlp_forward_bf16.restype = ci
+        L.ctr_mlp_forward_bf16.argtypes = L.ctr_mlp_forward.argtypes
         L.ctr_mlp_kstep_merge.restype = ci
         L.ctr_mlp_kstep_merge.argtypes = [vp, vp]
         L.ctr_mlp_export.restype = ci
@@ -112,16 +116,18 @@ class CtrMlp:
         except Exception:
             pass
 
-    def step(self, replica, pooled, labels, grad_pooled=None, mode=CTR_STEP_LOCAL):
-        """pooled f32 [B, in], labels f32 [B] (device).  Returns (status, loss tensor[1], grad_pooled)."""
+    def step(self, replica, pooled, labels, grad_pooled=None, mode=CTR_STEP_LOCAL, loss=None):
+        """pooled f32 or bf16 [B, in], labels f32 [B] (device).  Returns (status, loss tensor[1], grad_pooled f32)."""
         torch = self._torch
         B = pooled.shape[0]
         self.reserve(B)
         if grad_pooled is None:
-            grad_pooled = torch.empty_like(pooled)
-        loss = torch.empty(1, dtype=torch.float32, device=self.device)
-        st = lib().ctr_mlp_step(self._handle, replica, pooled.data_ptr(), labels.data_ptr(), B, grad_pooled.data_ptr(),
-                                loss.data_ptr(), self._ws.data_ptr(), self.ws_bytes, mode, self.stream)
+            grad_pooled = torch.empty(pooled.shape, dtype=torch.float32, device=self.device)
+        if loss is None:
+            loss = torch.empty(1, dtype=torch.float32, device=self.device)
+        fn = lib().ctr_mlp_step_bf16 if pooled.dtype == torch.bfloat16 else lib().ctr_mlp_step
+        st = fn(self._handle, replica, pooled.data_ptr(), labels.data_ptr(), B, grad_pooled.data_ptr(),
+                loss.data_ptr(), self._ws.data_ptr(), self.ws_bytes, mode, self.stream)
         return st, loss, grad_pooled
 
     def forward(self, replica, pooled):
@@ -129,8 +135,9 @@ class CtrMlp:
         B = pooled.shape[0]
         self.reserve(B)
         logits = torch.empty(B, dtype=torch.float32, device=self.device)
-        st = lib().ctr_mlp_forward(self._handle, replica, pooled.data_ptr(), B, logits.data_ptr(),
-                                   self._ws.data_ptr(), self.ws_bytes, self.stream)
+        fn = lib().ctr_mlp_forward_bf16 if pooled.dtype == torch.bfloat16 else lib().ctr_mlp_forward
+        st = fn(self._handle, replica, pooled.data_ptr(), B, logits.data_ptr(), self._ws.data_ptr(), self.ws_bytes,
+                self.stream)
         return st, logits
 
     def kstep_merge(self):

@@ -112,4 +112,17 @@ struct d4 {
 __device__ __forceinline__ f4 ldg4(const float* p) { return *reinterpret_cast<const f4*>(p); }
 __device__ __forceinline__ void stg4(float* p, f4 v) { *reinterpret_cast<f4*>(p) = v; }
 
+// bfloat16 as its 16-bit pattern; rounding from fp32 is nearest-even on the bit pattern.
+typedef uint16_t bf16_t;
+__device__ __forceinline__ bf16_t to_bf16(float f) {
+  const u32 u = __float_as_uint(f);
+  return (bf16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+__device__ __forceinline__ float from_bf16(bf16_t h) { return __uint_as_float((u32)h << 16); }
+__device__ __forceinline__ void stg4_bf16(bf16_t* p, f4 v) {
+  ushort4 o;
+  o.x = to_bf16(v.x); o.y = to_bf16(v.y); o.z = to_bf16(v.z); o.w = to_bf16(v.w);
+  *reinterpret_cast<ushort4*>(p) = o;
+}
+
 }  // namespace ctr

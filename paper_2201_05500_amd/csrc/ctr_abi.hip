@@ -326,14 +326,14 @@ int ctr_table_destroy(ctr_table* t) {
   return CTR_OK;
 }
 
-int ctr_pull_pool(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint64_t n_keys,
-                  const uint32_t* d_offsets, uint32_t n_segments, float* d_pooled, void* d_workspace,
-                  size_t workspace_bytes, ctr_batch** batch_out, void* hip_stream) {
+static int pull_pool_impl(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint64_t n_keys,
+                          const uint32_t* d_offsets, uint32_t n_segments, float* d_pooled, bf16_t* d_pooled_bf16,
+                          void* d_workspace, size_t workspace_bytes, ctr_batch** batch_out, void* hip_stream) {
   if (!t || !batch_out || !d_offsets || !d_workspace) return CTR_E_INVAL;
   if (replica >= t->W) return CTR_E_INVAL;
   if (n_keys >= (1ull << 31) || n_segments == 0xFFFFFFFFu) return CTR_E_INVAL;
   if (n_keys > 0 && !d_keys) return CTR_E_INVAL;
-  if (n_segments > 0 && !d_pooled) return CTR_E_INVAL;
+  if (n_segments > 0 && !d_pooled && !d_pooled_bf16) return CTR_E_INVAL;
   if (((uintptr_t)d_workspace & 255) != 0) return CTR_E_INVAL;
   WorkLayout wl;
   work_layout(t->D, n_keys, &wl);
@@ -365,7 +365,7 @@ int ctr_pull_pool(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint64
     const float* vals = t->values + (u64)replica * t->tl.replica_stride;
     const u32 segs_per_block = (BLOCK / t->lpr) * POOL_NS * POOL_ROUNDS;
     LPR_DISPATCH(t->lpr, k_pool, (n_segments + segs_per_block - 1) / segs_per_block, st, t->hdr, occ_row, seg_of,
-                 d_offsets, n_segments, vals, t->D, t->rf, d_pooled);
+                 d_offsets, n_segments, vals, t->D, t->rf, d_pooled, d_pooled_bf16);
   }
   if (n > 0) {
     StageTimer tm(t, CTR_STAGE_SORT, st);
@@ -404,6 +404,22 @@ int ctr_pull_pool(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint64
   t->live = b;
   *batch_out = b;
   return CTR_OK;
+}
+
+int ctr_pull_pool(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint64_t n_keys,
+                  const uint32_t* d_offsets, uint32_t n_segments, float* d_pooled, void* d_workspace,
+                  size_t workspace_bytes, ctr_batch** batch_out, void* hip_stream) {
+  return pull_pool_impl(t, replica, d_keys, n_keys, d_offsets, n_segments, d_pooled, nullptr, d_workspace,
+                        workspace_bytes, batch_out, hip_stream);
+}
+
+int ctr_pull_pool_bf16(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint64_t n_keys,
+                       const uint32_t* d_offsets, uint32_t n_segments, float* d_pooled, uint16_t* d_pooled_bf16,
+                       void* d_workspace, size_t workspace_bytes, ctr_batch** batch_out, void* hip_stream) {
+  if (n_segments > 0 && !d_pooled_bf16) return CTR_E_INVAL;
+  if (((uintptr_t)d_pooled_bf16 & 7) != 0) return CTR_E_INVAL;
+  return pull_pool_impl(t, replica, d_keys, n_keys, d_offsets, n_segments, d_pooled, d_pooled_bf16, d_workspace,
+                        workspace_bytes, batch_out, hip_stream);
 }
 
 int ctr_push_adam(ctr_table* t, uint32_t replica, ctr_batch* batch, const float* d_grad_pooled, uint32_t mode,

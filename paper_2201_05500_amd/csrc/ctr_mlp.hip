@@ -66,7 +66,7 @@ void mem_layout(const ctr_mlp_config* c, const MlpLayout& L, MemLayout* M) {
 
 struct WsLayout {
   u32 max_h;
-  size_t off_h0, off_act[CTR_MLP_MAX_HIDDEN], off_z, off_da, off_dz[2], off_logits, off_dlogit, off_grads,
+  size_t off_h0, off_act[CTR_MLP_MAX_HIDDEN], off_z, off_da, off_dz[2], off_logits, off_dlogit, off_lterm, off_grads,
       off_partial, total;
 };
 
@@ -86,6 +86,7 @@ void ws_layout(const ctr_mlp_config* c, const MlpLayout& L, u32 B, WsLayout* S) 
   S->off_dz[1] = o; o += align256((size_t)B * mh * sizeof(bf16_t));
   S->off_logits = o; o += align256((size_t)B * sizeof(float));
   S->off_dlogit = o; o += align256((size_t)B * sizeof(float));
+  S->off_lterm = o; o += align256((size_t)B * sizeof(double));
   S->off_grads = o; o += align256((size_t)L.n_params * sizeof(float));
   S->off_partial = o; o += align256((size_t)COLSUM_SLICES * mh * sizeof(float));
   S->total = o;
@@ -120,15 +121,19 @@ bool gemm(ctr_mlp* t, rocblas_operation opa, rocblas_operation opb, int m, int n
 }
 
 // Forward through the hidden layers and the output layer; activations stay in the workspace.
-bool forward(ctr_mlp* t, u32 replica, const float* d_pooled, u32 B, char* ws, const WsLayout& S, float* logits,
-             hipStream_t st) {
+// The input is either fp32 (rounded to bf16 into the workspace) or already bf16 (used in place).
+bool forward(ctr_mlp* t, u32 replica, const float* d_pooled, const bf16_t* d_pooled_bf16, u32 B, char* ws,
+             const WsLayout& S, float* logits, hipStream_t st) {
   const MlpLayout& L = t->L;
   const float* P = t->params + (u64)replica * t->M.stride;
   const bf16_t* PB = t->pb + (u64)replica * t->M.stride;
-  bf16_t* h = (bf16_t*)(ws + S.off_h0);
+  const bf16_t* h = d_pooled_bf16;
   float* z = (float*)(ws + S.off_z);
-  const u64 n0 = (u64)B * L.in[0];
-  hipLaunchKernelGGL(k_cast_bf16, dim3(blocks_for(n0 / 4)), dim3(BLOCK), 0, st, d_pooled, h, n0);
+  if (!h) {
+    const u64 n0 = (u64)B * L.in[0];
+    hipLaunchKernelGGL(k_cast_bf16, dim3(blocks_for(n0 / 4)), dim3(BLOCK), 0, st, d_pooled, (bf16_t*)(ws + S.off_h0), n0);
+    h = (const bf16_t*)(ws + S.off_h0);
+  }
   for (u32 l = 0; l + 1 < L.n_layers; ++l) {
     const int i = (int)L.in[l], o = (int)L.out[l];
     // Z[B x o] = H[B x i] W[i x o]
@@ -222,9 +227,10 @@ int ctr_mlp_destroy(ctr_mlp* t) {
   return CTR_OK;
 }
 
-int ctr_mlp_forward(ctr_mlp* t, uint32_t replica, const float* d_pooled, uint32_t batch, float* d_logits,
-                    void* d_workspace, size_t workspace_bytes, void* hip_stream) {
-  if (!t || !d_pooled || !d_logits || !d_workspace) return CTR_E_INVAL;
+static int mlp_forward_impl(ctr_mlp* t, uint32_t replica, const float* d_pooled, const bf16_t* d_pooled_bf16,
+                            uint32_t batch, float* d_logits, void* d_workspace, size_t workspace_bytes,
+                            void* hip_stream) {
+  if (!t || (!d_pooled && !d_pooled_bf16) || !d_logits || !d_workspace) return CTR_E_INVAL;
   if (replica >= t->cfg.n_replicas || batch == 0 || batch % 8 != 0) return CTR_E_INVAL;
   if (((uintptr_t)d_workspace & 255) != 0) return CTR_E_INVAL;
   WsLayout S;
@@ -232,14 +238,15 @@ int ctr_mlp_forward(ctr_mlp* t, uint32_t replica, const float* d_pooled, uint32_
   if (workspace_bytes < S.total) return CTR_E_NOMEM;
   hipStream_t st = (hipStream_t)hip_stream;
   if (rocblas_set_stream(t->blas, st) != rocblas_status_success) return CTR_E_DEVICE;
-  if (!forward(t, replica, d_pooled, batch, (char*)d_workspace, S, d_logits, st)) return CTR_E_DEVICE;
+  if (!forward(t, replica, d_pooled, d_pooled_bf16, batch, (char*)d_workspace, S, d_logits, st)) return CTR_E_DEVICE;
   return launch_status();
 }
 
-int ctr_mlp_step(ctr_mlp* t, uint32_t replica, const float* d_pooled, const float* d_labels, uint32_t batch,
-                 float* d_grad_pooled, float* d_loss, void* d_workspace, size_t workspace_bytes, uint32_t mode,
-                 void* hip_stream) {
-  if (!t || !d_pooled || !d_labels || !d_grad_pooled || !d_loss || !d_workspace) return CTR_E_INVAL;
+static int mlp_step_impl(ctr_mlp* t, uint32_t replica, const float* d_pooled, const bf16_t* d_pooled_bf16,
+                         const float* d_labels, uint32_t batch, float* d_grad_pooled, float* d_loss,
+                         void* d_workspace, size_t workspace_bytes, uint32_t mode, void* hip_stream) {
+  if (!t || (!d_pooled && !d_pooled_bf16) || !d_labels || !d_grad_pooled || !d_loss || !d_workspace)
+    return CTR_E_INVAL;
   if (replica >= t->cfg.n_replicas || batch == 0 || batch % 8 != 0) return CTR_E_INVAL;
   if (mode != CTR_STEP_LOCAL && mode != CTR_STEP_MERGE_PENDING) return CTR_E_INVAL;
   if (!t->cfg.kstep && mode != CTR_STEP_LOCAL) return CTR_E_INVAL;
@@ -260,8 +267,11 @@ int ctr_mlp_step(ctr_mlp* t, uint32_t replica, const float* d_pooled, const floa
   float* da = (float*)(ws + S.off_da);
   const bf16_t* PB = t->pb + (u64)replica * t->M.stride;
 
-  if (!forward(t, replica, d_pooled, B, ws, S, logits, st)) return CTR_E_DEVICE;
-  hipLaunchKernelGGL(k_bce, dim3(1), dim3(BLOCK), 0, st, logits, d_labels, B, dlogit, d_loss);
+  double* lterm = (double*)(ws + S.off_lterm);
+  const bf16_t* h0 = d_pooled_bf16 ? d_pooled_bf16 : (const bf16_t*)(ws + S.off_h0);
+  if (!forward(t, replica, d_pooled, d_pooled_bf16, B, ws, S, logits, st)) return CTR_E_DEVICE;
+  hipLaunchKernelGGL(k_bce, dim3(blocks_for(B)), dim3(BLOCK), 0, st, logits, d_labels, B, dlogit, lterm);
+  hipLaunchKernelGGL(k_loss_mean, dim3(1), dim3(BLOCK), 0, st, lterm, B, d_loss);
 
   // output layer: weight and bias gradients, then back through the last ReLU
   const u32 lo = L.n_layers - 1;
@@ -281,7 +291,7 @@ int ctr_mlp_step(ctr_mlp* t, uint32_t replica, const float* d_pooled, const floa
   // hidden layers, last to first
   for (int l = (int)lo - 1; l >= 0; --l) {
     const int i = (int)L.in[l], o = (int)L.out[l];
-    const bf16_t* h_prev = l == 0 ? (const bf16_t*)(ws + S.off_h0) : (const bf16_t*)(ws + S.off_act[l - 1]);
+    const bf16_t* h_prev = l == 0 ? h0 : (const bf16_t*)(ws + S.off_act[l - 1]);
     // dW[i x o] = H_prev^T[i x B] dZ[B x o]
     if (!gemm(t, rocblas_operation_none, rocblas_operation_transpose, o, i, (int)B, dz, o, h_prev, i,
               grads + L.w_off[l], o))
@@ -308,6 +318,35 @@ int ctr_mlp_step(ctr_mlp* t, uint32_t replica, const float* d_pooled, const floa
                      L.n_params, (double)t->cfg.beta1, (double)t->cfg.beta2, (double)t->cfg.lr, amode);
   if (mode == CTR_STEP_MERGE_PENDING) t->pend_mask |= 1u << replica;
   return launch_status();
+}
+
+int ctr_mlp_forward(ctr_mlp* t, uint32_t replica, const float* d_pooled, uint32_t batch, float* d_logits,
+                    void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!d_pooled) return CTR_E_INVAL;
+  return mlp_forward_impl(t, replica, d_pooled, nullptr, batch, d_logits, d_workspace, workspace_bytes, hip_stream);
+}
+
+int ctr_mlp_forward_bf16(ctr_mlp* t, uint32_t replica, const uint16_t* d_pooled_bf16, uint32_t batch,
+                         float* d_logits, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!d_pooled_bf16) return CTR_E_INVAL;
+  return mlp_forward_impl(t, replica, nullptr, d_pooled_bf16, batch, d_logits, d_workspace, workspace_bytes,
+                          hip_stream);
+}
+
+int ctr_mlp_step(ctr_mlp* t, uint32_t replica, const float* d_pooled, const float* d_labels, uint32_t batch,
+                 float* d_grad_pooled, float* d_loss, void* d_workspace, size_t workspace_bytes, uint32_t mode,
+                 void* hip_stream) {
+  if (!d_pooled) return CTR_E_INVAL;
+  return mlp_step_impl(t, replica, d_pooled, nullptr, d_labels, batch, d_grad_pooled, d_loss, d_workspace,
+                       workspace_bytes, mode, hip_stream);
+}
+
+int ctr_mlp_step_bf16(ctr_mlp* t, uint32_t replica, const uint16_t* d_pooled_bf16, const float* d_labels,
+                      uint32_t batch, float* d_grad_pooled, float* d_loss, void* d_workspace,
+                      size_t workspace_bytes, uint32_t mode, void* hip_stream) {
+  if (!d_pooled_bf16) return CTR_E_INVAL;
+  return mlp_step_impl(t, replica, nullptr, d_pooled_bf16, d_labels, batch, d_grad_pooled, d_loss, d_workspace,
+                       workspace_bytes, mode, hip_stream);
 }
 
 int ctr_mlp_kstep_merge(ctr_mlp* t, void* hip_stream) {

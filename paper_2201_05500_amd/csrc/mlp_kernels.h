@@ -9,14 +9,6 @@
 
 namespace ctr {
 
-typedef uint16_t bf16_t;
-
-__device__ __forceinline__ bf16_t to_bf16(float f) {
-  const u32 u = __float_as_uint(f);
-  return (bf16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
-}
-__device__ __forceinline__ float from_bf16(bf16_t h) { return __uint_as_float((u32)h << 16); }
-
 struct MlpLayout {
   u32 n_layers;        // hidden layers + the output layer
   u32 in[8], out[8];   // widths per layer
@@ -62,17 +54,22 @@ __global__ void k_out_forward(const bf16_t* __restrict__ a, const bf16_t* __rest
   if (lane == 0) logits[r] = s + bias[0];
 }
 
-// Sigmoid cross-entropy with logits: per-sample loss summed in binary64 by ONE block in a fixed
-// order (the mean goes to *loss), and dlogit[b] = (sigmoid(z) - y) / rows.
+// Sigmoid cross-entropy with logits, evaluated in binary64 per sample:
+// lterm[b] = max(z, 0) - z y + log1p(exp(-|z|)) and dlogit[b] = (sigmoid(z) - y) / rows.
 __global__ void k_bce(const float* __restrict__ logits, const float* __restrict__ labels, u32 rows,
-                      float* __restrict__ dlogit, float* __restrict__ loss) {
+                      float* __restrict__ dlogit, double* __restrict__ lterm) {
+  const u32 r = blockIdx.x * BLOCK + threadIdx.x;
+  if (r >= rows) return;
+  const double z = (double)logits[r], y = (double)labels[r];
+  lterm[r] = fmax(z, 0.0) - z * y + log1p(exp(-fabs(z)));
+  dlogit[r] = (float)((1.0 / (1.0 + exp(-z)) - y) / (double)rows);
+}
+
+// Mean of the per-sample loss terms, summed by ONE block in a fixed order.
+__global__ void k_loss_mean(const double* __restrict__ lterm, u32 rows, float* __restrict__ loss) {
   __shared__ double part[BLOCK];
   double s = 0.0;
-  for (u32 r = threadIdx.x; r < rows; r += BLOCK) {
-    const double z = (double)logits[r], y = (double)labels[r];
-    s += fmax(z, 0.0) - z * y + log1p(exp(-fabs(z)));
-    dlogit[r] = (float)((1.0 / (1.0 + exp(-z)) - y) / (double)rows);
-  }
+  for (u32 r = threadIdx.x; r < rows; r += BLOCK) s += lterm[r];
   part[threadIdx.x] = s;
   __syncthreads();
   for (int off = BLOCK / 2; off > 0; off >>= 1) {

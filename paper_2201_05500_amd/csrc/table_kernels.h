@@ -374,7 +374,7 @@ template <int LPR>
 __global__ void __launch_bounds__(BLOCK)
 k_pool(const DevHeader* hdr, const u32* __restrict__ occ_row, u32* __restrict__ seg_of,
        const u32* __restrict__ offsets, u32 n_seg, const float* __restrict__ values, u32 D, u32 rf,
-       float* __restrict__ pooled) {
+       float* __restrict__ pooled, bf16_t* __restrict__ pooled_bf16) {
   if (hdr->status) return;
   constexpr int GROUPS = BLOCK / LPR;
   constexpr int TILE = GROUPS * POOL_NS * POOL_ROUNDS;
@@ -438,7 +438,8 @@ k_pool(const DevHeader* hdr, const u32* __restrict__ occ_row, u32* __restrict__ 
       const u32 l = (rnd * POOL_NS + s) * GROUPS + grp;
       if (l < tile_n && col_ok) {
         f4 o = {(float)acc[s].x, (float)acc[s].y, (float)acc[s].z, (float)acc[s].w};
-        stg4(pooled + (u64)(tile_g0 + l) * D + 4 * c, o);
+        if (pooled) stg4(pooled + (u64)(tile_g0 + l) * D + 4 * c, o);
+        if (pooled_bf16) stg4_bf16(pooled_bf16 + (u64)(tile_g0 + l) * D + 4 * c, o);  // the fp32 value, rounded again
       }
     }
   }

@@ -30,14 +30,15 @@ def test_pull_tower_push_chain():
         keys = torch.from_numpy(bn["keys"].view(np.int64)).cuda()
         offs = torch.from_numpy(bn["offsets"].view(np.int32)).cuda()
         labels = (rng.random(w.batch) < 0.05).astype(np.float32)
-        st, gb, pooled = gt.pull_pool(0, keys, offs)
+        st, gb, pooled16, pooled = gt.pull_pool_bf16(0, keys, offs, want_f32=True)
         assert st == CTR_OK and gt.last_status() == CTR_OK
+        assert torch.equal(pooled16, pooled.to(torch.bfloat16))
         ost, opooled = ot.pull_pool(0, bn["keys"], bn["offsets"])
         assert ost == 0
         _, orows, oinv = ot.batch_export(bn["keys"].size)
         assert_close(pooled.cpu().numpy(), opooled, "pooled step %d" % step,
                      pooled_tolerance(ot.table_export(0)["x"], orows, oinv, bn["offsets"]))
-        x = pooled.view(w.batch, in_dim)                       # [B, S*D]: slots concatenated per sample
+        x = pooled16.view(w.batch, in_dim)                     # [B, S*D]: slots concatenated per sample
         st, loss, gp = gm.step(0, x, torch.from_numpy(labels).cuda())
         assert st == CTR_OK
         oloss, ogp = om.step(0, pooled.cpu().numpy().reshape(w.batch, in_dim), labels)   # same input as the GPU tower

@@ -110,3 +110,24 @@ def test_argument_checks():
                                g._ws.data_ptr(), 64, 0, g.stream)
     assert st == B.CTR_E_NOMEM
     torch.cuda.synchronize()
+
+
+def test_bf16_input_equals_fp32_input_bit_for_bit():
+    """The bf16 entry points read in place what the fp32 ones would have written by rounding."""
+    import torch
+    rng = np.random.default_rng(11)
+    ga, _ = _pair(192, [128, 64])
+    gb, _ = _pair(192, [128, 64])
+    for _ in range(2):
+        _, _, dp, dl = _batch(rng, 128, 192)
+        dpb = dp.to(torch.bfloat16)              # nearest-even, as the library's own rounding
+        sa, la = ga.forward(0, dp)
+        sb, lb = gb.forward(0, dpb)
+        assert sa == 0 and sb == 0 and torch.equal(la, lb)
+        sa, lossa, gpa = ga.step(0, dp, dl)
+        sb, lossb, gpb = gb.step(0, dpb, dl)
+        assert sa == 0 and sb == 0
+        assert torch.equal(lossa, lossb) and torch.equal(gpa, gpb)
+    ea, eb = ga.export(), gb.export()
+    for k in ("params", "m", "v"):
+        assert np.array_equal(ea[k], eb[k]), k

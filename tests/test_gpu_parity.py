@@ -299,3 +299,29 @@ def test_random_small_cases_differential():
                 assert gt.kstep_merge() == 0 and ot.kstep_merge() == 0
             compare_tables(gt, ot, what="case %d after step %d" % (case, step))
         gt.close()
+
+
+def test_bf16_pooled_output():
+    """ctr_pull_pool_bf16: the bf16 copy is the fp32 pooled value rounded to nearest-even, with or without the
+    fp32 output; the table and the batch are those of the plain pull."""
+    import torch
+    from paper_2201_05500_amd.binding import CTR_OK, CtrTable
+    w = WL.scaled(WL.WORKLOADS["large"], capacity_rows=1 << 14, zipf_universe=5000, batch=37, slots=9, dim=32)
+    bn = WL.as_numpy(WL.make_batch(w, 0))
+    bt = to_device(bn)
+    keys, offs, grad = bt["keys"], bt["offsets"], bt["grad"]
+    ta, tb, tc = (CtrTable(w.capacity_rows, w.dim, init_seed=4, init_std=0.05) for _ in range(3))
+    st, ba, pa = ta.pull_pool(0, keys, offs)
+    assert st == CTR_OK
+    st, bb, pb16, pb32 = tb.pull_pool_bf16(0, keys, offs, want_f32=True)
+    assert st == CTR_OK and tb.last_status() == CTR_OK
+    st, bc, pc16, none = tc.pull_pool_bf16(0, keys, offs)
+    assert st == CTR_OK and none is None and tc.last_status() == CTR_OK
+    assert torch.equal(pa, pb32)
+    assert torch.equal(pb16, pa.to(torch.bfloat16))
+    assert torch.equal(pc16, pb16)
+    for t, b in ((ta, ba), (tb, bb), (tc, bc)):
+        assert t.push_adam(0, b, grad) == CTR_OK
+    ea, eb, ec = ta.table_export(0), tb.table_export(0), tc.table_export(0)
+    for k in ("keys", "x", "m", "v"):
+        assert np.array_equal(ea[k], eb[k]) and np.array_equal(ea[k], ec[k]), k
