@@ -15,6 +15,12 @@ from tests.parity_util import ATOL, RTOL
 pytestmark = pytest.mark.gpu
 
 
+def _say(capsys, *a):
+    """Progress line that reaches the terminal even under output capture (these tests run for minutes)."""
+    with capsys.disabled():
+        print("[full size]", *a, flush=True)
+
+
 def _close_chunked(g, o, what, chunk=1 << 18):
     assert g.shape == o.shape, what
     for i in range(0, g.shape[0], chunk):
@@ -28,7 +34,7 @@ def _close_chunked(g, o, what, chunk=1 << 18):
 
 
 @pytest.mark.timeout(1200)
-def test_large_config_two_steps_full_table():
+def test_large_config_two_steps_full_table(capsys):
     import torch
     from paper_2201_05500_amd.binding import CTR_OK, CtrTable
     w = WL.WORKLOADS["large"]
@@ -41,12 +47,12 @@ def test_large_config_two_steps_full_table():
         bt = WL.make_batch(w, step, device="cuda:0")
         bn = WL.as_numpy(bt)
         L = bn["keys"].size
-        print("step", step, "L", L, flush=True)
+        _say(capsys, "step", step, "L", L)
         st, gb, pooled = gt.pull_pool(0, bt["keys"], bt["offsets"])
         assert st == CTR_OK and gt.last_status() == CTR_OK
         ost, opooled = ot.pull_pool(0, bn["keys"], bn["offsets"])
         assert ost == 0
-        print("oracle pull done", flush=True)
+        _say(capsys, "oracle pull done")
         # dedup result, bit-exact
         gu, gr, gi = gt.batch_export(gb, L)
         ou, orow, oi = ot.batch_export(L)
@@ -65,10 +71,81 @@ def test_large_config_two_steps_full_table():
         assert ot.push_adam(0, bn["grad"]) == 0
         u, n_new = gt.batch_stats()
         assert u == orow.size and n_new == ot.n_new_last
-        print("oracle push done", flush=True)
+        _say(capsys, "oracle push done")
         del bt, bn, pooled, opooled
     assert gt.last_status() == CTR_OK and gt.n_rows == ot.n_rows
     g, o = gt.table_export(0), ot.table_export(0)
     assert np.array_equal(g["keys"], o["keys"])
     for f in ("x", "m", "v"):
         _close_chunked(g[f], o[f], "large config, " + f)
+
+
+@pytest.mark.timeout(1200)
+def test_full_step_config_one_step(capsys):
+    """The whole training step at the size bench.py --workload full times: batch 16384 x 300 slots into the
+    2^24-row table, tower 19200-1024-512-256-1.  The tower is compared with its oracle on the very pooled
+    input the GPU produced; the table with the table oracle fed the very gradient the GPU tower produced."""
+    import torch
+    from oracle import mlp_oracle as M
+    from paper_2201_05500_amd.binding import CTR_OK, CtrTable
+    from paper_2201_05500_amd.binding_mlp import CtrMlp
+    from tests.test_gpu_mlp import close_enough, close_rows
+    w = WL.WORKLOADS["full"]
+    in_dim = w.slots * w.dim
+    gt = CtrTable(w.capacity_rows, w.dim, lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, init_seed=1,
+                  init_std=w.init_std, load_factor=w.load_factor)
+    ot = O.OracleTable(w.capacity_rows, w.dim, lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps,
+                       init_seed=1, init_std=w.init_std)
+    gm = CtrMlp(in_dim, WL.FULL_STEP_HIDDEN, lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, init_seed=3)
+    om = M.MlpOracle(in_dim, WL.FULL_STEP_HIDDEN, lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, init_seed=3)
+    bt = WL.make_batch(w, 0, device="cuda:0", with_grad=False)
+    labels = WL.make_labels(w, 0, device="cuda:0")
+    bn = WL.as_numpy(bt)
+    L = bn["keys"].size
+    _say(capsys, "full step, L", L)
+
+    st, gb, pooled16, pooled = gt.pull_pool_bf16(0, bt["keys"], bt["offsets"], want_f32=True)
+    assert st == CTR_OK and gt.last_status() == CTR_OK
+    assert torch.equal(pooled16, pooled.to(torch.bfloat16))
+    st, loss, gp = gm.step(0, pooled16.view(w.batch, in_dim), labels)
+    assert st == CTR_OK
+    assert gt.push_adam(0, gb, gp.view(w.n_segments, w.dim)) == CTR_OK
+    assert gt.last_status() == CTR_OK
+    _say(capsys, "GPU step done, loss", float(loss.cpu()[0]))
+
+    ost, opooled = ot.pull_pool(0, bn["keys"], bn["offsets"])
+    assert ost == 0
+    _say(capsys, "oracle pull done")
+    _, orow, oi = ot.batch_export(L)
+    ox = ot.table_export(0)["x"]
+    rng = np.random.default_rng(5)
+    segs = rng.integers(0, w.n_segments, 20000)
+    gsel = pooled[torch.from_numpy(segs).to("cuda:0")].cpu().numpy().astype(np.float64)
+    off = bn["offsets"].astype(np.int64)
+    for n, g in enumerate(segs):
+        rows = orow[oi[off[g]:off[g + 1]]]
+        tol = np.maximum((ATOL + RTOL * np.abs(ox[rows].astype(np.float64))).sum(axis=0), ATOL)
+        assert np.all(np.abs(gsel[n] - opooled[g]) <= tol), ("pooled", g)
+    del ox, opooled, gsel, oi
+
+    pooled_h = pooled.cpu().numpy().reshape(w.batch, in_dim)
+    del pooled, pooled16
+    oloss, ogp = om.step(0, pooled_h, labels.cpu().numpy())
+    _say(capsys, "oracle tower done, loss", float(oloss))
+    assert abs(float(loss.cpu()[0]) - float(oloss)) <= 1e-4 * max(1.0, float(oloss))
+    gp_h = gp.cpu().numpy()
+    n_round, n_mask = close_rows(gp_h, ogp, "gradient of the pooled input", in_dim)
+    _say(capsys, "gradient rows with rounding cascades:", n_round, "with a flipped mask:", n_mask, "of", w.batch)
+    e = gm.export()
+    close_enough(e["params"], om.params[0], "tower parameters", rtol=1e-3, norm_tol=1e-3)
+    close_enough(e["m"], om.m[0], "tower first moment")
+    del ogp, pooled_h
+
+    assert ot.push_adam(0, gp_h.reshape(w.n_segments, w.dim)) == 0       # the GPU tower's gradient
+    _say(capsys, "oracle push done")
+    u, n_new = gt.batch_stats()
+    assert u == orow.size and n_new == ot.n_new_last and gt.n_rows == ot.n_rows
+    g, o = gt.table_export(0), ot.table_export(0)
+    assert np.array_equal(g["keys"], o["keys"])
+    for f in ("x", "m", "v"):
+        _close_chunked(g[f], o[f], "full step, table " + f)

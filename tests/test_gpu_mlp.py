@@ -27,6 +27,38 @@ def close_enough(gpu, ref, what, rtol=1e-2, frac_atol=2e-3, norm_tol=2e-3, outli
     assert nerr <= norm_tol, "%s: norm-wise error %.3g" % (what, nerr)
 
 
+def close_rows(gpu, ref, what, row_len, rtol=1e-2, frac_atol=2e-3, round_rows=0.05, round_err=1e-2,
+               mask_rows=2e-2, mask_err=0.6, norm_tol=1e-2):
+    """Per-sample outputs (one row per sample) at sizes where rare rounding events are certain to occur somewhere.
+    A back-propagated hidden gradient that sits on a bf16 rounding boundary may round the other way on the GPU
+    (2^-8 relative on that element); everything downstream of it in that sample then moves by up to about
+    2^-8 / sqrt(width), which in turn pushes further elements of that sample over their boundaries.  Measured on
+    the 19200-1024-512-256-1 tower: 98 % of the samples agree to 1e-7, about 2 % show this cascade with a row-wise
+    error of 0.1-0.3 %, and 0.1-0.7 % have a ReLU mask flipped, which moves the row by 1/sqrt(active units), 5-20 %.
+    The mask flips follow from the same arithmetic: a first-layer pre-activation (19200 fp32-accumulated terms) is
+    off by about 1e-6 relative, so each of the ~512 active first-layer outputs rounds the other way with probability
+    ~1e-6 / 2^-8 (0.13 per sample); such a step moves every second-layer pre-activation by ~2^-8 / sqrt(512) of
+    its spread, and one of 512 of them lies that close to zero with probability ~0.1: about 1 % of the samples.
+    So: rows with any element outside atol + rtol |ref| may be at
+    most `round_rows` of all rows; of those, rows with a norm-wise error above `round_err` at most `mask_rows`
+    (but one is always allowed), none above `mask_err`; and the whole tensor within `norm_tol` norm-wise."""
+    gpu = np.asarray(gpu, np.float64).reshape(-1, row_len)
+    ref = np.asarray(ref, np.float64).reshape(-1, row_len)
+    assert gpu.shape == ref.shape, what
+    n = ref.shape[0]
+    rms = np.sqrt(np.mean(ref * ref)) + 1e-30
+    diff = gpu - ref
+    badrow = (np.abs(diff) > frac_atol * rms + rtol * np.abs(ref)).any(axis=1)
+    rowerr = np.linalg.norm(diff, axis=1) / (np.linalg.norm(ref, axis=1) + 1e-30)
+    assert badrow.mean() <= round_rows, "%s: %d of %d rows off" % (what, int(badrow.sum()), n)
+    n_mask = int((rowerr > round_err).sum())
+    assert n_mask <= max(1, int(mask_rows * n)), "%s: %d of %d rows off by more than %g" % (what, n_mask, n, round_err)
+    assert rowerr.max() <= mask_err, "%s: worst row error %.3g" % (what, rowerr.max())
+    nerr = np.linalg.norm(diff) / (np.linalg.norm(ref) + 1e-30)
+    assert nerr <= norm_tol, "%s: norm-wise error %.3g" % (what, nerr)
+    return int(badrow.sum()), n_mask
+
+
 def _pair(in_dim, hidden, seed=3, **kw):
     from paper_2201_05500_amd.binding_mlp import CtrMlp
     return (CtrMlp(in_dim, hidden, init_seed=seed, **kw), M.MlpOracle(in_dim, hidden, init_seed=seed, **kw))
