@@ -579,13 +579,32 @@ int ctr_table_export(ctr_table* t, uint32_t replica, uint64_t* h_keys, float* h_
   if (n == 0) return CTR_OK;
   const size_t D = t->D, rowb = D * sizeof(float), pitch = (size_t)t->rf * sizeof(float);
   const float* vals = t->values + (u64)replica * t->tl.replica_stride;
-  const float* v_src = vals + (adagrad ? D : 2 * D);
   bool ok = true;
   if (h_keys) ok = ok && hipMemcpyAsync(h_keys, t->row_key, n * sizeof(u64), hipMemcpyDeviceToHost, st) == hipSuccess;
-  if (h_x) ok = ok && hipMemcpy2DAsync(h_x, rowb, vals, pitch, rowb, n, hipMemcpyDeviceToHost, st) == hipSuccess;
-  if (h_m) ok = ok && hipMemcpy2DAsync(h_m, rowb, vals + D, pitch, rowb, n, hipMemcpyDeviceToHost, st) == hipSuccess;
-  if (h_v) ok = ok && hipMemcpy2DAsync(h_v, rowb, v_src, pitch, rowb, n, hipMemcpyDeviceToHost, st) == hipSuccess;
   if (h_vhat) ok = ok && hipMemcpyAsync(h_vhat, t->vhat, n * rowb, hipMemcpyDeviceToHost, st) == hipSuccess;
+  // Rows are [x | m | v] interleaved: whole rows come over in contiguous chunks and are split on
+  // the host (a strided device copy of 64..1024-byte pieces is far slower than that).
+  struct Field { float* dst; size_t off; };
+  const Field fields[3] = {{h_x, 0}, {h_m, D}, {h_v, adagrad ? D : 2 * D}};
+  if (h_x || h_m || h_v) {
+    const size_t chunk_rows = std::max<size_t>(1, ((size_t)32 << 20) / pitch);
+    std::vector<float> tmp;
+    try {
+      tmp.resize(std::min<size_t>(chunk_rows, n) * t->rf);
+    } catch (const std::bad_alloc&) {
+      return CTR_E_NOMEM;
+    }
+    for (size_t r0 = 0; r0 < n && ok; r0 += chunk_rows) {
+      const size_t cnt = std::min<size_t>(chunk_rows, n - r0);
+      ok = ok && hipMemcpyAsync(tmp.data(), vals + r0 * t->rf, cnt * pitch, hipMemcpyDeviceToHost, st) == hipSuccess;
+      ok = ok && hipStreamSynchronize(st) == hipSuccess;
+      if (!ok) break;
+      for (const Field& f : fields) {
+        if (!f.dst) continue;
+        for (size_t r = 0; r < cnt; ++r) memcpy(f.dst + (r0 + r) * D, tmp.data() + r * t->rf + f.off, rowb);
+      }
+    }
+  }
   ok = ok && hipStreamSynchronize(st) == hipSuccess;
   return ok ? CTR_OK : CTR_E_DEVICE;
 }

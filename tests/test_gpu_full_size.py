@@ -5,6 +5,8 @@ The oracle runs the same two steps on the host (about half a minute each); the f
 compared element by element, the pooled outputs on a sample of segments (their tolerance needs the
 rows of each segment, which is too much to materialise for all 9.8 M segments).
 """
+import time
+
 import numpy as np
 import pytest
 
@@ -18,7 +20,7 @@ pytestmark = pytest.mark.gpu
 def _say(capsys, *a):
     """Progress line that reaches the terminal even under output capture (these tests run for minutes)."""
     with capsys.disabled():
-        print("[full size]", *a, flush=True)
+        print("[full size %s]" % time.strftime("%H:%M:%S"), *a, flush=True)
 
 
 def _close_chunked(g, o, what, chunk=1 << 18):
@@ -149,3 +151,23 @@ def test_full_step_config_one_step(capsys):
     assert np.array_equal(g["keys"], o["keys"])
     for f in ("x", "m", "v"):
         _close_chunked(g[f], o[f], "full step, table " + f)
+
+
+@pytest.mark.timeout(900)
+def test_mid_config_full_size(capsys):
+    """Configuration 2 as benchmarked (2^22 x 16 table, 8192 x 100 slots, ~2.5 M occurrences per batch):
+    three steps, every output compared."""
+    from tests.test_gpu_parity import run_workload
+    _say(capsys, "mid config, 3 steps")
+    gt, ot = run_workload(WL.WORKLOADS["mid"], 3, say=lambda m: _say(capsys, m))
+    assert gt.n_rows == ot.n_rows
+
+
+@pytest.mark.timeout(1200)
+def test_kstep_config_full_size(capsys):
+    """Configuration 4 as benchmarked (W = 8 replicas, k = 4, 2^22 x 16 table, 4096 x 100 slots per replica
+    step): one full merge round (3 local steps, the merge step, the merge), tables compared before and after."""
+    from tests.test_gpu_parity import _kstep_rounds
+    _say(capsys, "k-step config, one merge round of 8 replicas")
+    gt, ot = _kstep_rounds(WL.WORKLOADS["kstep"], 1, 4, say=lambda m: _say(capsys, m))
+    assert gt.n_rows == ot.n_rows

@@ -20,11 +20,11 @@ def make_tables(w, seed=1234, **kw):
     return gt, ot
 
 
-def run_workload(w, steps, **kw):
+def run_workload(w, steps, say=None, **kw):
     gt, ot = make_tables(w, **kw)
     for s in range(steps):
         bn = WL.as_numpy(WL.make_batch(w, s))
-        print("step", s, "L", bn["keys"].size, flush=True)
+        (say or print)("step %d L %d" % (s, bn["keys"].size))
         run_step(gt, ot, to_device(bn), bn, what="%s step %d" % (w.name, s))
         compare_tables(gt, ot, what="%s after step %d" % (w.name, s))
     return gt, ot
@@ -59,7 +59,7 @@ def test_other_dims(dim):
     run_workload(w, 2)
 
 
-def _kstep_rounds(w, rounds, k):
+def _kstep_rounds(w, rounds, k, say=None):
     gt, ot = make_tables(w)
     step = 0
     for r in range(rounds):
@@ -70,7 +70,11 @@ def _kstep_rounds(w, rounds, k):
                 run_step(gt, ot, to_device(bn), bn, replica=j, mode=mode,
                          what="round %d step %d replica %d" % (r, i, j))
             step += 1
+            if say:
+                say("round %d local step %d of %d done for %d replicas" % (r, i, k, w.n_replicas))
         compare_tables(gt, ot, what="before merge %d" % r)
+        if say:
+            say("tables compared before merge %d" % r)
         assert gt.kstep_merge() == 0 and ot.kstep_merge() == 0
         assert gt.last_status() == 0
         compare_tables(gt, ot, what="after merge %d" % r)
