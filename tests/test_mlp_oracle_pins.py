@@ -110,6 +110,31 @@ def test_one_unit_network_by_hand():
     assert abs(g[8 * 8 + 8] - (sig[0] - 1.0) / 2 * w * 2.0) < 1e-12
 
 
+def test_backward_goes_through_the_rounded_weights():
+    """The products of the backward pass take the same bf16 weight copies as the forward pass.  All-positive
+    network whose inputs and activations are exactly representable, weights 1 + 2^-9 (bf16: 1.0): the gradient of
+    the pooled input is then sum_j bf16(dlogit * u_j) * 1.0, not * (1 + 2^-9)."""
+    o = M.MlpOracle(8, [8])
+    p = o.params[0]
+    p[:] = 0
+    p[:64] = F32(1 + 2.0 ** -9)              # W1
+    u = F32(0.25)
+    p[64 + 8:64 + 16] = u                    # w_out
+    x = np.full((2, 8), F32(1 + 2.0 ** -9))  # the input is rounded too: bf16 1.0 and 2.0
+    x[1] = F32(2 + 2.0 ** -8)
+    y = np.array([1.0, 0.0], F32)
+    loss, g, dp = o.loss_and_grads(0, x, y)
+    x = np.round(x)
+    z = np.array([8.0, 16.0]) * 8 * 0.25     # hidden = 8 x (resp. 16), logit = sum of 8 hidden * 0.25
+    dlogit = (1 / (1 + np.exp(-z)) - y) / 2
+    assert abs(loss - np.mean(np.log1p(np.exp(z)) - y * z)) < 1e-12
+    dz = M.bf16_round((dlogit * 0.25).astype(F32)).astype(np.float64)   # per hidden unit, equal for all 8
+    assert np.allclose(dp, (8 * dz)[:, None] * np.ones((1, 8)), rtol=1e-12, atol=0)
+    # weight gradient of the first layer: x^T dz, exactly
+    assert np.allclose(g[:64].reshape(8, 8), np.outer(np.ones(8), np.ones(8)) * (x[0, 0] * dz[0] + x[1, 0] * dz[1]),
+                       rtol=1e-12, atol=0)
+
+
 def _replay_on_sparse_oracle(o_kwargs, grads_per_step, n, W, kstep, k):
     """Feeds recorded dense gradients to the C++ table oracle with every row touched every step."""
     D = 4
@@ -120,10 +145,11 @@ def _replay_on_sparse_oracle(o_kwargs, grads_per_step, n, W, kstep, k):
     return t, keys, off
 
 
-@pytest.mark.parametrize("W,k", [(1, 0), (1, 1), (3, 2)])
-def test_dense_optimizer_equals_the_table_oracle_with_every_row_touched(W, k):
+@pytest.mark.parametrize("W,k,mixed", [(1, 0, False), (1, 1, False), (3, 2, False), (3, 2, True)])
+def test_dense_optimizer_equals_the_table_oracle_with_every_row_touched(W, k, mixed):
     """Two independent implementations of Algorithm 2 (numpy here, C++ in the table oracle) must agree
-    bit for bit when the table's every row is touched at every step."""
+    bit for bit when the table's every row is touched at every step.  `mixed`: replica 0 takes its k-th step
+    as a local one, so the merge must add the pending step for the other replicas only."""
     rng = np.random.default_rng(5)
     in_dim, hidden, B = 8, [8], 6                         # 8*8+8+8+1 = 81 parameters -> use the first 80
     kstep = k > 0
@@ -136,12 +162,13 @@ def test_dense_optimizer_equals_the_table_oracle_with_every_row_touched(W, k):
     for s in range(1, 7):
         mode = M.STEP_MERGE_PENDING if (kstep and s % k == 0) else M.STEP_LOCAL
         for j in range(W):
+            mode_j = M.STEP_LOCAL if (mixed and j == 0) else mode
             pooled = rng.standard_normal((B, in_dim)).astype(F32)
             labels = (rng.random(B) < 0.5).astype(F32)
             g = o.loss_and_grads(j, pooled, labels)[1].astype(F32)
-            o.step(j, pooled, labels, mode)
+            o.step(j, pooled, labels, mode_j)
             st, _ = t.pull_pool(j, keys, off)
-            assert st == O.OK and t.push_adam(j, g[:n4].reshape(-1, 4), mode) == O.OK
+            assert st == O.OK and t.push_adam(j, g[:n4].reshape(-1, 4), mode_j) == O.OK
         if mode == M.STEP_MERGE_PENDING:
             o.kstep_merge()
             assert t.kstep_merge() == O.OK
