@@ -32,6 +32,7 @@ extern "C" {
 typedef struct ctr_mlp ctr_mlp; /* opaque host-side handle */
 
 #define CTR_MLP_MAX_HIDDEN 6
+#define CTR_MLP_MAX_BATCH (1u << 20) /* samples per call */
 
 typedef struct {
   uint32_t in_dim;                     /* width of the input (slots x embedding dim), multiple of 8 */
@@ -62,7 +63,7 @@ int ctr_mlp_destroy(ctr_mlp* m);
  *   d_loss                         device, out: one float, the mean sigmoid cross-entropy
  *   d_workspace                    device, >= ctr_mlp_workspace_bytes(cfg, batch), 256-byte aligned
  *   mode                           CTR_STEP_LOCAL or CTR_STEP_MERGE_PENDING, as in ctr_push_adam
- * batch must be a multiple of 8.  Errors: CTR_E_INVAL, CTR_E_NOMEM, CTR_E_DEVICE. */
+ * batch must be a multiple of 8 and at most CTR_MLP_MAX_BATCH.  Errors: CTR_E_INVAL, CTR_E_NOMEM, CTR_E_DEVICE. */
 int ctr_mlp_step(ctr_mlp* m, uint32_t replica, const float* d_pooled, const float* d_labels, uint32_t batch,
                  float* d_grad_pooled, float* d_loss, void* d_workspace, size_t workspace_bytes, uint32_t mode,
                  void* hip_stream);

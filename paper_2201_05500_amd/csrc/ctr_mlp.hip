@@ -172,7 +172,7 @@ size_t ctr_mlp_bytes(const ctr_mlp_config* cfg) {
 }
 
 size_t ctr_mlp_workspace_bytes(const ctr_mlp_config* cfg, uint32_t batch) {
-  if (!mlp_config_ok(cfg) || batch == 0 || batch % 8 != 0) return 0;
+  if (!mlp_config_ok(cfg) || batch == 0 || batch % 8 != 0 || batch > CTR_MLP_MAX_BATCH) return 0;
   MlpLayout L;
   WsLayout S;
   make_layout(cfg, &L);
@@ -231,7 +231,7 @@ static int mlp_forward_impl(ctr_mlp* t, uint32_t replica, const float* d_pooled,
                             uint32_t batch, float* d_logits, void* d_workspace, size_t workspace_bytes,
                             void* hip_stream) {
   if (!t || (!d_pooled && !d_pooled_bf16) || !d_logits || !d_workspace) return CTR_E_INVAL;
-  if (replica >= t->cfg.n_replicas || batch == 0 || batch % 8 != 0) return CTR_E_INVAL;
+  if (replica >= t->cfg.n_replicas || batch == 0 || batch % 8 != 0 || batch > CTR_MLP_MAX_BATCH) return CTR_E_INVAL;
   if (((uintptr_t)d_workspace & 255) != 0) return CTR_E_INVAL;
   WsLayout S;
   ws_layout(&t->cfg, t->L, batch, &S);
@@ -247,7 +247,7 @@ static int mlp_step_impl(ctr_mlp* t, uint32_t replica, const float* d_pooled, co
                          void* d_workspace, size_t workspace_bytes, uint32_t mode, void* hip_stream) {
   if (!t || (!d_pooled && !d_pooled_bf16) || !d_labels || !d_grad_pooled || !d_loss || !d_workspace)
     return CTR_E_INVAL;
-  if (replica >= t->cfg.n_replicas || batch == 0 || batch % 8 != 0) return CTR_E_INVAL;
+  if (replica >= t->cfg.n_replicas || batch == 0 || batch % 8 != 0 || batch > CTR_MLP_MAX_BATCH) return CTR_E_INVAL;
   if (mode != CTR_STEP_LOCAL && mode != CTR_STEP_MERGE_PENDING) return CTR_E_INVAL;
   if (!t->cfg.kstep && mode != CTR_STEP_LOCAL) return CTR_E_INVAL;
   if (((uintptr_t)d_workspace & 255) != 0) return CTR_E_INVAL;

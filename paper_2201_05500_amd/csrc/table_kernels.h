@@ -292,9 +292,10 @@ __global__ void k_load_rows(const DevHeader* hdr, const u32* __restrict__ occ_ro
                             const float* __restrict__ x_src, const float* __restrict__ m_src,
                             const float* __restrict__ v_src) {
   if (hdr->status) return;
-  const u32 p = (blockIdx.x * BLOCK + threadIdx.x) / LPR;
+  const u64 p64 = ((u64)blockIdx.x * BLOCK + threadIdx.x) / LPR;  // n * LPR threads can pass 2^32
   const u32 c = threadIdx.x % LPR;
-  if (p >= n || c * 4 >= D) return;
+  if (p64 >= n || c * 4 >= D) return;
+  const u32 p = (u32)p64;
   const u32 row = occ_row[p];
   const f4 x = ldg4(x_src + (u64)p * D + 4 * c);
   const f4 v = ldg4(v_src + (u64)p * D + 4 * c);
@@ -321,9 +322,10 @@ __global__ void k_collect_rows(const DevHeader* hdr, const Slot* __restrict__ sl
                                u32 rf, float* __restrict__ x_dst, float* __restrict__ m_dst,
                                float* __restrict__ v_dst, u32* __restrict__ found) {
   if (hdr->status) return;
-  const u32 p = (blockIdx.x * BLOCK + threadIdx.x) / LPR;
+  const u64 p64 = ((u64)blockIdx.x * BLOCK + threadIdx.x) / LPR;  // n * LPR threads can pass 2^32
   const u32 c = threadIdx.x % LPR;
-  if (p >= n) return;
+  if (p64 >= n) return;
+  const u32 p = (u32)p64;
   const u64 key = keys[p];
   u32 row = ROW_PENDING;
   if (key != KEY_EMPTY) {

@@ -38,6 +38,7 @@ def test_mlp_host_logic():
     assert L.ctr_mlp_bytes(C.byref(cfg)) >= n * (4 * 3 + 2)
     assert L.ctr_mlp_workspace_bytes(C.byref(cfg), 16384) >= 16384 * 19200 * 2
     assert L.ctr_mlp_workspace_bytes(C.byref(cfg), 100) == 0          # batch must be a multiple of 8
+    assert L.ctr_mlp_workspace_bytes(C.byref(cfg), (1 << 20) + 8) == 0  # and at most CTR_MLP_MAX_BATCH
     for bad in (BM.make_config(100, [8]), BM.make_config(64, []), BM.make_config(64, [12]),
                 BM.make_config(64, [8], n_replicas=2), BM.make_config(64, [8], lr=0.0)):
         assert L.ctr_mlp_bytes(C.byref(bad)) == 0

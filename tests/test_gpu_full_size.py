@@ -171,3 +171,58 @@ def test_kstep_config_full_size(capsys):
     _say(capsys, "k-step config, one merge round of 8 replicas")
     gt, ot = _kstep_rounds(WL.WORKLOADS["kstep"], 1, 4, say=lambda m: _say(capsys, m))
     assert gt.n_rows == ot.n_rows
+
+
+@pytest.mark.timeout(900)
+def test_maximum_batch_size_closed_form(capsys):
+    """The largest batch one call accepts (just under 2^31 key occurrences; 2^25 - 1 segments of 64 keys) against
+    closed forms: keys cycle through 1..K, so every count, every pooled sum and the one Adam step are known
+    without running the oracle's loop over 2 G occurrences.  Exercises 32-bit index arithmetic near its limit,
+    a pull in which every occurrence is pending, rows whose occurrences span 16 K work spans."""
+    import torch
+    from paper_2201_05500_amd.binding import CTR_OK, CtrTable
+    free, _ = torch.cuda.mem_get_info()
+    if free < 140 << 30:
+        pytest.skip("needs 140 GiB of free device memory")
+    K, D, S = 1000, 4, 64
+    G = (1 << 25) - 1
+    n = G * S                                                   # 2^31 - 64
+    lr, b1, b2, eps, std, seed = 1e-3, 0.9, 0.999, 1e-8, 0.01, 9
+    gt = CtrTable(1 << 16, D, lr=lr, beta1=b1, beta2=b2, eps=eps, init_seed=seed, init_std=std)
+    dev = "cuda:0"
+    keys = torch.arange(n, dtype=torch.int64, device=dev)
+    keys.remainder_(K).add_(1)
+    offs = (torch.arange(G + 1, dtype=torch.int64, device=dev) * S).to(torch.int32)
+    _say(capsys, "max batch: n =", n, "G =", G)
+    st, gb, pooled = gt.pull_pool(0, keys, offs)
+    assert st == CTR_OK and gt.last_status() == CTR_OK
+    assert gt.n_rows == K
+    _say(capsys, "pull done")
+    init = np.array([[O.init_value(seed, k, d, std) for d in range(D)] for k in range(1, K + 1)], np.float32)
+    # segment g holds keys ((64 g + j) mod K) + 1, j < 64: sums over a cyclic window of the init table
+    c = np.concatenate([np.zeros((1, D)), np.cumsum(np.concatenate([init, init]).astype(np.float64), axis=0)])
+    rng = np.random.default_rng(1)
+    segs = np.concatenate([[0, 1, G - 1], rng.integers(0, G, 50000)])
+    start = (segs * S) % K
+    want = c[start + S] - c[start]
+    got = pooled[torch.from_numpy(segs).to(dev)].cpu().numpy().astype(np.float64)
+    tol = S * (ATOL + RTOL * np.abs(init).max())
+    assert np.all(np.abs(got - want) <= tol), "pooled"
+    del pooled
+    grad = torch.ones((G, D), dtype=torch.float32, device=dev)
+    assert gt.push_adam(0, gb, grad) == CTR_OK
+    assert gt.last_status() == CTR_OK
+    u, n_new = gt.batch_stats()
+    assert u == K and n_new == K
+    _say(capsys, "push done")
+    e = gt.table_export(0)
+    assert np.array_equal(e["keys"], np.arange(1, K + 1, dtype=np.uint64))      # rows in order of first occurrence
+    cnt = ((n + K - 1 - np.arange(K)) // K).astype(np.float64)                   # occurrences of key k + 1
+    assert cnt.sum() == n
+    g = cnt[:, None] * np.ones((1, D))
+    m = (1 - np.float64(np.float32(b1))) * g
+    v = np.float64(np.float32(b2)) * np.float64(np.float32(eps)) + (1 - np.float64(np.float32(b2))) * g * g
+    m32, v32 = m.astype(np.float32), v.astype(np.float32)
+    x = init.astype(np.float64) - np.float64(np.float32(lr)) * m32.astype(np.float64) / np.sqrt(v32.astype(np.float64))
+    for name, got_a, want_a in (("m", e["m"], m), ("v", e["v"], v), ("x", e["x"], x)):
+        assert np.all(np.abs(got_a.astype(np.float64) - want_a) <= ATOL + RTOL * np.abs(want_a)), name
