@@ -34,8 +34,9 @@
  *  - Determinism: the same call sequence on the same inputs gives bit-identical
  *    key->row assignment (new keys take consecutive rows in order of their
  *    first occurrence in the batch), unique sets and pooled/updated values.
- *  - Limits: dim a multiple of 4 and <= 256; capacity_rows <= 2^30;
- *    n_keys < 2^31 per call; n_replicas <= 31.
+ *  - Limits: dim a multiple of 4 and <= 256; capacity_rows <= 2^30 and at most
+ *    2^30 index slots (the power of two >= capacity_rows / load_factor: 2^29
+ *    rows at a load factor of 0.5); n_keys < 2^31 per call; n_replicas <= 31.
  *  - Calls on one table must be issued from one host thread at a time and on
  *    one stream (or on streams the caller has ordered).
  */

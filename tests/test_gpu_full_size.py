@@ -226,3 +226,58 @@ def test_maximum_batch_size_closed_form(capsys):
     x = init.astype(np.float64) - np.float64(np.float32(lr)) * m32.astype(np.float64) / np.sqrt(v32.astype(np.float64))
     for name, got_a, want_a in (("m", e["m"], m), ("v", e["v"], v), ("x", e["x"], x)):
         assert np.all(np.abs(got_a.astype(np.float64) - want_a) <= ATOL + RTOL * np.abs(want_a)), name
+
+
+@pytest.mark.timeout(900)
+def test_maximum_capacity_closed_form(capsys):
+    """The largest table the build accepts (2^29 rows at the default load factor: 2^30 index slots; dim 4) filled to the last row by ONE
+    batch of 2^29 distinct keys, then one Adam step on every row, checked on sampled keys against closed forms;
+    one more new key must then be refused without side effects.  Exercises 64-bit offsets into the row storage."""
+    import torch
+    from paper_2201_05500_amd.binding import CTR_E_FULL, CTR_OK, CtrTable
+    free, _ = torch.cuda.mem_get_info()
+    if free < 100 << 30:
+        pytest.skip("needs 100 GiB of free device memory")
+    R, D, S = 1 << 29, 4, 64
+    G = R // S
+    lr, b1, b2, eps, std, seed = 1e-3, 0.9, 0.999, 1e-8, 0.01, 4
+    dev = "cuda:0"
+    gt = CtrTable(R, D, lr=lr, beta1=b1, beta2=b2, eps=eps, init_seed=seed, init_std=std)
+    keys = torch.arange(1, R + 1, dtype=torch.int64, device=dev)
+    offs = (torch.arange(G + 1, dtype=torch.int64, device=dev) * S).to(torch.int32)
+    _say(capsys, "max capacity: R =", R)
+    st, gb, pooled = gt.pull_pool(0, keys, offs)
+    assert st == CTR_OK and gt.last_status() == CTR_OK
+    assert gt.n_rows == R
+    _say(capsys, "pull done, table full")
+    rng = np.random.default_rng(2)
+    segs = np.concatenate([[0, G - 1], rng.integers(0, G, 300)])
+    got = pooled[torch.from_numpy(segs).to(dev)].cpu().numpy().astype(np.float64)
+    for i, g in enumerate(segs):
+        want = np.sum([[np.float64(O.init_value(seed, int(g) * S + j + 1, d, std)) for d in range(D)] for j in range(S)],
+                      axis=0)
+        assert np.all(np.abs(got[i] - want) <= S * (ATOL + RTOL * 0.1)), ("pooled", g)
+    del pooled
+    grad = torch.ones((G, D), dtype=torch.float32, device=dev)
+    assert gt.push_adam(0, gb, grad) == CTR_OK and gt.last_status() == CTR_OK
+    u, n_new = gt.batch_stats()
+    assert u == R and n_new == R
+    _say(capsys, "push done")
+    sample = np.concatenate([[1, 2, R - 1, R], rng.integers(1, R + 1, 2000)]).astype(np.int64)
+    st, x, m, v, found = gt.table_collect(0, torch.from_numpy(sample).to(dev))
+    assert st == CTR_OK and bool(found.all())
+    init = np.array([[O.init_value(seed, int(k), d, std) for d in range(D)] for k in sample], np.float32)
+    m_w = 1 - np.float64(np.float32(b1))
+    v_w = np.float64(np.float32(b2)) * np.float64(np.float32(eps)) + (1 - np.float64(np.float32(b2)))
+    x_w = init.astype(np.float64) - np.float64(np.float32(lr)) * np.float64(np.float32(m_w)) / np.sqrt(np.float64(np.float32(v_w)))
+    for name, got_a, want_a in (("m", m, np.full_like(x_w, m_w)), ("v", v, np.full_like(x_w, v_w)), ("x", x, x_w)):
+        ga = got_a.cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(ga - want_a) <= ATOL + RTOL * np.abs(want_a)), name
+    # one key too many: refused, nothing changes
+    extra = torch.tensor([R + 5], dtype=torch.int64, device=dev)
+    st, _, _ = gt.pull_pool(0, extra, torch.tensor([0, 1], dtype=torch.int32, device=dev))
+    assert st == CTR_OK and gt.last_status() == CTR_E_FULL and gt.n_rows == R
+    st, _, _, _, found = gt.table_collect(0, extra)
+    assert st == CTR_OK and int(found[0]) == 0
+    st, x2, _, _, found = gt.table_collect(0, torch.from_numpy(sample[:8]).to(dev))
+    assert bool(found.all()) and torch.equal(x2, x[:8])
