@@ -51,7 +51,8 @@ extern "C" {
 #endif
 
 typedef struct ctr_table ctr_table; /* opaque host-side handle */
-typedef struct ctr_batch ctr_batch; /* opaque: dedup result of one pull */
+typedef struct ctr_batch ctr_batch; /* opaque token for the dedup result of one pull: never dereferenced by the
+                                       caller, never reused by the table, so a stale one is always recognised */
 
 typedef enum {
   CTR_OK = 0,

@@ -155,7 +155,10 @@ struct ctr_table {
   u64 seed_mul;
   float init_scale;
   u64 generation;
-  ctr_batch* live;
+  // At most one batch is live per table: it is kept here, and the handle the caller holds is its
+  // generation number (never reused), so a stale handle can never be mistaken for a live one.
+  ctr_batch cur;
+  bool has_live;
   bool profile;
   // stage timers: one (start, stop) event pair per recorded execution since the last read
   std::vector<hipEvent_t> ev_start[CTR_N_STAGES], ev_stop[CTR_N_STAGES];
@@ -202,6 +205,11 @@ struct StageTimer {
   }
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? CTR_OK : CTR_E_DEVICE; }
+
+// The batch a caller's handle stands for, or null if it is not the table's live one.
+inline ctr_batch* live_batch(ctr_table* t, const ctr_batch* handle) {
+  return (t->has_live && (uintptr_t)handle == (uintptr_t)t->cur.generation) ? &t->cur : nullptr;
+}
 
 int status_code_from_bits(u32 bits) {
   if (bits & ST_INVAL) return CTR_E_INVAL;
@@ -296,7 +304,7 @@ int ctr_table_create(const ctr_config* cfg, void* d_mem, size_t bytes, void* hip
   t->seed_mul = cfg->init_seed * 0x9E3779B97F4A7C15ull;
   t->init_scale = (float)((double)cfg->init_std / 37837.2);
   t->generation = 0;
-  t->live = nullptr;
+  t->has_live = false;
   t->profile = false;
   for (int i = 0; i < CTR_N_STAGES; ++i) t->ev_used[i] = 0;
   hipStream_t st = (hipStream_t)hip_stream;
@@ -314,10 +322,6 @@ int ctr_table_create(const ctr_config* cfg, void* d_mem, size_t bytes, void* hip
 
 int ctr_table_destroy(ctr_table* t) {
   if (!t) return CTR_E_INVAL;
-  if (t->live) {
-    delete t->live;
-    t->live = nullptr;
-  }
   for (int i = 0; i < CTR_N_STAGES; ++i) {
     for (hipEvent_t e : t->ev_start[i]) (void)hipEventDestroy(e);
     for (hipEvent_t e : t->ev_stop[i]) (void)hipEventDestroy(e);
@@ -339,12 +343,8 @@ static int pull_pool_impl(ctr_table* t, uint32_t replica, const uint64_t* d_keys
   work_layout(t->D, n_keys, &wl);
   if (workspace_bytes < wl.total) return CTR_E_NOMEM;
 
-  ctr_batch* b = new (std::nothrow) ctr_batch();
-  if (!b) return CTR_E_NOMEM;
-  if (t->live) {  // an unpushed batch goes stale
-    delete t->live;
-    t->live = nullptr;
-  }
+  t->has_live = false;  // an unpushed batch goes stale
+  ctr_batch* b = &t->cur;
   b->t = t;
   b->generation = ++t->generation;
   b->replica = replica;
@@ -397,12 +397,9 @@ static int pull_pool_impl(ctr_table* t, uint32_t replica, const uint64_t* d_keys
     b->sorted_rows = (u32*)kin;
     b->sorted_segs = (u32*)vin;
   }
-  if (launch_status() != CTR_OK) {
-    delete b;
-    return CTR_E_DEVICE;
-  }
-  t->live = b;
-  *batch_out = b;
+  if (launch_status() != CTR_OK) return CTR_E_DEVICE;
+  t->has_live = true;
+  *batch_out = (ctr_batch*)(uintptr_t)b->generation;
   return CTR_OK;
 }
 
@@ -422,16 +419,17 @@ int ctr_pull_pool_bf16(ctr_table* t, uint32_t replica, const uint64_t* d_keys, u
                         workspace_bytes, batch_out, hip_stream);
 }
 
-int ctr_push_adam(ctr_table* t, uint32_t replica, ctr_batch* batch, const float* d_grad_pooled, uint32_t mode,
+int ctr_push_adam(ctr_table* t, uint32_t replica, ctr_batch* handle, const float* d_grad_pooled, uint32_t mode,
                   void* hip_stream) {
-  if (!t || !batch) return CTR_E_INVAL;
+  if (!t || !handle) return CTR_E_INVAL;
   if (replica >= t->W) return CTR_E_INVAL;
   if (mode != CTR_STEP_LOCAL && mode != CTR_STEP_MERGE_PENDING) return CTR_E_INVAL;
   const uint32_t flags = t->cfg.flags;
   const bool kstep = (flags & CTR_F_KSTEP) != 0;
   const bool prose = (flags & CTR_F_KSTEP_PROSE) != 0;
   if ((!kstep || prose) && mode != CTR_STEP_LOCAL) return CTR_E_INVAL;  // only Algorithm 2 as printed defers a step
-  if (t->live != batch) return CTR_E_STATE;  // stale, foreign or already consumed
+  ctr_batch* batch = live_batch(t, handle);
+  if (!batch) return CTR_E_STATE;  // stale, foreign or already consumed
   if (batch->replica != replica) return CTR_E_STATE;
   if (batch->n_seg > 0 && !d_grad_pooled) return CTR_E_INVAL;
 
@@ -495,8 +493,7 @@ int ctr_push_adam(ctr_table* t, uint32_t replica, ctr_batch* batch, const float*
 #undef CTR_SPAN_LAUNCH
 #undef CTR_FIXUP_LAUNCH
   }
-  t->live = nullptr;
-  delete batch;
+  t->has_live = false;
   return launch_status();
 }
 
@@ -526,10 +523,7 @@ int ctr_table_load(ctr_table* t, const uint64_t* d_keys, uint64_t n_keys, const 
   WorkLayout wl;
   work_layout(t->D, n_keys, &wl);
   if (workspace_bytes < wl.total) return CTR_E_NOMEM;
-  if (t->live) {  // the workspace of an unpushed batch may be this one: it goes stale
-    delete t->live;
-    t->live = nullptr;
-  }
+  t->has_live = false;  // the workspace of an unpushed batch may be this one: it goes stale
   ++t->generation;
   hipStream_t st = (hipStream_t)hip_stream;
   const u32 n = (u32)n_keys;
@@ -609,10 +603,11 @@ int ctr_table_export(ctr_table* t, uint32_t replica, uint64_t* h_keys, float* h_
   return ok ? CTR_OK : CTR_E_DEVICE;
 }
 
-int ctr_batch_export(ctr_table* t, ctr_batch* batch, uint64_t* n_unique, uint64_t* h_uniq, uint32_t* h_rows,
+int ctr_batch_export(ctr_table* t, ctr_batch* handle, uint64_t* n_unique, uint64_t* h_uniq, uint32_t* h_rows,
                      uint32_t* h_inverse, void* hip_stream) {
-  if (!t || !batch) return CTR_E_INVAL;
-  if (t->live != batch) return CTR_E_STATE;
+  if (!t || !handle) return CTR_E_INVAL;
+  const ctr_batch* batch = live_batch(t, handle);
+  if (!batch) return CTR_E_STATE;
   hipStream_t st = (hipStream_t)hip_stream;
   DevHeader h;
   if (hipMemcpyAsync(&h, t->hdr, sizeof(h), hipMemcpyDeviceToHost, st) != hipSuccess) return CTR_E_DEVICE;

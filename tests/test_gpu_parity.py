@@ -239,6 +239,13 @@ def test_host_detected_errors():
     assert gt.push_adam(1, b2, bt["grad"], 9) == B.CTR_E_INVAL
     assert gt.push_adam(1, b2, bt["grad"]) == B.CTR_OK
     assert gt.push_adam(1, b2, bt["grad"]) == B.CTR_E_STATE          # consumed
+    handles = {b1, b2}
+    for _ in range(6):                                               # handles are never reused: old ones stay stale
+        st, b, _ = gt.pull_pool(0, bt["keys"], bt["offsets"])
+        assert st == B.CTR_OK and b not in handles
+        assert all(gt.push_adam(0, old, bt["grad"]) == B.CTR_E_STATE for old in handles)
+        handles.add(b)
+    assert gt.push_adam(0, b, bt["grad"]) == B.CTR_OK
     assert gt.pull_pool(2, bt["keys"], bt["offsets"])[0] == B.CTR_E_INVAL
     st, _ = B.ctr_pull_pool(gt._handle, 0, bt["keys"].data_ptr(), 2, bt["offsets"].data_ptr(), 1,
                             torch.empty(8, device="cuda").data_ptr(), gt._ws.data_ptr(), 16, gt.stream)
