@@ -9,15 +9,16 @@
  * gradient of the pooled embeddings (the input of ctr_push_adam), and the dense optimizer.
  *
  * Arithmetic: matrix products take bf16 operands with fp32 accumulation on the matrix cores
- * (rocBLAS gemm_ex; everything else is hand-written HIP).  Master parameters, moments and the
+ * (vendor GEMM kernels through hipBLASLt, rocBLAS as the fallback; everything else is
+ * hand-written HIP).  Master parameters, moments and the
  * optimizer are fp32/fp64 exactly as in the sparse path: m0 = 0, v0 = eps, no bias correction,
  * x -= lr m / sqrt(den) with den = own v (one replica) or the shared v frozen at the last merge.
  * Rounding to bf16 (nearest-even) happens at: the input, the weight copies used by the products,
  * every hidden activation, and every back-propagated hidden gradient.
  *
  * Conventions are those of ctr_sparse.h: d_* device pointers owned by the caller, `hip_stream`
- * a hipStream_t, calls enqueue only, status codes of ctr_status.  The rocBLAS handle the tower
- * owns keeps its own device workspace.
+ * a hipStream_t, calls enqueue only, status codes of ctr_status.  The library handles the tower
+ * owns may keep small device allocations of their own.
  */
 #ifndef CTR_MLP_H
 #define CTR_MLP_H
@@ -80,6 +81,16 @@ int ctr_mlp_step_bf16(ctr_mlp* m, uint32_t replica, const uint16_t* d_pooled_bf1
                       size_t workspace_bytes, uint32_t mode, void* hip_stream);
 int ctr_mlp_forward_bf16(ctr_mlp* m, uint32_t replica, const uint16_t* d_pooled_bf16, uint32_t batch,
                          float* d_logits, void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Optional set-up call: for every matrix product of a step at this batch size, times each
+ * applicable matrix-core kernel of the vendor library on synthetic operands and keeps the fastest
+ * one whose result agrees with the default kernel's (to 1e-3 of the largest element) and repeats
+ * bit for bit; steps at this batch size then use those kernels (a call with another batch size
+ * drops them).  Takes a few seconds, synchronises the stream, overwrites d_workspace
+ * (>= ctr_mlp_tune_workspace_bytes(cfg, batch), 256-byte aligned; larger than the step's), leaves
+ * parameters and optimizer state untouched.  Errors: CTR_E_INVAL, CTR_E_NOMEM, CTR_E_DEVICE. */
+size_t ctr_mlp_tune_workspace_bytes(const ctr_mlp_config* cfg, uint32_t batch);
+int ctr_mlp_tune(ctr_mlp* m, uint32_t batch, void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Algorithm 2's global-averaging branch over all dense parameters of the W replicas:
  * shared v = mean_j v_j; x_i = mean_j (x_j - [merge step pending in j] lr m_j / sqrt(shared v)). */

@@ -9,7 +9,7 @@ from .binding import CTR_OK, CTR_STEP_LOCAL, lib as _base_lib
 
 CTR_MLP_MAX_HIDDEN = 6
 EXPORTED = ("ctr_mlp_bytes", "ctr_mlp_workspace_bytes", "ctr_mlp_create", "ctr_mlp_destroy", "ctr_mlp_step",
-            "ctr_mlp_forward", "ctr_mlp_step_bf16", "ctr_mlp_forward_bf16", "ctr_mlp_kstep_merge", "ctr_mlp_n_params", "ctr_mlp_export")
+            "ctr_mlp_forward", "ctr_mlp_step_bf16", "ctr_mlp_forward_bf16", "ctr_mlp_tune_workspace_bytes", "ctr_mlp_tune", "ctr_mlp_kstep_merge", "ctr_mlp_n_params", "ctr_mlp_export")
 
 
 class ctr_mlp_config(C.Structure):
@@ -54,6 +54,10 @@ def lib():
         L.ctr_mlp_step_bf16.argtypes = L.ctr_mlp_step.argtypes
         L.ctr_mlp_forward_bf16.restype = ci
         L.ctr_mlp_forward_bf16.argtypes = L.ctr_mlp_forward.argtypes
+        L.ctr_mlp_tune_workspace_bytes.restype = sz
+        L.ctr_mlp_tune_workspace_bytes.argtypes = [cfgp, u32]
+        L.ctr_mlp_tune.restype = ci
+        L.ctr_mlp_tune.argtypes = [vp, u32, vp, sz, vp]
         L.ctr_mlp_kstep_merge.restype = ci
         L.ctr_mlp_kstep_merge.argtypes = [vp, vp]
         L.ctr_mlp_export.restype = ci
@@ -139,6 +143,18 @@ class CtrMlp:
         st = fn(self._handle, replica, pooled.data_ptr(), B, logits.data_ptr(), self._ws.data_ptr(), self.ws_bytes,
                 self.stream)
         return st, logits
+
+    def tune(self, batch):
+        """Kernel search for the products of a step at this batch size (set-up call, seconds)."""
+        torch = self._torch
+        need = int(lib().ctr_mlp_tune_workspace_bytes(C.byref(self.cfg), batch))
+        if need == 0:
+            raise ValueError("invalid batch")
+        tmp = torch.empty(need, dtype=torch.uint8, device=self.device)
+        st = lib().ctr_mlp_tune(self._handle, batch, tmp.data_ptr(), need, self.stream)
+        torch.cuda.synchronize(self.device)
+        del tmp
+        return st
 
     def kstep_merge(self):
         return lib().ctr_mlp_kstep_merge(self._handle, self.stream)

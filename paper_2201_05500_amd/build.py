@@ -20,7 +20,7 @@ def sources():
 
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB] + sources() + ["-lrocblas"]  # bf16 GEMMs of the dense tower
+    cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB] + sources() + ["-lrocblas", "-lhipblaslt"]  # bf16 GEMMs of the dense tower
     if verbose:
         print(" ".join(cmd))
     subprocess.check_call(cmd)

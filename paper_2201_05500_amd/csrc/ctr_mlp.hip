@@ -1,13 +1,20 @@
-// Host side of the dense-tower C ABI (include/ctr_mlp.h): memory layout, the sequence of rocBLAS
-// bf16 GEMMs and hand-written kernels of one training step, the dense optimizer and its merge.
+// Host side of the dense-tower C ABI (include/ctr_mlp.h): memory layout, the sequence of library
+// bf16 GEMMs (hipBLASLt with a kernel chosen per product, rocBLAS as the fallback) and hand-written
+// kernels of one training step, the dense optimizer and its merge.
 #include "../../include/ctr_mlp.h"
 #include "../../include/ctr_sparse.h"
 
+#include <hipblaslt/hipblaslt.h>
+#include <hipblaslt/hipblaslt-ext.hpp>
 #include <rocblas/rocblas.h>
 
 #include <algorithm>
 #include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
 #include <new>
+#include <vector>
 
 #include "common.h"
 #include "mlp_kernels.h"
@@ -17,6 +24,14 @@ using namespace ctr;
 namespace {
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+// Scratch a split-K product kernel may ask for: room for four partial copies of the largest weight
+// gradient (products with a small result and a long contraction are split along the batch).
+size_t lt_ws_bytes(const ctr_mlp_config* c) {
+  size_t mx = 0;
+  for (u32 l = 0; l < c->n_hidden; ++l)
+    mx = std::max(mx, (size_t)(l == 0 ? c->in_dim : c->hidden[l - 1]) * c->hidden[l] * sizeof(float));
+  return std::min<size_t>(std::max<size_t>(align256(4 * mx), (size_t)32 << 20), (size_t)512 << 20);
+}
 inline u32 blocks_for(u64 threads) { return (u32)((threads + BLOCK - 1) / BLOCK); }
 
 bool mlp_config_ok(const ctr_mlp_config* c) {
@@ -67,7 +82,7 @@ void mem_layout(const ctr_mlp_config* c, const MlpLayout& L, MemLayout* M) {
 struct WsLayout {
   u32 max_h;
   size_t off_h0, off_act[CTR_MLP_MAX_HIDDEN], off_z, off_da, off_dz[2], off_logits, off_dlogit, off_lterm, off_grads,
-      off_partial, total;
+      off_partial, off_lt_ws, lt_ws, total;
 };
 
 void ws_layout(const ctr_mlp_config* c, const MlpLayout& L, u32 B, WsLayout* S) {
@@ -89,12 +104,30 @@ void ws_layout(const ctr_mlp_config* c, const MlpLayout& L, u32 B, WsLayout* S) 
   S->off_lterm = o; o += align256((size_t)B * sizeof(double));
   S->off_grads = o; o += align256((size_t)L.n_params * sizeof(float));
   S->off_partial = o; o += align256((size_t)COLSUM_SLICES * mh * sizeof(float));
+  S->off_lt_ws = o; S->lt_ws = lt_ws_bytes(c); o += S->lt_ws;
   S->total = o;
 }
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? CTR_OK : CTR_E_DEVICE; }
 
 }  // namespace
+
+// The three products of a hidden layer.  Row-major matrices are handed to the column-major
+// library as the column-major matrices of their transposes ((XY)^T = Y^T X^T):
+//   OP_FWD  Z[B x o]  = H[B x i] W[i x o]      -> gemm(N, N, m = o, n = B, k = i)
+//   OP_DW   dW[i x o] = H^T[i x B] dZ[B x o]   -> gemm(N, T, m = o, n = i, k = B)
+//   OP_DH   dH[B x i] = dZ[B x o] W^T[o x i]   -> gemm(T, N, m = i, n = B, k = o)
+enum { OP_FWD = 0, OP_DW = 1, OP_DH = 2, N_OPS = 3 };
+
+struct LtPlan {
+  bool ready = false;  // descriptors exist and an algorithm was found
+  bool tuned = false;  // the algorithm is the winner of ctr_mlp_tune, not the library's first guess
+  hipblasLtMatmulDesc_t desc = nullptr;
+  hipblasLtMatrixLayout_t la = nullptr, lb = nullptr, lc = nullptr;
+  hipblasLtMatmulAlgo_t algo;
+  size_t ws = 0;
+  int m = 0, n = 0, k = 0;
+};
 
 struct ctr_mlp {
   ctr_mlp_config cfg;
@@ -104,21 +137,258 @@ struct ctr_mlp {
   float *params, *m, *v, *vhat;
   bf16_t* pb;
   rocblas_handle blas;
+  hipblasLtHandle_t lt;
+  u32 plan_batch;  // batch size the plans were made for (0: none)
+  LtPlan plans[CTR_MLP_MAX_HIDDEN][N_OPS];
   u32 pend_mask;  // replicas whose last step was a merge step not merged yet
 };
 
 namespace {
 
-// Row-major C[M x N] = A[M x K] B[K x N] and its two transposed forms, written for a column-major
-// library through (XY)^T = Y^T X^T: a row-major matrix is the column-major matrix of its transpose.
-bool gemm(ctr_mlp* t, rocblas_operation opa, rocblas_operation opb, int m, int n, int k, const void* a, int lda,
-          const void* b, int ldb, float* c, int ldc) {
-  const float alpha = 1.0f, beta = 0.0f;
-  return rocblas_gemm_ex(t->blas, opa, opb, m, n, k, &alpha, a, rocblas_datatype_bf16_r, lda, b,
-                         rocblas_datatype_bf16_r, ldb, &beta, c, rocblas_datatype_f32_r, ldc, c,
-                         rocblas_datatype_f32_r, ldc, rocblas_datatype_f32_r, rocblas_gemm_algo_standard, 0,
-                         0) == rocblas_status_success;
+struct GemmShape {
+  hipblasOperation_t opa, opb;
+  int m, n, k, lda, ldb, ldc;
+};
+
+GemmShape shape_of(const MlpLayout& L, u32 l, int op, u32 B) {
+  const int i = (int)L.in[l], o = (int)L.out[l], b = (int)B;
+  switch (op) {
+    case OP_FWD: return {HIPBLAS_OP_N, HIPBLAS_OP_N, o, b, i, o, i, o};
+    case OP_DW: return {HIPBLAS_OP_N, HIPBLAS_OP_T, o, i, b, o, i, o};
+    default: return {HIPBLAS_OP_T, HIPBLAS_OP_N, i, b, o, o, o, i};
+  }
 }
+
+void destroy_plan(LtPlan* p) {
+  if (p->desc) (void)hipblasLtMatmulDescDestroy(p->desc);
+  if (p->la) (void)hipblasLtMatrixLayoutDestroy(p->la);
+  if (p->lb) (void)hipblasLtMatrixLayoutDestroy(p->lb);
+  if (p->lc) (void)hipblasLtMatrixLayoutDestroy(p->lc);
+  *p = LtPlan();
+}
+
+void destroy_plans(ctr_mlp* t) {
+  for (u32 l = 0; l < CTR_MLP_MAX_HIDDEN; ++l)
+    for (int op = 0; op < N_OPS; ++op) destroy_plan(&t->plans[l][op]);
+  t->plan_batch = 0;
+}
+
+// Descriptors of one product and the library's own first choice of kernel for it.
+bool make_plan(ctr_mlp* t, u32 l, int op, u32 B, LtPlan* p) {
+  const GemmShape g = shape_of(t->L, l, op, B);
+  const bool ok = hipblasLtMatmulDescCreate(&p->desc, HIPBLAS_COMPUTE_32F, HIP_R_32F) == HIPBLAS_STATUS_SUCCESS &&
+                  hipblasLtMatmulDescSetAttribute(p->desc, HIPBLASLT_MATMUL_DESC_TRANSA, &g.opa, sizeof(g.opa)) ==
+                      HIPBLAS_STATUS_SUCCESS &&
+                  hipblasLtMatmulDescSetAttribute(p->desc, HIPBLASLT_MATMUL_DESC_TRANSB, &g.opb, sizeof(g.opb)) ==
+                      HIPBLAS_STATUS_SUCCESS &&
+                  hipblasLtMatrixLayoutCreate(&p->la, HIP_R_16BF, g.opa == HIPBLAS_OP_N ? g.m : g.k,
+                                              g.opa == HIPBLAS_OP_N ? g.k : g.m, g.lda) == HIPBLAS_STATUS_SUCCESS &&
+                  hipblasLtMatrixLayoutCreate(&p->lb, HIP_R_16BF, g.opb == HIPBLAS_OP_N ? g.k : g.n,
+                                              g.opb == HIPBLAS_OP_N ? g.n : g.k, g.ldb) == HIPBLAS_STATUS_SUCCESS &&
+                  hipblasLtMatrixLayoutCreate(&p->lc, HIP_R_32F, g.m, g.n, g.ldc) == HIPBLAS_STATUS_SUCCESS;
+  if (!ok) return false;
+  p->m = g.m; p->n = g.n; p->k = g.k;
+  hipblasLtMatmulPreference_t pref = nullptr;
+  if (hipblasLtMatmulPreferenceCreate(&pref) != HIPBLAS_STATUS_SUCCESS) return false;
+  const uint64_t max_ws = lt_ws_bytes(&t->cfg);
+  hipblasLtMatmulHeuristicResult_t res[4];
+  int n_res = 0;
+  bool found = hipblasLtMatmulPreferenceSetAttribute(pref, HIPBLASLT_MATMUL_PREF_MAX_WORKSPACE_BYTES, &max_ws,
+                                                      sizeof(max_ws)) == HIPBLAS_STATUS_SUCCESS &&
+               hipblasLtMatmulAlgoGetHeuristic(t->lt, p->desc, p->la, p->lb, p->lc, p->lc, pref, 4, res, &n_res) ==
+                   HIPBLAS_STATUS_SUCCESS;
+  (void)hipblasLtMatmulPreferenceDestroy(pref);
+  if (!found) return false;
+  for (int r = 0; r < n_res; ++r) {
+    if (res[r].state == HIPBLAS_STATUS_SUCCESS && res[r].workspaceSize <= max_ws) {
+      p->algo = res[r].algo;
+      p->ws = res[r].workspaceSize;
+      p->ready = true;
+      return true;
+    }
+  }
+  return false;
+}
+
+// Plans are made for one batch size and kept until a call comes with another.
+void ensure_plans(ctr_mlp* t, u32 B) {
+  if (t->plan_batch == B || !t->lt) return;
+  destroy_plans(t);
+  for (u32 l = 0; l + 1 < t->L.n_layers; ++l)
+    for (int op = 0; op < N_OPS; ++op)
+      if (!make_plan(t, l, op, B, &t->plans[l][op])) destroy_plan(&t->plans[l][op]);
+  t->plan_batch = B;
+}
+
+// One product on the matrix cores: the planned hipBLASLt kernel, else rocBLAS's default.
+bool product(ctr_mlp* t, u32 l, int op, u32 B, const void* a, const void* b, float* c, char* ws, const WsLayout& S,
+             hipStream_t st) {
+  const float alpha = 1.0f, beta = 0.0f;
+  const LtPlan& p = t->plans[l][op];
+  if (t->plan_batch == B && p.ready)
+    return hipblasLtMatmul(t->lt, p.desc, &alpha, a, p.la, b, p.lb, &beta, c, p.lc, c, p.lc, &p.algo,
+                           ws + S.off_lt_ws, p.ws, st) == HIPBLAS_STATUS_SUCCESS;
+  const GemmShape g = shape_of(t->L, l, op, B);
+  return rocblas_gemm_ex(t->blas, g.opa == HIPBLAS_OP_N ? rocblas_operation_none : rocblas_operation_transpose,
+                         g.opb == HIPBLAS_OP_N ? rocblas_operation_none : rocblas_operation_transpose, g.m, g.n, g.k,
+                         &alpha, a, rocblas_datatype_bf16_r, g.lda, b, rocblas_datatype_bf16_r, g.ldb, &beta, c,
+                         rocblas_datatype_f32_r, g.ldc, c, rocblas_datatype_f32_r, g.ldc, rocblas_datatype_f32_r,
+                         rocblas_gemm_algo_standard, 0, 0) == rocblas_status_success;
+}
+
+// ---------------------------------------------------------------- kernel search (ctr_mlp_tune)
+
+size_t tune_result_bytes(const MlpLayout& L, u32 B) {
+  size_t mx = 0;
+  for (u32 l = 0; l + 1 < L.n_layers; ++l) {
+    mx = std::max(mx, (size_t)B * L.out[l]);        // forward
+    mx = std::max(mx, (size_t)L.in[l] * L.out[l]);  // weight gradient
+    mx = std::max(mx, (size_t)B * L.in[l]);         // input gradient
+  }
+  return align256(mx * sizeof(float));
+}
+
+struct Tuner {
+  ctr_mlp* t;
+  hipStream_t st;
+  char* ws;
+  const WsLayout& S;
+  u32* d_words;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  bool ok = false;
+
+  Tuner(ctr_mlp* t_, hipStream_t st_, char* ws_, const WsLayout& S_, u32* d_words_)
+      : t(t_), st(st_), ws(ws_), S(S_), d_words(d_words_) {
+    if (hipEventCreate(&e0) != hipSuccess) return;
+    if (hipEventCreate(&e1) != hipSuccess) return;
+    ok = true;
+  }
+  ~Tuner() {
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+  }
+
+  // Milliseconds of one run of `algo` into `out`, or a negative value if the library refuses it.
+  float run(const LtPlan& p, const hipblasLtMatmulAlgo_t& algo, size_t wsz, const void* a, const void* b, float* out) {
+    const float alpha = 1.0f, beta = 0.0f;
+    if (hipEventRecord(e0, st) != hipSuccess) return -1.0f;
+    const hipblasStatus_t rc = hipblasLtMatmul(t->lt, p.desc, &alpha, a, p.la, b, p.lb, &beta, out, p.lc, out, p.lc,
+                                               &algo, ws + S.off_lt_ws, wsz, st);
+    if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) return -1.0f;
+    if (rc != HIPBLAS_STATUS_SUCCESS) return -1.0f;
+    float ms = -1.0f;
+    if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) return -1.0f;
+    return ms;
+  }
+
+  bool read_words(u32 h[4]) {
+    return hipMemcpyAsync(h, d_words, 4 * sizeof(u32), hipMemcpyDeviceToHost, st) == hipSuccess &&
+           hipStreamSynchronize(st) == hipSuccess;
+  }
+
+  // The candidate agrees with the reference (accumulation order aside) and repeats bit for bit.
+  bool valid(const LtPlan& p, const hipblasLtMatmulAlgo_t& algo, size_t wsz, const void* a, const void* b,
+             const float* ref, float* cand, u64 n) {
+    u32 h1[4], h2[4];
+    for (int rep = 0; rep < 2; ++rep) {
+      if (hipMemsetAsync(d_words, 0, 4 * sizeof(u32), st) != hipSuccess) return false;
+      if (run(p, algo, wsz, a, b, cand) < 0.0f) return false;
+      hipLaunchKernelGGL(k_max_diff, dim3(2048), dim3(BLOCK), 0, st, ref, cand, n, d_words);
+      hipLaunchKernelGGL(k_hash_bits, dim3(2048), dim3(BLOCK), 0, st, cand, n, (unsigned long long*)(d_words + 2));
+      if (!read_words(rep ? h2 : h1)) return false;
+    }
+    float md, ma;
+    memcpy(&md, &h1[0], 4);
+    memcpy(&ma, &h1[1], 4);
+    return md <= 1e-3f * ma && h1[2] == h2[2] && h1[3] == h2[3];
+  }
+
+  // Replaces the plan's kernel by the fastest applicable one that passes valid().  A product for
+  // which nothing better is found keeps the library's choice.  Returns false on a device error only.
+  bool tune_one(u32 l, int op, u32 B, float* ref, float* cand) {
+    LtPlan& p = t->plans[l][op];
+    if (!p.ready) {
+      if (getenv("CTR_MLP_TUNE_LOG")) fprintf(stderr, "ctr_mlp_tune: layer %u product %d: no plan (rocBLAS runs it)\n", l, op);
+      return true;
+    }
+    const MlpLayout& L = t->L;
+    bf16_t* act_in = l == 0 ? (bf16_t*)(ws + S.off_h0) : (bf16_t*)(ws + S.off_act[l - 1]);  // B x in_l
+    bf16_t* dzb = (bf16_t*)(ws + S.off_dz[0]);                                              // B x out_l
+    const bf16_t* w = t->pb + L.w_off[l];
+    const void* a = op == OP_DW ? (const void*)dzb : (const void*)w;
+    const void* b = op == OP_DH ? (const void*)dzb : (const void*)act_in;
+    const u64 n = (u64)p.m * p.n;
+    hipLaunchKernelGGL(k_fill_pattern_bf16, dim3(2048), dim3(BLOCK), 0, st, act_in, (u64)B * L.in[l], 0x1234u + l);
+    hipLaunchKernelGGL(k_fill_pattern_bf16, dim3(2048), dim3(BLOCK), 0, st, dzb, (u64)B * L.out[l], 0x9876u + l);
+    // reference: rocBLAS's own kernel for the same product
+    {
+      const float alpha = 1.0f, beta = 0.0f;
+      const GemmShape g = shape_of(L, l, op, B);
+      if (rocblas_gemm_ex(t->blas, g.opa == HIPBLAS_OP_N ? rocblas_operation_none : rocblas_operation_transpose,
+                          g.opb == HIPBLAS_OP_N ? rocblas_operation_none : rocblas_operation_transpose, g.m, g.n, g.k,
+                          &alpha, a, rocblas_datatype_bf16_r, g.lda, b, rocblas_datatype_bf16_r, g.ldb, &beta, ref,
+                          rocblas_datatype_f32_r, g.ldc, ref, rocblas_datatype_f32_r, g.ldc, rocblas_datatype_f32_r,
+                          rocblas_gemm_algo_standard, 0, 0) != rocblas_status_success)
+        return true;  // nothing to compare against: keep the plan as it is
+    }
+    std::vector<hipblasLtMatmulHeuristicResult_t> all;
+    const GemmShape g = shape_of(L, l, op, B);
+    if (hipblaslt_ext::getAllAlgos(t->lt, hipblaslt_ext::GemmType::HIPBLASLT_GEMM, g.opa, g.opb, HIP_R_16BF, HIP_R_16BF,
+                                   HIP_R_32F, HIP_R_32F, HIPBLAS_COMPUTE_32F, all) != HIPBLAS_STATUS_SUCCESS)
+      return true;
+    struct Timed { float ms; size_t idx, wsz; };
+    std::vector<Timed> timed;
+    size_t n_big = 0, n_sup = 0;
+    const float alpha = 1.0f, beta = 0.0f;
+    float best = run(p, p.algo, p.ws, a, b, cand);  // the current choice; the first run warms up
+    best = run(p, p.algo, p.ws, a, b, cand);
+    if (best >= 0.0f) best = std::min(best, run(p, p.algo, p.ws, a, b, cand));
+    if (best < 0.0f) {
+      if (getenv("CTR_MLP_TUNE_LOG")) fprintf(stderr, "ctr_mlp_tune: layer %u product %d: the planned kernel does not run\n", l, op);
+      return hipGetLastError() == hipSuccess;
+    }
+    const float current = best;
+    for (size_t i = 0; i < all.size(); ++i) {
+      size_t wsz = 0;
+      if (hipblaslt_ext::matmulIsAlgoSupported(t->lt, p.desc, &alpha, p.la, p.lb, &beta, p.lc, p.lc, all[i].algo, wsz) !=
+          HIPBLAS_STATUS_SUCCESS)
+        continue;
+      if (wsz > S.lt_ws) { ++n_big; continue; }
+      ++n_sup;
+      if (run(p, all[i].algo, wsz, a, b, cand) < 0.0f) continue;  // the first run of a kernel pays for loading it
+      float ms = run(p, all[i].algo, wsz, a, b, cand);
+      if (ms < 0.0f) continue;
+      if (ms < 1.1f * best) {  // a contender: one more look
+        const float ms2 = run(p, all[i].algo, wsz, a, b, cand);
+        if (ms2 >= 0.0f) ms = std::min(ms, ms2);
+      }
+      best = std::min(best, ms);
+      timed.push_back({ms, i, wsz});
+    }
+    std::sort(timed.begin(), timed.end(), [](const Timed& x, const Timed& y) { return x.ms < y.ms; });
+    const bool log = getenv("CTR_MLP_TUNE_LOG") != nullptr;
+    if (log)
+      fprintf(stderr, "ctr_mlp_tune: layer %u product %d (m %d n %d k %d): library's choice %.3f ms (index %d), %zu listed, %zu applicable, %zu need more scratch, %zu ran, fastest %.3f ms\n",
+              l, op, p.m, p.n, p.k, current, hipblaslt_ext::getIndexFromAlgo(p.algo), all.size(), n_sup, n_big, timed.size(), timed.empty() ? -1.0f : timed[0].ms);
+    if (log)
+      for (size_t r = 0; r < std::min<size_t>(timed.size(), 4); ++r)
+        fprintf(stderr, "ctr_mlp_tune:   #%zu %.3f ms ws %zu index %d %s\n", r, timed[r].ms, timed[r].wsz,
+                hipblaslt_ext::getIndexFromAlgo(all[timed[r].idx].algo),
+                hipblaslt_ext::getKernelNameFromAlgo(t->lt, all[timed[r].idx].algo).substr(0, 110).c_str());
+    for (const Timed& c : timed) {
+      if (c.ms >= 0.97f * current) break;  // not better than what the library chose by itself
+      const bool good = valid(p, all[c.idx].algo, c.wsz, a, b, ref, cand, n);
+      if (log) fprintf(stderr, "ctr_mlp_tune:   candidate %zu at %.3f ms: %s\n", c.idx, c.ms, good ? "taken" : "rejected");
+      if (good) {
+        p.algo = all[c.idx].algo;
+        p.ws = c.wsz;
+        p.tuned = true;
+        break;
+      }
+    }
+    return hipGetLastError() == hipSuccess;
+  }
+};
 
 // Forward through the hidden layers and the output layer; activations stay in the workspace.
 // The input is either fp32 (rounded to bf16 into the workspace) or already bf16 (used in place).
@@ -136,9 +406,7 @@ bool forward(ctr_mlp* t, u32 replica, const float* d_pooled, const bf16_t* d_poo
   }
   for (u32 l = 0; l + 1 < L.n_layers; ++l) {
     const int i = (int)L.in[l], o = (int)L.out[l];
-    // Z[B x o] = H[B x i] W[i x o]
-    if (!gemm(t, rocblas_operation_none, rocblas_operation_none, o, (int)B, i, PB + L.w_off[l], o, h, i, z, o))
-      return false;
+    if (!product(t, l, OP_FWD, B, PB + L.w_off[l], h, z, ws, S, st)) return false;
     bf16_t* a = (bf16_t*)(ws + S.off_act[l]);
     const u64 n = (u64)B * o;
     hipLaunchKernelGGL(k_bias_relu_bf16, dim3(blocks_for(n / 4)), dim3(BLOCK), 0, st, z,
@@ -204,6 +472,8 @@ int ctr_mlp_create(const ctr_mlp_config* cfg, void* d_mem, size_t bytes, void* h
     delete t;
     return CTR_E_DEVICE;
   }
+  if (hipblasLtCreate(&t->lt) != HIPBLAS_STATUS_SUCCESS) t->lt = nullptr;  // products then go through rocBLAS
+  t->plan_batch = 0;
   // fixed summation order: no atomics in the products
   (void)rocblas_set_atomics_mode(t->blas, rocblas_atomics_not_allowed);
   (void)rocblas_set_pointer_mode(t->blas, rocblas_pointer_mode_host);
@@ -213,6 +483,7 @@ int ctr_mlp_create(const ctr_mlp_config* cfg, void* d_mem, size_t bytes, void* h
                      t->v, t->vhat, t->pb);
   if (launch_status() != CTR_OK) {
     (void)rocblas_destroy_handle(t->blas);
+    if (t->lt) (void)hipblasLtDestroy(t->lt);
     delete t;
     return CTR_E_DEVICE;
   }
@@ -222,7 +493,9 @@ int ctr_mlp_create(const ctr_mlp_config* cfg, void* d_mem, size_t bytes, void* h
 
 int ctr_mlp_destroy(ctr_mlp* t) {
   if (!t) return CTR_E_INVAL;
+  destroy_plans(t);
   (void)rocblas_destroy_handle(t->blas);
+  if (t->lt) (void)hipblasLtDestroy(t->lt);
   delete t;
   return CTR_OK;
 }
@@ -238,6 +511,7 @@ static int mlp_forward_impl(ctr_mlp* t, uint32_t replica, const float* d_pooled,
   if (workspace_bytes < S.total) return CTR_E_NOMEM;
   hipStream_t st = (hipStream_t)hip_stream;
   if (rocblas_set_stream(t->blas, st) != rocblas_status_success) return CTR_E_DEVICE;
+  ensure_plans(t, batch);
   if (!forward(t, replica, d_pooled, d_pooled_bf16, batch, (char*)d_workspace, S, d_logits, st)) return CTR_E_DEVICE;
   return launch_status();
 }
@@ -256,6 +530,7 @@ static int mlp_step_impl(ctr_mlp* t, uint32_t replica, const float* d_pooled, co
   if (workspace_bytes < S.total) return CTR_E_NOMEM;
   hipStream_t st = (hipStream_t)hip_stream;
   if (rocblas_set_stream(t->blas, st) != rocblas_status_success) return CTR_E_DEVICE;
+  ensure_plans(t, batch);
 
   const MlpLayout& L = t->L;
   char* ws = (char*)d_workspace;
@@ -292,18 +567,14 @@ static int mlp_step_impl(ctr_mlp* t, uint32_t replica, const float* d_pooled, co
   for (int l = (int)lo - 1; l >= 0; --l) {
     const int i = (int)L.in[l], o = (int)L.out[l];
     const bf16_t* h_prev = l == 0 ? h0 : (const bf16_t*)(ws + S.off_act[l - 1]);
-    // dW[i x o] = H_prev^T[i x B] dZ[B x o]
-    if (!gemm(t, rocblas_operation_none, rocblas_operation_transpose, o, i, (int)B, dz, o, h_prev, i,
-              grads + L.w_off[l], o))
-      return CTR_E_DEVICE;
+    if (!product(t, (u32)l, OP_DW, B, dz, h_prev, grads + L.w_off[l], ws, S, st)) return CTR_E_DEVICE;
     hipLaunchKernelGGL(k_colsum_partial, dim3((o + 31) / 32, COLSUM_SLICES), dim3(BLOCK), 0, st, dz, (const float*)nullptr,
                        B, (u32)o, partial);
     hipLaunchKernelGGL(k_colsum_final, dim3(blocks_for(o)), dim3(BLOCK), 0, st, partial, (u32)o,
                        grads + L.w_off[l] + (u64)i * o);
     // dH_prev[B x i] = dZ[B x o] W^T[o x i]; for the first layer this is the gradient of the pooled input
     float* dst = l == 0 ? d_grad_pooled : da;
-    if (!gemm(t, rocblas_operation_transpose, rocblas_operation_none, i, (int)B, o, PB + L.w_off[l], o, dz, o, dst, i))
-      return CTR_E_DEVICE;
+    if (!product(t, (u32)l, OP_DH, B, PB + L.w_off[l], dz, dst, ws, S, st)) return CTR_E_DEVICE;
     if (l > 0) {
       const u64 n = (u64)B * i;
       hipLaunchKernelGGL(k_relu_bwd_bf16, dim3(blocks_for(n / 4)), dim3(BLOCK), 0, st, da, h_prev, n, dz_next);
@@ -347,6 +618,39 @@ int ctr_mlp_step_bf16(ctr_mlp* t, uint32_t replica, const uint16_t* d_pooled_bf1
   if (!d_pooled_bf16) return CTR_E_INVAL;
   return mlp_step_impl(t, replica, nullptr, d_pooled_bf16, d_labels, batch, d_grad_pooled, d_loss, d_workspace,
                        workspace_bytes, mode, hip_stream);
+}
+
+size_t ctr_mlp_tune_workspace_bytes(const ctr_mlp_config* cfg, uint32_t batch) {
+  if (!mlp_config_ok(cfg) || batch == 0 || batch % 8 != 0 || batch > CTR_MLP_MAX_BATCH) return 0;
+  MlpLayout L;
+  WsLayout S;
+  make_layout(cfg, &L);
+  ws_layout(cfg, L, batch, &S);
+  return S.total + 2 * tune_result_bytes(L, batch) + 256;
+}
+
+int ctr_mlp_tune(ctr_mlp* t, uint32_t batch, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!t || !d_workspace) return CTR_E_INVAL;
+  if (batch == 0 || batch % 8 != 0 || batch > CTR_MLP_MAX_BATCH) return CTR_E_INVAL;
+  if (((uintptr_t)d_workspace & 255) != 0) return CTR_E_INVAL;
+  WsLayout S;
+  ws_layout(&t->cfg, t->L, batch, &S);
+  const size_t res_bytes = tune_result_bytes(t->L, batch);
+  if (workspace_bytes < S.total + 2 * res_bytes + 256) return CTR_E_NOMEM;
+  if (!t->lt) return CTR_OK;  // no kernel to choose: the products run through rocBLAS
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (rocblas_set_stream(t->blas, st) != rocblas_status_success) return CTR_E_DEVICE;
+  ensure_plans(t, batch);
+  char* ws = (char*)d_workspace;
+  float* ref = (float*)(ws + S.total);
+  float* cand = (float*)(ws + S.total + res_bytes);
+  u32* d_words = (u32*)(ws + S.total + 2 * res_bytes);  // [0..1] max diff / max abs, [2..3] a 64-bit hash
+  Tuner tu(t, st, ws, S, d_words);
+  if (!tu.ok) return CTR_E_DEVICE;
+  for (u32 l = 0; l + 1 < t->L.n_layers; ++l)
+    for (int op = 0; op < N_OPS; ++op)
+      if (!tu.tune_one(l, op, batch, ref, cand)) return CTR_E_DEVICE;
+  return launch_status();
 }
 
 int ctr_mlp_kstep_merge(ctr_mlp* t, void* hip_stream) {

@@ -223,4 +223,45 @@ __global__ void k_dense_merge(float* __restrict__ params, const float* __restric
   }
 }
 
+// ---------------------------------------------------------------- helpers of the kernel search
+
+// Bounded pseudo-random bf16 values in (-1/16, 1/16): operands for timing and checking a product.
+__global__ void k_fill_pattern_bf16(bf16_t* __restrict__ dst, u64 n, u32 seed) {
+  for (u64 i = (u64)blockIdx.x * BLOCK + threadIdx.x; i < n; i += (u64)gridDim.x * BLOCK) {
+    u32 x = (u32)i * 2654435761u + seed;
+    x ^= x >> 15; x *= 2246822519u; x ^= x >> 13;
+    dst[i] = to_bf16(((int)(x & 0xFFFFu) - 32768) * (1.0f / 524288.0f));
+  }
+}
+
+// out[0] = max |a - b|, out[1] = max |a| as float bit patterns (non-negative floats order like
+// unsigned integers); a NaN anywhere sets out[0] to the pattern of +inf.  out[] zeroed by the caller.
+__global__ void k_max_diff(const float* __restrict__ a, const float* __restrict__ b, u64 n, u32* __restrict__ out) {
+  float md = 0.0f, ma = 0.0f;
+  for (u64 i = (u64)blockIdx.x * BLOCK + threadIdx.x; i < n; i += (u64)gridDim.x * BLOCK) {
+    const float x = a[i], y = b[i];
+    float d = fabsf(x - y);
+    if (!(d == d)) d = __uint_as_float(0x7F800000u);
+    md = fmaxf(md, d);
+    ma = fmaxf(ma, fabsf(x));
+  }
+  for (int off = WAVE / 2; off > 0; off >>= 1) {
+    md = fmaxf(md, __shfl_xor(md, off, WAVE));
+    ma = fmaxf(ma, __shfl_xor(ma, off, WAVE));
+  }
+  if (lane_id() == 0) {
+    atomicMax(&out[0], __float_as_uint(md));
+    atomicMax(&out[1], __float_as_uint(ma));
+  }
+}
+
+// Order-independent 64-bit sum of (bit pattern x per-index odd multiplier): equal for equal contents.
+__global__ void k_hash_bits(const float* __restrict__ a, u64 n, unsigned long long* __restrict__ out) {
+  u64 h = 0;
+  for (u64 i = (u64)blockIdx.x * BLOCK + threadIdx.x; i < n; i += (u64)gridDim.x * BLOCK)
+    h += (u64)__float_as_uint(a[i]) * ((i * 0x9E3779B97F4A7C15ull) | 1ull);
+  for (int off = WAVE / 2; off > 0; off >>= 1) h += __shfl_xor(h, off, WAVE);
+  if (lane_id() == 0) atomicAdd(out, (unsigned long long)h);
+}
+
 }  // namespace ctr
