@@ -364,8 +364,17 @@ static int pull_pool_impl(ctr_table* t, uint32_t replica, const uint64_t* d_keys
     StageTimer tm(t, CTR_STAGE_POOL, st);
     const float* vals = t->values + (u64)replica * t->tl.replica_stride;
     const u32 segs_per_block = (BLOCK / t->lpr) * POOL_NS * POOL_ROUNDS;
-    LPR_DISPATCH(t->lpr, k_pool, (n_segments + segs_per_block - 1) / segs_per_block, st, t->hdr, occ_row, seg_of,
-                 d_offsets, n_segments, vals, t->D, t->rf, d_pooled, d_pooled_bf16);
+    const u32 pgrid = (n_segments + segs_per_block - 1) / segs_per_block;
+#define CTR_POOL_LAUNCH(KERNEL) \
+  LPR_DISPATCH(t->lpr, KERNEL, pgrid, st, t->hdr, occ_row, seg_of, d_offsets, n_segments, vals, t->D, t->rf, d_pooled, d_pooled_bf16)
+    if (d_pooled && d_pooled_bf16) {
+      CTR_POOL_LAUNCH(k_pool_both);
+    } else if (d_pooled_bf16) {
+      CTR_POOL_LAUNCH(k_pool_bf16);
+    } else {
+      CTR_POOL_LAUNCH(k_pool);
+    }
+#undef CTR_POOL_LAUNCH
   }
   if (n > 0) {
     StageTimer tm(t, CTR_STAGE_SORT, st);

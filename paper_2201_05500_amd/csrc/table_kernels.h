@@ -372,11 +372,13 @@ __global__ void k_collect_rows(const DevHeader* hdr, const Slot* __restrict__ sl
 constexpr int POOL_NS = 2;      // segments a group works on at once
 constexpr int POOL_ROUNDS = 2;  // such pairs per group
 
-template <int LPR>
-__global__ void __launch_bounds__(BLOCK)
-k_pool(const DevHeader* hdr, const u32* __restrict__ occ_row, u32* __restrict__ seg_of,
-       const u32* __restrict__ offsets, u32 n_seg, const float* __restrict__ values, u32 D, u32 rf,
-       float* __restrict__ pooled, bf16_t* __restrict__ pooled_bf16) {
+// OUT: 1 = fp32 output, 2 = bf16 output, 3 = both (compile-time, so the common fp32-only kernel
+// carries neither the second pointer nor its branches).
+template <int LPR, int OUT>
+__device__ __forceinline__ void pool_body(const DevHeader* hdr, const u32* __restrict__ occ_row,
+                                          u32* __restrict__ seg_of, const u32* __restrict__ offsets, u32 n_seg,
+                                          const float* __restrict__ values, u32 D, u32 rf,
+                                          float* __restrict__ pooled, bf16_t* __restrict__ pooled_bf16) {
   if (hdr->status) return;
   constexpr int GROUPS = BLOCK / LPR;
   constexpr int TILE = GROUPS * POOL_NS * POOL_ROUNDS;
@@ -440,11 +442,24 @@ k_pool(const DevHeader* hdr, const u32* __restrict__ occ_row, u32* __restrict__ 
       const u32 l = (rnd * POOL_NS + s) * GROUPS + grp;
       if (l < tile_n && col_ok) {
         f4 o = {(float)acc[s].x, (float)acc[s].y, (float)acc[s].z, (float)acc[s].w};
-        if (pooled) stg4(pooled + (u64)(tile_g0 + l) * D + 4 * c, o);
-        if (pooled_bf16) stg4_bf16(pooled_bf16 + (u64)(tile_g0 + l) * D + 4 * c, o);  // the fp32 value, rounded again
+        if constexpr (OUT & 1) stg4(pooled + (u64)(tile_g0 + l) * D + 4 * c, o);
+        if constexpr (OUT & 2) stg4_bf16(pooled_bf16 + (u64)(tile_g0 + l) * D + 4 * c, o);  // the fp32 value, rounded again
       }
     }
   }
 }
+
+#define CTR_POOL_ARGS                                                                                       \
+  const DevHeader *hdr, const u32 *__restrict__ occ_row, u32 *__restrict__ seg_of,                          \
+      const u32 *__restrict__ offsets, u32 n_seg, const float *__restrict__ values, u32 D, u32 rf,          \
+      float *__restrict__ pooled, bf16_t *__restrict__ pooled_bf16
+#define CTR_DEFINE_POOL(NAME, OUT)                                                            \
+  template <int LPR>                                                                          \
+  __global__ void __launch_bounds__(BLOCK) NAME(CTR_POOL_ARGS) {                              \
+    pool_body<LPR, OUT>(hdr, occ_row, seg_of, offsets, n_seg, values, D, rf, pooled, pooled_bf16); \
+  }
+CTR_DEFINE_POOL(k_pool, 1)
+CTR_DEFINE_POOL(k_pool_bf16, 2)
+CTR_DEFINE_POOL(k_pool_both, 3)
 
 }  // namespace ctr
