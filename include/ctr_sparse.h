@@ -191,6 +191,13 @@ int ctr_kstep_merge(ctr_table* t, void* hip_stream);
 int ctr_table_load(ctr_table* t, const uint64_t* d_keys, uint64_t n_keys, const float* d_x, const float* d_m,
                    const float* d_v, void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Empties the table without giving up its memory (Algorithm 1's outer loop: the hash table holds
+ * the working parameters of one batch; the next batch loads its own with ctr_table_load): no keys,
+ * no rows, no pending merge steps, device status cleared.  Row storage is not wiped: rows are
+ * (re)initialised when keys are inserted again.  A live batch goes stale.  The step count of the
+ * bias-corrected form keeps running.  Enqueues only.  Errors: CTR_E_INVAL, CTR_E_DEVICE. */
+int ctr_table_clear(ctr_table* t, void* hip_stream);
+
 /* Collection of updated rows (Algorithm 1: pull_updates_peer_GPU, the step that hands the batch's
  * parameters back to the host-side tiers): looks up n_keys keys WITHOUT inserting and copies the
  * rows of replica `replica` to dense device arrays (any of d_x, d_m, d_v, d_found may be NULL;

@@ -327,6 +327,26 @@ int orc_kstep_merge(void* h) {
   return ORC_OK;
 }
 
+// Empties the table (Algorithm 1: the hash table holds one batch's working parameters; the next batch
+// brings its own): no rows, no keys, nothing pending; hyper-parameters and the step count stay.
+int orc_table_clear(void* h) {
+  Table* t = (Table*)h;
+  t->n_rows = 0;
+  t->row_of.clear();
+  t->key_of_row.clear();
+  for (uint32_t j = 0; j < t->W; ++j) {
+    t->x[j].clear();
+    t->m[j].clear();
+    t->v[j].clear();
+    t->pending[j].clear();
+  }
+  t->vhat.clear();
+  t->touched.clear();
+  t->batch_valid = false;
+  t->n_new_last = 0;
+  return ORC_OK;
+}
+
 // Working-set load (Algorithm 1: insert_into_hash_table of a parameter partition): keys not in the
 // table get new rows in the order given, keys already there are overwritten; every replica gets
 // the same state and the shared denominator of the row is set to v.

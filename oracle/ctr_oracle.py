@@ -62,6 +62,8 @@ def lib():
         L.orc_table_export.argtypes = [vp, u32, vp, vp, vp, vp, vp]
         L.orc_table_load.restype = C.c_int
         L.orc_table_load.argtypes = [vp, vp, u64, vp, vp, vp]
+        L.orc_table_clear.restype = C.c_int
+        L.orc_table_clear.argtypes = [vp]
         L.orc_table_collect.restype = C.c_int
         L.orc_table_collect.argtypes = [vp, u32, vp, u64, vp, vp, vp, vp]
         _lib = L
@@ -133,6 +135,9 @@ class OracleTable:
         v = np.ascontiguousarray(v, dtype=np.float32)
         m = np.zeros_like(x) if m is None else np.ascontiguousarray(m, dtype=np.float32)
         return lib().orc_table_load(self._h, _ptr(keys), keys.size, _ptr(x), _ptr(m), _ptr(v))
+
+    def table_clear(self):
+        return lib().orc_table_clear(self._h)
 
     def table_collect(self, replica, keys):
         """(status, x, m, v, found) for the given keys, without inserting."""

@@ -24,7 +24,7 @@ STAGE_NAMES = ("probe", "insert", "pool", "sort", "push", "fixup", "merge")
 
 EXPORTED = (
     "ctr_table_bytes", "ctr_workspace_bytes", "ctr_table_create", "ctr_table_destroy",
-    "ctr_pull_pool", "ctr_pull_pool_bf16", "ctr_push_adam", "ctr_kstep_merge", "ctr_table_load", "ctr_table_collect",
+    "ctr_pull_pool", "ctr_pull_pool_bf16", "ctr_push_adam", "ctr_kstep_merge", "ctr_table_load", "ctr_table_collect", "ctr_table_clear",
     "ctr_table_size", "ctr_table_export",
     "ctr_batch_export", "ctr_batch_stats", "ctr_last_status", "ctr_profile_enable",
     "ctr_profile_read",
@@ -72,6 +72,8 @@ def lib():
     L.ctr_table_destroy.argtypes = [vp]
     L.ctr_pull_pool.restype = ci
     L.ctr_pull_pool.argtypes = [vp, u32, vp, u64, vp, u32, vp, vp, sz, C.POINTER(vp), vp]
+    L.ctr_table_clear.restype = ci
+    L.ctr_table_clear.argtypes = [vp, vp]
     L.ctr_pull_pool_bf16.restype = ci
     L.ctr_pull_pool_bf16.argtypes = [vp, u32, vp, u64, vp, u32, vp, vp, vp, sz, C.POINTER(vp), vp]
     L.ctr_push_adam.restype = ci
@@ -260,6 +262,9 @@ class CtrTable:
         return ctr_table_load(self._handle, keys.data_ptr() if n else None, n, x.data_ptr() if n else None,
                               m.data_ptr() if (m is not None and n) else None, v.data_ptr() if n else None,
                               self._ws.data_ptr(), self.ws_bytes, self.stream)
+
+    def table_clear(self):
+        return lib().ctr_table_clear(self._handle, self.stream)
 
     def table_collect(self, replica, keys):
         """Returns (status, x, m or None, v, found) device tensors for the given keys (no insert)."""

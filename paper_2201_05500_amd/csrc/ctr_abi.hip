@@ -545,6 +545,18 @@ int ctr_table_load(ctr_table* t, const uint64_t* d_keys, uint64_t n_keys, const 
   return launch_status();
 }
 
+int ctr_table_clear(ctr_table* t, void* hip_stream) {
+  if (!t) return CTR_E_INVAL;
+  t->has_live = false;
+  ++t->generation;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const u64 work = std::max<u64>(t->tl.n_slots, t->R);
+  const u32 grid = (u32)std::min<u64>((work + BLOCK - 1) / BLOCK, 8192);
+  hipLaunchKernelGGL(k_table_clear, dim3(grid), dim3(BLOCK), 0, st, t->hdr, t->slots, t->tl.n_slots, t->row_state,
+                     t->R);
+  return launch_status();
+}
+
 int ctr_table_collect(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint64_t n_keys, float* d_x,
                       float* d_m, float* d_v, uint32_t* d_found, void* hip_stream) {
   if (!t || replica >= t->W) return CTR_E_INVAL;

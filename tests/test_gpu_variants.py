@@ -4,7 +4,7 @@ import pytest
 
 from oracle import ctr_oracle as O
 from paper_2201_05500_amd import workloads as WL
-from tests.parity_util import compare_tables, run_step, to_device
+from tests.parity_util import assert_close, compare_tables, run_step, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -124,3 +124,49 @@ def test_working_set_load_and_collect(kw):
     st = gt.table_load(torch.from_numpy(big.view(np.int64)).cuda(), z, None if adagrad else z, z + 1)
     assert st == B.CTR_OK and gt.last_status() == B.CTR_E_FULL and gt.n_rows == n_before
     compare_tables(gt, ot, what="after refused load")
+
+
+@pytest.mark.parametrize("kw", [dict(), dict(W=2, kstep=True)])
+def test_clear_and_reload_cycle(kw):
+    """Algorithm 1's outer loop on the GPU: load a working set, train mini-batches, collect, clear, load the next."""
+    import torch
+    from paper_2201_05500_amd import binding as B
+    from paper_2201_05500_amd.binding import CtrTable
+    rng = np.random.default_rng(9)
+    D, R = 8, 4000
+    W, kstep = kw.get("W", 1), kw.get("kstep", False)
+    gt = CtrTable(R, D, n_replicas=W, kstep=kstep, init_seed=4)
+    ot = O.OracleTable(R, D, n_replicas=W, kstep=kstep, init_seed=4)
+    w = WL.scaled(WL.WORKLOADS["mid"], dim=D, capacity_rows=R, zipf_universe=2500, batch=24)
+    mode = O.STEP_MERGE_PENDING if kstep else O.STEP_LOCAL
+    for outer in range(3):
+        bn0 = WL.as_numpy(WL.make_batch(w, 10 * outer))
+        part = np.unique(bn0["keys"])
+        n = part.size
+        x = rng.standard_normal((n, D)).astype(np.float32)
+        m = rng.standard_normal((n, D)).astype(np.float32)
+        v = (rng.random((n, D)) + 0.05).astype(np.float32)
+        dev = lambda a: torch.from_numpy(a).cuda()
+        assert gt.table_load(torch.from_numpy(part.view(np.int64)).cuda(), dev(x), dev(m), dev(v)) == B.CTR_OK
+        assert ot.table_load(part, x, m, v) == O.OK
+        assert gt.n_rows == n == ot.n_rows
+        for s in range(2):
+            for j in range(W):
+                bn = WL.as_numpy(WL.make_batch(w, 10 * outer + s, replica=j))
+                run_step(gt, ot, to_device(bn), bn, replica=j, mode=mode, what="outer %d step %d" % (outer, s))
+            if kstep:
+                assert gt.kstep_merge() == B.CTR_OK and ot.kstep_merge() == O.OK
+        compare_tables(gt, ot, what="outer %d before clear" % outer)
+        st, gx, gm, gv, found = gt.table_collect(0, torch.from_numpy(part.view(np.int64)).cuda())
+        ost, ox, om, ov, ofound = ot.table_collect(0, part)
+        assert st == B.CTR_OK and bool(found.all()) and ofound.all()
+        assert_close(gx.cpu().numpy(), ox, "collected x")
+        # a pull left unpushed goes stale with the clear
+        bt = to_device(WL.as_numpy(WL.make_batch(w, 99)))
+        st, stale, _ = gt.pull_pool(0, bt["keys"], bt["offsets"])
+        assert st == B.CTR_OK
+        assert gt.table_clear() == B.CTR_OK and ot.table_clear() == O.OK
+        assert gt.push_adam(0, stale, bt["grad"]) == B.CTR_E_STATE
+        assert gt.n_rows == 0 and gt.last_status() == B.CTR_OK
+        st, _, _, _, found = gt.table_collect(0, torch.from_numpy(part[:5].view(np.int64)).cuda())
+        assert st == B.CTR_OK and not bool(found.any())

@@ -246,3 +246,34 @@ def test_load_capacity_and_sentinel_leave_the_table_unchanged():
     assert t.table_load(np.array([2, 2 ** 64 - 1], np.uint64), z[:2], z[:2], z[:2] + 1) == O.E_BADKEY
     assert t.n_rows == 2 and t.lookup(3) == -1
     assert t.table_load(np.array([2, 3], np.uint64), z[:2], z[:2], z[:2] + 1) == O.OK and t.n_rows == 3
+
+
+def test_clear_makes_the_table_equal_to_a_fresh_one():
+    """Algorithm 1's outer loop: the hash table is emptied and the next working set loaded.  After a clear,
+    everything behaves as in a table that was just created (rows renumbered from 0, old keys unknown)."""
+    rng = np.random.default_rng(3)
+    D = 4
+    for kw in (dict(), dict(n_replicas=2, kstep=True)):
+        a = O.OracleTable(16, D, init_seed=2, **kw)
+        b = O.OracleTable(16, D, init_seed=2, **kw)
+        keys = np.array([7, 8, 9, 7], np.uint64)
+        off = np.array([0, 2, 4], np.uint32)
+        g = rng.standard_normal((2, D)).astype(F32)
+        mode = O.STEP_MERGE_PENDING if a.kstep else O.STEP_LOCAL
+        assert a.pull_pool(0, keys, off)[0] == O.OK and a.push_adam(0, g, mode) == O.OK
+        assert a.table_clear() == O.OK
+        assert a.n_rows == 0 and a.lookup(7) == -1
+        assert a.push_adam(0, g) != O.OK                            # the batch of before the clear is gone
+        if a.kstep:
+            assert a.kstep_merge() == O.OK                          # nothing pending, nothing touched
+        keys2 = np.array([9, 5, 9], np.uint64)
+        off2 = np.array([0, 1, 3], np.uint32)
+        for t in (a, b):
+            st, pooled = t.pull_pool(0, keys2, off2)
+            assert st == O.OK and t.push_adam(0, g, mode) == O.OK
+            if t.kstep:
+                assert t.kstep_merge() == O.OK
+        assert a.lookup(9) == 0 and a.lookup(5) == 1 and a.n_rows == 2
+        ea, eb = a.table_export(0), b.table_export(0)
+        for f in ("keys", "x", "m", "v"):
+            assert np.array_equal(ea[f], eb[f]), f
