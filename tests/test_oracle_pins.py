@@ -361,16 +361,16 @@ def test_merge_skips_untouched_rows_and_absent_worker_counts_as_init():
     step(t, 1, kb, off, g, O.STEP_MERGE_PENDING)
     t.kstep_merge()
     s0 = [t.table_export(j) for j in range(W)]
-    # round 2 touches key 10 only, by worker 2, with a local step then a merge
+    # merge round 2 touches key 10 only, by worker 2, with a local step then a merge
     step(t, 2, ka, off, g, O.STEP_LOCAL)
     pre = [t.table_export(j) for j in range(W)]
     t.kstep_merge()
     s1 = [t.table_export(j) for j in range(W)]
     for j in range(W):
-        assert np.array_equal(s0[j]["x"][1], s1[j]["x"][1])          # key 20 untouched in round 2
+        assert np.array_equal(s0[j]["x"][1], s1[j]["x"][1])          # key 20 untouched in merge round 2
     xbar = np.mean([p["x"][0].astype(np.float64) for p in pre], axis=0)   # no pending step terms
     np.testing.assert_allclose(s1[0]["x"][0], xbar, rtol=1e-6)
-    # round 1, key 10: workers 1 and 2 held init(key) and contributed no step
+    # merge round 1, key 10: workers 1 and 2 held init(key) and contributed no step
     init = np.array([O.init_value(1, 10, d, 0.01) for d in range(D)])
     v0 = (float(F32(0.999)) * 1e-8 + (1 - float(F32(0.999))) * g[0].astype(np.float64) ** 2)
     vhat = (v0 + 2 * float(F32(1e-8))) / 3

@@ -191,7 +191,7 @@ def test_prose_merge_skips_untouched_rows():
     s1 = [t.table_export(j) for j in range(W)]
     for j in range(W):
         for f in ("x", "v"):
-            assert np.array_equal(s0[j][f][1], s1[j][f][1])     # key 20 untouched in round 2
+            assert np.array_equal(s0[j][f][1], s1[j][f][1])     # key 20 untouched in merge round 2
 
 
 def test_variant_argument_checks():
