@@ -281,3 +281,13 @@ def test_maximum_capacity_closed_form(capsys):
     assert st == CTR_OK and int(found[0]) == 0
     st, x2, _, _, found = gt.table_collect(0, torch.from_numpy(sample[:8]).to(dev))
     assert bool(found.all()) and torch.equal(x2, x[:8])
+
+
+@pytest.mark.timeout(900)
+def test_batch_of_five_million_occurrences(capsys):
+    """A batch size between the benchmarked ones (4096 x 300 slots, ~4.9 M occurrences into a 2^22-row table):
+    the host picks work spans of 64 occurrences and 8 probes per thread here, a combination no other test runs."""
+    from tests.test_gpu_parity import run_workload
+    w = WL.scaled(WL.WORKLOADS["large"], capacity_rows=1 << 22, zipf_universe=1 << 22, batch=4096)
+    gt, ot = run_workload(w, 2, say=lambda m: _say(capsys, m))
+    assert gt.n_rows == ot.n_rows
