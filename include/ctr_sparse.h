@@ -244,6 +244,13 @@ int ctr_last_status(ctr_table* t, void* hip_stream);
 #define CTR_STAGE_MERGE 6   /* k-step merge */
 #define CTR_N_STAGES 7
 
+/* Test hook: fixes the work geometry of later pulls and pushes instead of letting the batch size
+ * choose it (span: occurrences per work span of the push, 16/32/64/128; probe_items: occurrences
+ * per thread of the probe, 1 or 8; 0 = by batch size), so that every code path can be exercised
+ * on small inputs.  Results do not depend on the geometry.  A geometry that needs more workspace
+ * than the call was given makes the call return CTR_E_NOMEM.  Errors: CTR_E_INVAL. */
+int ctr_debug_set_geometry(ctr_table* t, uint32_t span, uint32_t probe_items);
+
 /* When enabled, a pair of HIP events is recorded around each stage of the
  * following calls, on the stream they run on (one pair per execution). */
 int ctr_profile_enable(ctr_table* t, int on);

@@ -26,7 +26,7 @@ EXPORTED = (
     "ctr_table_bytes", "ctr_workspace_bytes", "ctr_table_create", "ctr_table_destroy",
     "ctr_pull_pool", "ctr_pull_pool_bf16", "ctr_push_adam", "ctr_kstep_merge", "ctr_table_load", "ctr_table_collect", "ctr_table_clear",
     "ctr_table_size", "ctr_table_export",
-    "ctr_batch_export", "ctr_batch_stats", "ctr_last_status", "ctr_profile_enable",
+    "ctr_batch_export", "ctr_batch_stats", "ctr_last_status", "ctr_debug_set_geometry", "ctr_profile_enable",
     "ctr_profile_read",
 )
 
@@ -72,6 +72,8 @@ def lib():
     L.ctr_table_destroy.argtypes = [vp]
     L.ctr_pull_pool.restype = ci
     L.ctr_pull_pool.argtypes = [vp, u32, vp, u64, vp, u32, vp, vp, sz, C.POINTER(vp), vp]
+    L.ctr_debug_set_geometry.restype = ci
+    L.ctr_debug_set_geometry.argtypes = [vp, u32, u32]
     L.ctr_table_clear.restype = ci
     L.ctr_table_clear.argtypes = [vp, vp]
     L.ctr_pull_pool_bf16.restype = ci
@@ -200,6 +202,7 @@ class CtrTable:
         need = ctr_workspace_bytes(self.cfg, max_keys, max_segments)
         if need == 0:
             raise ValueError("invalid workspace request")
+        need += getattr(self, "_ws_slack", 0)
         if need > self.ws_bytes:
             self._torch.cuda.synchronize(self.device)
             self._ws = self._torch.empty(need, dtype=self._torch.uint8, device=self.device)
@@ -325,6 +328,12 @@ class CtrTable:
         if st != CTR_OK:
             raise RuntimeError("ctr_table_export: %d" % st)
         return {"keys": keys, "x": x, "m": m, "v": v, "vhat": vhat}
+
+    def set_geometry(self, span=0, probe_items=0):
+        """Test hook (ctr_debug_set_geometry); the workspace is grown for the larger probe tiles."""
+        st = lib().ctr_debug_set_geometry(self._handle, span, probe_items)
+        self._ws_slack = 1 << 20 if (span or probe_items) else 0
+        return st
 
     def profile_enable(self, on=True):
         return lib().ctr_profile_enable(self._handle, 1 if on else 0)

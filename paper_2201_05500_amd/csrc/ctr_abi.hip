@@ -79,12 +79,14 @@ struct WorkLayout {
       off_head, off_tail, off_block_head, off_span_flags, off_span_rows, total;
 };
 
-void work_layout(u32 D, u64 n_keys, WorkLayout* L) {
+// force_span / force_items: 0 = chosen by batch size; otherwise the geometry a test asks for.
+void work_layout(u32 D, u64 n_keys, WorkLayout* L, u32 force_span = 0, u32 force_items = 0) {
   const u64 n = n_keys;
   L->n_bit_words = (u32)((n + 31) / 32);
   L->n_bit_tiles = (L->n_bit_words + BITS_TILE_WORDS - 1) / BITS_TILE_WORDS;
   // shorter spans for smaller batches: the span walk is sequential, so parallelism = n / span groups
   L->span = n >= (8u << 20) ? 128u : n >= (4u << 20) ? 64u : n >= (2u << 20) ? 32u : 16u;
+  if (force_span) L->span = force_span;
   L->n_spans = (u32)((n + L->span - 1) / L->span);
   L->n_span_blocks = (L->n_spans + SPANS_PER_BLOCK - 1) / SPANS_PER_BLOCK;
   u64 tiles = (n + SORT_TILE - 1) / SORT_TILE;
@@ -107,6 +109,7 @@ void work_layout(u32 D, u64 n_keys, WorkLayout* L) {
   L->off_tile_count = o; o += align256(((size_t)L->n_bit_tiles + 1) * sizeof(u32));
   L->off_first_bits = o; o += align256(((size_t)L->n_bit_words + 1) * sizeof(u32));
   L->probe_items = n >= (4u << 20) ? PROBE_MAX_ITEMS : 1;
+  if (force_items) L->probe_items = force_items;
   L->probe_tile = BLOCK * L->probe_items;
   L->n_probe_tiles = (u32)((n + L->probe_tile - 1) / L->probe_tile);
   L->off_pend_list = o; o += align256(((size_t)L->n_probe_tiles + 1) * L->probe_tile * sizeof(u32));
@@ -159,6 +162,7 @@ struct ctr_table {
   // generation number (never reused), so a stale handle can never be mistaken for a live one.
   ctr_batch cur;
   bool has_live;
+  u32 force_span, force_items;  // test hook: 0 = geometry by batch size
   bool profile;
   // stage timers: one (start, stop) event pair per recorded execution since the last read
   std::vector<hipEvent_t> ev_start[CTR_N_STAGES], ev_stop[CTR_N_STAGES];
@@ -305,6 +309,7 @@ int ctr_table_create(const ctr_config* cfg, void* d_mem, size_t bytes, void* hip
   t->init_scale = (float)((double)cfg->init_std / 37837.2);
   t->generation = 0;
   t->has_live = false;
+  t->force_span = t->force_items = 0;
   t->profile = false;
   for (int i = 0; i < CTR_N_STAGES; ++i) t->ev_used[i] = 0;
   hipStream_t st = (hipStream_t)hip_stream;
@@ -340,7 +345,7 @@ static int pull_pool_impl(ctr_table* t, uint32_t replica, const uint64_t* d_keys
   if (n_segments > 0 && !d_pooled && !d_pooled_bf16) return CTR_E_INVAL;
   if (((uintptr_t)d_workspace & 255) != 0) return CTR_E_INVAL;
   WorkLayout wl;
-  work_layout(t->D, n_keys, &wl);
+  work_layout(t->D, n_keys, &wl, t->force_span, t->force_items);
   if (workspace_bytes < wl.total) return CTR_E_NOMEM;
 
   t->has_live = false;  // an unpushed batch goes stale
@@ -530,7 +535,7 @@ int ctr_table_load(ctr_table* t, const uint64_t* d_keys, uint64_t n_keys, const 
   if (n_keys > 0 && (!d_keys || !d_x || !d_v || (has_m && !d_m))) return CTR_E_INVAL;
   if (((uintptr_t)d_workspace & 255) != 0) return CTR_E_INVAL;
   WorkLayout wl;
-  work_layout(t->D, n_keys, &wl);
+  work_layout(t->D, n_keys, &wl, t->force_span, t->force_items);
   if (workspace_bytes < wl.total) return CTR_E_NOMEM;
   t->has_live = false;  // the workspace of an unpushed batch may be this one: it goes stale
   ++t->generation;
@@ -690,6 +695,15 @@ int ctr_last_status(ctr_table* t, void* hip_stream) {
     return CTR_E_DEVICE;
   if (hipStreamSynchronize(st) != hipSuccess) return CTR_E_DEVICE;
   return status_code_from_bits(h.status);
+}
+
+int ctr_debug_set_geometry(ctr_table* t, uint32_t span, uint32_t probe_items) {
+  if (!t) return CTR_E_INVAL;
+  if (span != 0 && span != 16 && span != 32 && span != 64 && span != 128) return CTR_E_INVAL;
+  if (probe_items != 0 && probe_items != 1 && probe_items != (uint32_t)PROBE_MAX_ITEMS) return CTR_E_INVAL;
+  t->force_span = span;
+  t->force_items = probe_items;
+  return CTR_OK;
 }
 
 int ctr_profile_enable(ctr_table* t, int on) {

@@ -134,11 +134,16 @@ def _tables(R, D, W=1, kstep=False, seed=3):
             O.OracleTable(R, D, n_replicas=W, kstep=kstep, init_seed=seed))
 
 
-def test_one_key_repeated_spans_many_work_spans():
+GEOMETRIES = [(0, 0), (32, 8), (64, 1), (128, 8)]     # (work span, probes per thread); 0 = chosen by batch size
+
+
+@pytest.mark.parametrize("geometry", GEOMETRIES)
+def test_one_key_repeated_spans_many_work_spans(geometry):
     """Degenerate batch: a single key fills every occurrence (one row crossing every span)."""
     D = 64
-    for n in (1, 127, 128, 129, 4096, 4097, 20000):
+    for n in (1, 127, 128, 129, 4096, 4097, 20000, 70001, 600001):   # the last: more than 64 blocks of 64 spans of 128
         gt, ot = _tables(64, D)
+        assert gt.set_geometry(*geometry) == 0
         G = max(1, n // 3)
         off = np.linspace(0, n, G + 1).astype(np.uint32)
         bn = _manual_batch(np.full(n, 0xABCDEF123, np.uint64), off, D, seed=n)
@@ -147,10 +152,12 @@ def test_one_key_repeated_spans_many_work_spans():
         compare_tables(gt, ot, what="one key n=%d" % n)
 
 
-def test_all_keys_distinct_and_ragged_tail():
+@pytest.mark.parametrize("geometry", GEOMETRIES)
+def test_all_keys_distinct_and_ragged_tail(geometry):
     D = 16
     for n in (1, 3, 255, 257, 4095, 4099, 12345):
         gt, ot = _tables(1 << 14, D)
+        assert gt.set_geometry(*geometry) == 0
         keys = (np.arange(n, dtype=np.uint64) + np.uint64(1)) * np.uint64(0x9E3779B97F4A7C15)
         off = np.unique(np.concatenate([[0, n], np.random.default_rng(n).integers(0, n + 1, n // 2)]))
         bn = _manual_batch(keys, off, D, seed=n)
@@ -279,7 +286,7 @@ def test_random_small_cases_differential():
     """Seeded random shapes: dims, replicas, k, ragged segments with empties, heavy duplication, table
     sizes that are not powers of two, several steps and merges - every state compared with the oracle."""
     rng = np.random.default_rng(2024)
-    for case in range(24):
+    for case in range(32):
         D = int(rng.choice([4, 8, 16, 20, 32, 64, 96]))
         W = int(rng.choice([1, 1, 2, 3, 5]))
         kstep = W > 1 or bool(rng.integers(0, 2))
@@ -291,6 +298,7 @@ def test_random_small_cases_differential():
         gt.close()
         from paper_2201_05500_amd.binding import CtrTable
         gt = CtrTable(R, D, n_replicas=W, kstep=kstep, init_seed=case, beta1=beta1, lr=3e-3)
+        assert gt.set_geometry(*GEOMETRIES[case % len(GEOMETRIES)]) == 0
         ot = O.OracleTable(R, D, n_replicas=W, kstep=kstep, init_seed=case, beta1=beta1, lr=3e-3)
         t = 0
         for step in range(int(rng.integers(2, 6))):
