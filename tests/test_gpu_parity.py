@@ -99,6 +99,16 @@ def test_kstep_three_replicas_k1():
     _kstep_rounds(w, 4, 1)
 
 
+def test_kstep_maximum_replicas():
+    """W = 31, the most the per-row state word can mark as pending (bit 31 is the touched flag)."""
+    from paper_2201_05500_amd import binding as B
+    w = WL.scaled(WL.WORKLOADS["kstep"], capacity_rows=2048, zipf_universe=1500, batch=8, slots=10, n_replicas=31,
+                  k_step=2)
+    _kstep_rounds(w, 2, 2)
+    with pytest.raises(ValueError):
+        B.CtrTable(64, 8, n_replicas=32, kstep=True)
+
+
 def test_kstep_one_replica_k1_equals_single_table():
     """Algorithm 2 with N = 1, k = 1 is plain Adam: the two GPU code paths agree to tolerance."""
     from paper_2201_05500_amd.binding import CtrTable
