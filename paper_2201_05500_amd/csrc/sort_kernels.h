@@ -30,6 +30,10 @@ constexpr int SORT_TILE = BLOCK * SORT_ITEMS;  // 4096
 #endif
 constexpr int SORT_MAX_CHUNKS = CTR_SORT_MAX_CHUNKS;
 constexpr int RADIX = 256;
+#ifndef CTR_HIST_COPIES
+#define CTR_HIST_COPIES 4
+#endif
+constexpr int HIST_COPIES = CTR_HIST_COPIES;  // power of two
 
 struct SortGeom {
   u32 n;            // elements
@@ -40,27 +44,39 @@ struct SortGeom {
 __global__ void k_sort_hist(const DevHeader* hdr, const u32* __restrict__ keys, SortGeom geo, u32 shift,
                             u32 digit_mask, u32* __restrict__ hist) {
   if (hdr->status) return;
-  __shared__ u32 h[4][RADIX];  // one histogram per wave: fewer same-address LDS atomics
+  // HIST_COPIES histograms per wave, chosen by lane: a popular digit (row ids of popular keys share
+  // their high bits) would otherwise serialise all 64 lanes on one LDS address
+  __shared__ u32 h[4 * HIST_COPIES][RADIX];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) h[i][threadIdx.x] = 0;
+  for (int i = 0; i < 4 * HIST_COPIES; ++i) h[i][threadIdx.x] = 0;
   __syncthreads();
   const u32 beg = blockIdx.x * geo.chunk_elems;  // multiple of SORT_TILE, so 16-byte aligned
   const u32 end = min(beg + geo.chunk_elems, geo.n);
-  u32* mine = h[wave_id()];
+  u32* mine = h[wave_id() * HIST_COPIES + (lane_id() & (HIST_COPIES - 1))];
   for (u32 e = beg + threadIdx.x * 4; e < end; e += BLOCK * 4) {
     if (e + 4 <= end) {
       const uint4 k4 = *reinterpret_cast<const uint4*>(keys + e);
-      atomicAdd(&mine[(k4.x >> shift) & digit_mask], 1u);
-      atomicAdd(&mine[(k4.y >> shift) & digit_mask], 1u);
-      atomicAdd(&mine[(k4.z >> shift) & digit_mask], 1u);
-      atomicAdd(&mine[(k4.w >> shift) & digit_mask], 1u);
+      const u32 d0 = (k4.x >> shift) & digit_mask, d1 = (k4.y >> shift) & digit_mask;
+      const u32 d2 = (k4.z >> shift) & digit_mask, d3 = (k4.w >> shift) & digit_mask;
+      // the digit of the wave's first key is counted with ballots (one add for the whole wave):
+      // under a popular digit that takes most of the keys away from the LDS atomics
+      const u32 ref = (u32)__builtin_amdgcn_readfirstlane((int)d0);
+      const u32 n_ref = (u32)(__popcll(__ballot(d0 == ref)) + __popcll(__ballot(d1 == ref)) +
+                              __popcll(__ballot(d2 == ref)) + __popcll(__ballot(d3 == ref)));
+      if (d0 != ref) atomicAdd(&mine[d0], 1u);
+      if (d1 != ref) atomicAdd(&mine[d1], 1u);
+      if (d2 != ref) atomicAdd(&mine[d2], 1u);
+      if (d3 != ref) atomicAdd(&mine[d3], 1u);
+      if (lane_id() == __ffsll((long long)__ballot(true)) - 1) atomicAdd(&mine[ref], n_ref);  // first lane that is here
     } else {
       for (u32 j = e; j < end; ++j) atomicAdd(&mine[(keys[j] >> shift) & digit_mask], 1u);
     }
   }
   __syncthreads();
-  hist[threadIdx.x * geo.n_chunks + blockIdx.x] =
-      h[0][threadIdx.x] + h[1][threadIdx.x] + h[2][threadIdx.x] + h[3][threadIdx.x];
+  u32 total = 0;
+#pragma unroll
+  for (int i = 0; i < 4 * HIST_COPIES; ++i) total += h[i][threadIdx.x];
+  hist[threadIdx.x * geo.n_chunks + blockIdx.x] = total;
 }
 
 // grid = RADIX blocks; block d turns hist[d][0..n_chunks) into exclusive prefix sums.
@@ -126,13 +142,18 @@ k_sort_scatter(const DevHeader* hdr, const u32* __restrict__ keys_in, const u32*
     for (int i = 0; i < SORT_ITEMS; ++i) {
       const u32 local = w * (SORT_TILE / 4) + i * WAVE + lane;
       const bool valid = local < n_valid;
-      const u32 d = (k[i] >> shift) & digit_mask;
-      u64 same = __ballot(valid);
+      const u32 d = (k[i] >> shift) & digit_mask;  // 0 for lanes past the end (k = 0)
+      // lanes whose digit equals mine: for every bit, the ballot of that bit XNOR my bit (m is
+      // 0 or ~0); the disagreements are OR-ed per 32-bit half, lanes past the end masked at the end
+      u32 diff_lo = 0, diff_hi = 0;
 #pragma unroll
       for (int b = 0; b < 8; ++b) {
-        const u64 bal = __ballot(valid && ((d >> b) & 1u));
-        same &= ((d >> b) & 1u) ? bal : ~bal;
+        const u32 m = (u32)__builtin_amdgcn_sbfe((int)d, b, 1);
+        const u64 bal = __builtin_amdgcn_ballot_w64(m != 0u);
+        diff_lo |= (u32)bal ^ m;
+        diff_hi |= (u32)(bal >> 32) ^ m;
       }
+      const u64 same = __ballot(valid) & ~(((u64)diff_hi << 32) | diff_lo);
       // lanes of `same` hold digit d; the lowest of them bumps the wave's counter
       const int leader = __ffsll((long long)same) - 1;
       u32 before = 0;
