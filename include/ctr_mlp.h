@@ -9,8 +9,9 @@
  * gradient of the pooled embeddings (the input of ctr_push_adam), and the dense optimizer.
  *
  * Arithmetic: matrix products take bf16 operands with fp32 accumulation on the matrix cores
- * (vendor GEMM kernels through hipBLASLt, rocBLAS as the fallback; everything else is
- * hand-written HIP).  Master parameters, moments and the
+ * (vendor GEMM kernels through hipBLASLt; rocBLAS if hipBLASLt cannot start or the environment
+ * variable CTR_MLP_NO_HIPBLASLT is set when the tower is created; everything else is hand-written
+ * HIP).  Master parameters, moments and the
  * optimizer are fp32/fp64 exactly as in the sparse path: m0 = 0, v0 = eps, no bias correction,
  * x -= lr m / sqrt(den) with den = own v (one replica) or the shared v frozen at the last merge.
  * Rounding to bf16 (nearest-even) happens at: the input, the weight copies used by the products,

@@ -472,7 +472,8 @@ int ctr_mlp_create(const ctr_mlp_config* cfg, void* d_mem, size_t bytes, void* h
     delete t;
     return CTR_E_DEVICE;
   }
-  if (hipblasLtCreate(&t->lt) != HIPBLAS_STATUS_SUCCESS) t->lt = nullptr;  // products then go through rocBLAS
+  // CTR_MLP_NO_HIPBLASLT in the environment (or a hipBLASLt that cannot start) sends the products through rocBLAS
+  if (getenv("CTR_MLP_NO_HIPBLASLT") != nullptr || hipblasLtCreate(&t->lt) != HIPBLAS_STATUS_SUCCESS) t->lt = nullptr;
   t->plan_batch = 0;
   // fixed summation order: no atomics in the products
   (void)rocblas_set_atomics_mode(t->blas, rocblas_atomics_not_allowed);

@@ -190,3 +190,22 @@ def test_kernel_search_keeps_the_results():
         close_rows(gpb.cpu().numpy(), ogp, "tuned grad of pooled step %d" % s, in_dim)
         close_rows(gpb.cpu().numpy(), gpa.cpu().numpy(), "tuned vs untuned step %d" % s, in_dim)
     close_enough(gb.export()["params"], o.params[0], "tuned parameters", rtol=1e-3, norm_tol=1e-3)
+
+
+def test_rocblas_fallback_path(monkeypatch):
+    """With hipBLASLt switched off at creation the products run through rocBLAS: same parity, and a kernel
+    search has nothing to do."""
+    monkeypatch.setenv("CTR_MLP_NO_HIPBLASLT", "1")
+    rng = np.random.default_rng(31)
+    in_dim, hidden, B = 192, [128, 64], 256
+    g, o = _pair(in_dim, hidden)
+    monkeypatch.delenv("CTR_MLP_NO_HIPBLASLT")
+    assert g.tune(B) == 0
+    for s in range(2):
+        pooled, labels, dp, dl = _batch(rng, B, in_dim)
+        st, loss, gp = g.step(0, dp, dl)
+        assert st == 0
+        oloss, ogp = o.step(0, pooled, labels)
+        assert abs(float(loss.cpu()[0]) - float(oloss)) <= 1e-4 * max(1.0, float(oloss))
+        close_rows(gp.cpu().numpy(), ogp, "fallback grad of pooled step %d" % s, in_dim)
+    close_enough(g.export()["params"], o.params[0], "fallback parameters", rtol=1e-3, norm_tol=1e-3)
