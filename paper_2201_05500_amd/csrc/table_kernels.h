@@ -72,14 +72,20 @@ k_probe_insert(DevHeader* hdr, Slot* slots, u32 slot_mask, const u64* __restrict
       } else {
         u32 h = (u32)hash_key(key) & slot_mask;
         bool found = false;
+        u32 r = ROW_PENDING;
         for (u32 probe = 0; probe <= slot_mask; ++probe) {
-          // A plain (cacheable) load: slots only ever go from free to taken inside this launch,
-          // so the worst a stale copy can show is "free", and the compare-and-swap below then
-          // returns the key that is really there.
-          u64 k = slots[h].key;
+          // One plain (cacheable) 16-byte load brings key and row id in a single request.  Slots
+          // only ever go from free to taken inside this launch, so the worst a stale copy can
+          // show is "free", and the compare-and-swap below then returns the key that is really
+          // there; rows are assigned between launches, never inside this one, so a slot taken
+          // during this launch has no row yet.
+          const uint4 raw = *reinterpret_cast<const uint4*>(&slots[h]);
+          u64 k = ((u64)raw.y << 32) | raw.x;
+          r = raw.z;
           if (k == KEY_EMPTY) {
             const u64 old = atomicCAS(&slots[h].key, KEY_EMPTY, key);
             k = (old == KEY_EMPTY) ? key : old;
+            r = ROW_PENDING;
           }
           if (k == key) {
             found = true;
@@ -91,7 +97,6 @@ k_probe_insert(DevHeader* hdr, Slot* slots, u32 slot_mask, const u64* __restrict
         if (!found) {  // every slot holds another key: more distinct keys than slots
           atomicOr(&hdr->pull_err, ST_FULL);
         } else {
-          const u32 r = slots[h].row;  // rows are assigned between launches, never inside this one
           if (r == ROW_PENDING) {
             // a popular new key has millions of occurrences: only those that can still lower
             // the minimum go to the atomic unit, the rest see a smaller value and pass
