@@ -418,13 +418,28 @@ __device__ __forceinline__ void pool_body(const DevHeader* hdr, const u32* __res
       acc[s] = d4{0.0, 0.0, 0.0, 0.0};
       maxlen = max(maxlen, end[s] - beg[s]);
     }
+    u32 win[POOL_NS];  // lane c of the group holds the row id of occurrence (window start + c)
     for (u32 k = 0; k < maxlen; k += 4) {
       u32 r[POOL_NS][4];
       f4 xv[POOL_NS][4];
+      if constexpr (LPR >= 4) {
+        // one coalesced load per group brings the row ids of the next LPR occurrences (a whole
+        // segment, usually); they are handed out by shuffles: a quarter of the memory requests
+        // of one broadcast load per occurrence
+        if (k % LPR == 0) {
 #pragma unroll
-      for (int s = 0; s < POOL_NS; ++s)
+          for (int s = 0; s < POOL_NS; ++s) win[s] = (beg[s] + k + c < end[s]) ? occ_row[beg[s] + k + c] : 0u;
+        }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) r[s][i] = (beg[s] + k + i < end[s]) ? occ_row[beg[s] + k + i] : 0u;
+        for (int s = 0; s < POOL_NS; ++s)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) r[s][i] = __shfl(win[s], (int)((k + i) % LPR), LPR);
+      } else {
+#pragma unroll
+        for (int s = 0; s < POOL_NS; ++s)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) r[s][i] = (beg[s] + k + i < end[s]) ? occ_row[beg[s] + k + i] : 0u;
+      }
 #pragma unroll
       for (int s = 0; s < POOL_NS; ++s)
 #pragma unroll
