@@ -172,9 +172,27 @@ __device__ __forceinline__ void push_span_body(const DevHeader* hdr, const u32* 
   u32 flags = 0, started = 0;
   d4 acc = {0.0, 0.0, 0.0, 0.0};
 
+  // LPR > PB: the group keeps a window of LPR consecutive list entries (lane c holds entry
+  // window start + c, plus the first row id after the window) and refills it with three loads
+  // every LPR occurrences, instead of two small loads per batch of PB
+  u32 win_r = NO_ROW, win_g = 0u, win_next = NO_ROW;
   for (u32 i0 = b; i0 < e; i0 += PB) {
     u32 r[PB + 1], g[PB];
-    if constexpr (LPR > PB) {  // one coalesced index load per group, then broadcast
+    if constexpr (LPR > PB && LPR % PB == 0) {
+      const u32 o = (i0 - b) % LPR;
+      if (o == 0) {
+        win_r = (i0 + c < n) ? sr[i0 + c] : NO_ROW;
+        win_g = (i0 + c < e) ? ss[i0 + c] : 0u;
+        win_next = (i0 + LPR < n) ? sr[i0 + LPR] : NO_ROW;
+      }
+#pragma unroll
+      for (int i = 0; i <= PB; ++i) {
+        const u32 from_win = __shfl(win_r, (int)((o + i) % LPR), LPR);
+        r[i] = (o + i < (u32)LPR) ? from_win : win_next;
+      }
+#pragma unroll
+      for (int i = 0; i < PB; ++i) g[i] = __shfl(win_g, (int)(o + i), LPR);
+    } else if constexpr (LPR > PB) {  // one coalesced index load per group, then broadcast
       const u32 mine_r = (c <= PB && i0 + c < n) ? sr[i0 + c] : NO_ROW;
       const u32 mine_g = (c < PB && i0 + c < e) ? ss[i0 + c] : 0u;
 #pragma unroll
