@@ -493,7 +493,7 @@ int ctr_push_adam(ctr_table* t, uint32_t replica, ctr_batch* handle, const float
     {
       StageTimer tm(t, CTR_STAGE_FIXUP, st);
       LPR_DISPATCH(t->lpr, k_push_block_heads, blocks_for((u64)wl.n_span_blocks * WAVE), st, t->hdr,
-                   batch->sorted_rows, wl.n_spans, wl.span, t->D, head, block_head);
+                   batch->sorted_rows, wl.n_spans, wl.span, t->D, head, block_head, span_flags);
       const u32 fgrid = blocks_for((u64)wl.n_spans * WAVE);
       switch (kind) {
         case STEP_ADAM_SHARED: CTR_FIXUP_LAUNCH(k_push_fixup_shared); break;

@@ -258,8 +258,8 @@ __device__ __forceinline__ void push_span_body(const DevHeader* hdr, const u32* 
     }
   }
   if (c == 0) {
-    span_flags[s] = flags;
-    span_rows[s] = started;  // rows that START in this span
+    span_flags[s] = (sr[b] << 2) | flags;  // first row id of the span above the two flag bits
+    span_rows[s] = started;                // rows that START in this span
   }
 }
 
@@ -305,7 +305,8 @@ __device__ __forceinline__ void combine_groups(d4& a) {
 template <int LPR>
 __global__ void __launch_bounds__(BLOCK)
 k_push_block_heads(const DevHeader* hdr, const u32* __restrict__ sr, u32 n_spans, u32 span, u32 D,
-                   const double* __restrict__ head_part, double* __restrict__ block_head) {
+                   const double* __restrict__ head_part, double* __restrict__ block_head,
+                   const u32* __restrict__ span_flags) {
   if (hdr->status) return;
   constexpr int GPW = WAVE / LPR;
   const u32 j = (blockIdx.x * BLOCK + threadIdx.x) / WAVE;  // wave-uniform
@@ -316,7 +317,7 @@ k_push_block_heads(const DevHeader* hdr, const u32* __restrict__ sr, u32 n_spans
   const bool col_ok = c * 4 < D;
   const u32 row = sr[first * span - 1];
   const u32 t = first + lane;
-  const u32 n_lead = leading_true(t < n_spans && sr[t * span] == row);
+  const u32 n_lead = leading_true(t < n_spans && (span_flags[t] >> 2) == row);  // coalesced, unlike sr[t * span]
   if (n_lead == 0) return;
   d4 acc = {0.0, 0.0, 0.0, 0.0};
   if (col_ok)
@@ -356,13 +357,13 @@ __device__ __forceinline__ void push_fixup_body(const DevHeader* hdr, const u32*
   }
   // spans after s inside its block (at most SPANS_PER_BLOCK - 1 = one per lane)
   const u32 t = s + 1 + lane;
-  const u32 n_in = leading_true(t < blk_end && sr[t * span] == row);
+  const u32 n_in = leading_true(t < blk_end && (span_flags[t] >> 2) == row);
   if (col_ok)
     for (u32 k = grp; k < n_in; k += GPW) add_partial(head_part, s + 1 + k, D, c, acc);
   if (s + 1 + n_in == blk_end) {  // the row reaches the end of the block: go on block by block
     for (u32 jb = s / SPANS_PER_BLOCK + 1; jb < n_blocks; jb += WAVE) {
       const u32 jj = jb + lane;
-      const u32 nb = leading_true(jj < n_blocks && sr[jj * SPANS_PER_BLOCK * span] == row);
+      const u32 nb = leading_true(jj < n_blocks && (span_flags[jj * SPANS_PER_BLOCK] >> 2) == row);
       if (col_ok)
         for (u32 k = grp; k < nb; k += GPW) add_partial(block_head, jb + k, D, c, acc);
       if (nb < WAVE) break;
