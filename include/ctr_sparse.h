@@ -152,6 +152,18 @@ int ctr_pull_pool_bf16(ctr_table* t, uint32_t replica, const uint64_t* d_keys, u
                        uint16_t* d_pooled_bf16, void* d_workspace, size_t workspace_bytes,
                        ctr_batch** batch_out, void* hip_stream);
 
+/* Lookup-only pooling, for prediction with a trained table (the embedding layer of Section 2.1
+ * without the insert-on-miss of the training workflow): pooled[g, :] = sum of the rows of the keys
+ * of segment g that ARE in the table; absent keys contribute nothing and are not inserted.  Table,
+ * counters and optimizer state are untouched and no batch handle is produced.  Either output may
+ * be NULL (not both).  The workspace (sized as for ctr_pull_pool) is overwritten: if it is the one
+ * a live batch owns, that batch goes stale.  Errors as ctr_pull_pool, except that the table cannot
+ * become full. */
+int ctr_lookup_pool(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint64_t n_keys,
+                    const uint32_t* d_offsets, uint32_t n_segments, float* d_pooled,
+                    uint16_t* d_pooled_bf16, void* d_workspace, size_t workspace_bytes,
+                    void* hip_stream);
+
 /* Push (Algorithm 1: push_parameters_updates_back; Algorithm 2: the m, v and
  * model lines).  The gradient of sum pooling hands grad_pooled[g, :] to every
  * key occurrence of segment g; per distinct key the occurrences' gradients are

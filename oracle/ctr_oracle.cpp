@@ -327,6 +327,34 @@ int orc_kstep_merge(void* h) {
   return ORC_OK;
 }
 
+// Lookup-only pooling (prediction with a trained table: the embedding layer of Section 2.1 without the
+// insert-on-miss of training): keys that are not in the table contribute nothing; the table, its
+// pending batch and every counter stay as they are.
+int orc_lookup_pool(void* h, uint32_t replica, const uint64_t* keys, uint64_t n_keys, const uint32_t* offsets,
+                    uint32_t n_seg, float* pooled) {
+  Table* t = (Table*)h;
+  const uint32_t D = t->D;
+  if (replica >= t->W) return ORC_E_INVAL;
+  if (offsets[0] != 0 || offsets[n_seg] != n_keys) return ORC_E_INVAL;
+  for (uint32_t g = 0; g < n_seg; ++g)
+    if (offsets[g + 1] < offsets[g]) return ORC_E_INVAL;
+  for (uint64_t p = 0; p < n_keys; ++p)
+    if (keys[p] == SENTINEL) return ORC_E_BADKEY;
+  const std::vector<float>& x = t->x[replica];
+  std::vector<double> acc(D);
+  for (uint32_t g = 0; g < n_seg; ++g) {
+    std::fill(acc.begin(), acc.end(), 0.0);
+    for (uint32_t p = offsets[g]; p < offsets[g + 1]; ++p) {
+      auto it = t->row_of.find(keys[p]);
+      if (it == t->row_of.end()) continue;
+      const float* row = &x[(size_t)it->second * D];
+      for (uint32_t d = 0; d < D; ++d) acc[d] += (double)row[d];
+    }
+    for (uint32_t d = 0; d < D; ++d) pooled[(size_t)g * D + d] = (float)acc[d];
+  }
+  return ORC_OK;
+}
+
 // Empties the table (Algorithm 1: the hash table holds one batch's working parameters; the next batch
 // brings its own): no rows, no keys, nothing pending; hyper-parameters and the step count stay.
 int orc_table_clear(void* h) {

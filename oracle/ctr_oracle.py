@@ -62,6 +62,8 @@ def lib():
         L.orc_table_export.argtypes = [vp, u32, vp, vp, vp, vp, vp]
         L.orc_table_load.restype = C.c_int
         L.orc_table_load.argtypes = [vp, vp, u64, vp, vp, vp]
+        L.orc_lookup_pool.restype = C.c_int
+        L.orc_lookup_pool.argtypes = [vp, u32, vp, u64, vp, u32, vp]
         L.orc_table_clear.restype = C.c_int
         L.orc_table_clear.argtypes = [vp]
         L.orc_table_collect.restype = C.c_int
@@ -135,6 +137,15 @@ class OracleTable:
         v = np.ascontiguousarray(v, dtype=np.float32)
         m = np.zeros_like(x) if m is None else np.ascontiguousarray(m, dtype=np.float32)
         return lib().orc_table_load(self._h, _ptr(keys), keys.size, _ptr(x), _ptr(m), _ptr(v))
+
+    def lookup_pool(self, replica, keys, offsets):
+        """(status, pooled[G, D]) without inserting: absent keys contribute nothing."""
+        keys = np.ascontiguousarray(keys, dtype=np.uint64)
+        offsets = np.ascontiguousarray(offsets, dtype=np.uint32)
+        n_seg = offsets.size - 1
+        pooled = np.zeros((n_seg, self.D), np.float32)
+        st = lib().orc_lookup_pool(self._h, replica, _ptr(keys), keys.size, _ptr(offsets), n_seg, _ptr(pooled))
+        return st, pooled
 
     def table_clear(self):
         return lib().orc_table_clear(self._h)

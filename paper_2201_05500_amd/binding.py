@@ -24,7 +24,7 @@ STAGE_NAMES = ("probe", "insert", "pool", "sort", "push", "fixup", "merge")
 
 EXPORTED = (
     "ctr_table_bytes", "ctr_workspace_bytes", "ctr_table_create", "ctr_table_destroy",
-    "ctr_pull_pool", "ctr_pull_pool_bf16", "ctr_push_adam", "ctr_kstep_merge", "ctr_table_load", "ctr_table_collect", "ctr_table_clear",
+    "ctr_pull_pool", "ctr_pull_pool_bf16", "ctr_lookup_pool", "ctr_push_adam", "ctr_kstep_merge", "ctr_table_load", "ctr_table_collect", "ctr_table_clear",
     "ctr_table_size", "ctr_table_export",
     "ctr_batch_export", "ctr_batch_stats", "ctr_last_status", "ctr_debug_set_geometry", "ctr_profile_enable",
     "ctr_profile_read",
@@ -74,6 +74,8 @@ def lib():
     L.ctr_pull_pool.argtypes = [vp, u32, vp, u64, vp, u32, vp, vp, sz, C.POINTER(vp), vp]
     L.ctr_debug_set_geometry.restype = ci
     L.ctr_debug_set_geometry.argtypes = [vp, u32, u32]
+    L.ctr_lookup_pool.restype = ci
+    L.ctr_lookup_pool.argtypes = [vp, u32, vp, u64, vp, u32, vp, vp, vp, sz, vp]
     L.ctr_table_clear.restype = ci
     L.ctr_table_clear.argtypes = [vp, vp]
     L.ctr_pull_pool_bf16.restype = ci
@@ -250,6 +252,18 @@ class CtrTable:
                                        pooled_bf16.data_ptr() if n_seg else None, self._ws.data_ptr(), self.ws_bytes,
                                        self.stream)
         return st, batch, pooled_bf16, pooled
+
+    def lookup_pool(self, replica, keys, offsets, bf16=False):
+        """Pooling without insert (prediction).  Returns (status, pooled[G, D] fp32 or bf16)."""
+        torch = self._torch
+        n_keys, n_seg = keys.numel(), offsets.numel() - 1
+        self.reserve(max(n_keys, 1), n_seg)
+        pooled = torch.empty((n_seg, self.D), dtype=torch.bfloat16 if bf16 else torch.float32, device=self.device)
+        ptr = pooled.data_ptr() if n_seg else None
+        st = lib().ctr_lookup_pool(self._handle, replica, keys.data_ptr() if n_keys else None, n_keys,
+                                   offsets.data_ptr(), n_seg, None if bf16 else ptr, ptr if bf16 else None,
+                                   self._ws.data_ptr(), self.ws_bytes, self.stream)
+        return st, pooled
 
     def push_adam(self, replica, batch, grad, mode=CTR_STEP_LOCAL):
         return ctr_push_adam(self._handle, replica, batch, grad.data_ptr() if grad.numel() else None,

@@ -433,6 +433,51 @@ int ctr_pull_pool_bf16(ctr_table* t, uint32_t replica, const uint64_t* d_keys, u
                         workspace_bytes, batch_out, hip_stream);
 }
 
+int ctr_lookup_pool(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint64_t n_keys,
+                    const uint32_t* d_offsets, uint32_t n_segments, float* d_pooled, uint16_t* d_pooled_bf16,
+                    void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!t || !d_offsets || !d_workspace) return CTR_E_INVAL;
+  if (replica >= t->W) return CTR_E_INVAL;
+  if (n_keys >= (1ull << 31) || n_segments == 0xFFFFFFFFu) return CTR_E_INVAL;
+  if (n_keys > 0 && !d_keys) return CTR_E_INVAL;
+  if (n_segments > 0 && !d_pooled && !d_pooled_bf16) return CTR_E_INVAL;
+  if (((uintptr_t)d_workspace & 255) != 0 || ((uintptr_t)d_pooled_bf16 & 7) != 0) return CTR_E_INVAL;
+  WorkLayout wl;
+  work_layout(t->D, n_keys, &wl, t->force_span, t->force_items);
+  if (workspace_bytes < wl.total) return CTR_E_NOMEM;
+  if (t->has_live && t->cur.ws == (char*)d_workspace) t->has_live = false;  // the live batch's lists are overwritten
+  hipStream_t st = (hipStream_t)hip_stream;
+  char* ws = (char*)d_workspace;
+  u32* occ_row = (u32*)(ws + wl.off_occ_row);
+  u32* seg_of = (u32*)(ws + wl.off_seg_of);
+  const u32 n = (u32)n_keys;
+  {
+    StageTimer tm(t, CTR_STAGE_PROBE, st);
+    const u64 work = std::max<u64>(n, (u64)n_segments + 1);
+    hipLaunchKernelGGL(k_lookup, dim3(blocks_for(work)), dim3(BLOCK), 0, st, t->hdr, t->slots,
+                       (u32)(t->tl.n_slots - 1), (const u64*)d_keys, n, d_offsets, n_segments, occ_row);
+    hipLaunchKernelGGL(k_lookup_commit, dim3(1), dim3(WAVE), 0, st, t->hdr);
+  }
+  if (n_segments > 0) {
+    StageTimer tm(t, CTR_STAGE_POOL, st);
+    const float* vals = t->values + (u64)replica * t->tl.replica_stride;
+    const u32 segs_per_block = (BLOCK / t->lpr) * POOL_NS * POOL_ROUNDS;
+    const u32 pgrid = (n_segments + segs_per_block - 1) / segs_per_block;
+    bf16_t* pb = (bf16_t*)d_pooled_bf16;
+#define CTR_POOL_LAUNCH(KERNEL) \
+  LPR_DISPATCH(t->lpr, KERNEL, pgrid, st, t->hdr, occ_row, seg_of, d_offsets, n_segments, vals, t->D, t->rf, d_pooled, pb)
+    if (d_pooled && pb) {
+      CTR_POOL_LAUNCH(k_pool_lookup_both);
+    } else if (pb) {
+      CTR_POOL_LAUNCH(k_pool_lookup_bf16);
+    } else {
+      CTR_POOL_LAUNCH(k_pool_lookup);
+    }
+#undef CTR_POOL_LAUNCH
+  }
+  return launch_status();
+}
+
 int ctr_push_adam(ctr_table* t, uint32_t replica, ctr_batch* handle, const float* d_grad_pooled, uint32_t mode,
                   void* hip_stream) {
   if (!t || !handle) return CTR_E_INVAL;

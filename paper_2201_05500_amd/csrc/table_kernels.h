@@ -319,6 +319,51 @@ __global__ void k_load_rows(const DevHeader* hdr, const u32* __restrict__ occ_ro
   if (vhat) stg4(vhat + (u64)row * D + 4 * c, v);
 }
 
+// Lookup without insert for every occurrence of a batch (prediction): occ_row[p] = row of keys[p],
+// or OCC_INVALID if the key is not in the table.  Checks keys and offsets like the training probe;
+// what it finds goes to pull_err and is folded into the status by k_lookup_commit.
+__global__ void __launch_bounds__(BLOCK)
+k_lookup(DevHeader* hdr, const Slot* __restrict__ slots, u32 slot_mask, const u64* __restrict__ keys, u32 n_keys,
+         const u32* __restrict__ offsets, u32 n_seg, u32* __restrict__ occ_row) {
+  if (hdr->status) return;
+  const u32 p = blockIdx.x * BLOCK + threadIdx.x;
+  if (p <= n_seg) {
+    const u32 a = offsets[p];
+    bool bad = (p == 0 && a != 0);
+    if (p == n_seg)
+      bad = bad || (a != n_keys);
+    else
+      bad = bad || (offsets[p + 1] < a);
+    if (bad) atomicOr(&hdr->pull_err, ST_INVAL);
+  }
+  if (p >= n_keys) return;
+  const u64 key = keys[p];
+  u32 out = OCC_INVALID;
+  if (key == KEY_EMPTY) {
+    atomicOr(&hdr->pull_err, ST_BADKEY);
+  } else {
+    u32 h = (u32)hash_key(key) & slot_mask;
+    for (u32 probe = 0; probe <= slot_mask; ++probe) {
+      const uint4 raw = *reinterpret_cast<const uint4*>(&slots[h]);  // key and row id in one request
+      const u64 k = ((u64)raw.y << 32) | raw.x;
+      if (k == key) {
+        out = raw.z;
+        break;
+      }
+      if (k == KEY_EMPTY) break;
+      h = (h + 1) & slot_mask;
+    }
+  }
+  occ_row[p] = out;
+}
+
+__global__ void k_lookup_commit(DevHeader* hdr) {
+  if (threadIdx.x == 0 && blockIdx.x == 0 && !hdr->status) {
+    hdr->status = hdr->pull_err;
+    hdr->pull_err = 0;
+  }
+}
+
 // Pure lookup (no insert) of n keys and copy of their rows of one replica to dense arrays; a key
 // that is not in the table gets found = 0 and zeros.
 template <int LPR>
@@ -377,8 +422,8 @@ __global__ void k_collect_rows(const DevHeader* hdr, const Slot* __restrict__ sl
 constexpr int POOL_NS = 2;      // segments a group works on at once
 constexpr int POOL_ROUNDS = 2;  // such pairs per group
 
-// OUT: 1 = fp32 output, 2 = bf16 output, 3 = both (compile-time, so the common fp32-only kernel
-// carries neither the second pointer nor its branches).
+// OUT: 1 = fp32 output, 2 = bf16 output, 3 = both; + 4 = lookup-only input, where an occurrence may have
+// no row (compile-time, so the common fp32-only training kernel carries none of the other cases).
 template <int LPR, int OUT>
 __device__ __forceinline__ void pool_body(const DevHeader* hdr, const u32* __restrict__ occ_row,
                                           u32* __restrict__ seg_of, const u32* __restrict__ offsets, u32 n_seg,
@@ -445,7 +490,9 @@ __device__ __forceinline__ void pool_body(const DevHeader* hdr, const u32* __res
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           xv[s][i].x = xv[s][i].y = xv[s][i].z = xv[s][i].w = 0.0f;
-          if (beg[s] + k + i < end[s] && col_ok) xv[s][i] = ldg4(values + (u64)r[s][i] * rf + 4 * c);
+          bool take = beg[s] + k + i < end[s] && col_ok;
+          if constexpr (OUT & 4) take = take && r[s][i] != OCC_INVALID;  // lookup-only: absent keys add nothing
+          if (take) xv[s][i] = ldg4(values + (u64)r[s][i] * rf + 4 * c);
         }
 #pragma unroll
       for (int s = 0; s < POOL_NS; ++s) {  // padded entries add +0.0
@@ -481,5 +528,8 @@ __device__ __forceinline__ void pool_body(const DevHeader* hdr, const u32* __res
 CTR_DEFINE_POOL(k_pool, 1)
 CTR_DEFINE_POOL(k_pool_bf16, 2)
 CTR_DEFINE_POOL(k_pool_both, 3)
+CTR_DEFINE_POOL(k_pool_lookup, 5)
+CTR_DEFINE_POOL(k_pool_lookup_bf16, 6)
+CTR_DEFINE_POOL(k_pool_lookup_both, 7)
 
 }  // namespace ctr

@@ -277,3 +277,39 @@ def test_clear_makes_the_table_equal_to_a_fresh_one():
         ea, eb = a.table_export(0), b.table_export(0)
         for f in ("keys", "x", "m", "v"):
             assert np.array_equal(ea[f], eb[f]), f
+
+
+def test_lookup_pool_reads_without_inserting():
+    """Prediction path: pooling over the keys that are in the table, nothing for the others, no side effects."""
+    from fractions import Fraction
+    rng = np.random.default_rng(12)
+    D = 4
+    t = O.OracleTable(16, D, init_seed=5)
+    train_keys = np.array([3, 4, 5, 3], np.uint64)
+    off = np.array([0, 2, 4], np.uint32)
+    st, pooled_train = t.pull_pool(0, train_keys, off)
+    assert st == O.OK and t.push_adam(0, rng.standard_normal((2, D)).astype(F32)) == O.OK
+    before = t.table_export(0)
+    # all keys present: the same sums a pull would give now
+    st, a = t.lookup_pool(0, train_keys, off)
+    st2, b = t.pull_pool(0, train_keys, off)
+    assert st == O.OK and st2 == O.OK and np.array_equal(a, b)
+    # absent keys (77, 99) add nothing and are not inserted; exact rational sums of the present rows
+    keys = np.array([77, 4, 99, 5, 5, 99], np.uint64)
+    off2 = np.array([0, 1, 3, 3, 6], np.uint32)
+    st, p = t.lookup_pool(0, keys, off2)
+    assert st == O.OK and t.n_rows == 3 and t.lookup(77) == -1 and t.lookup(99) == -1
+    x = before["x"]
+    row = {3: 0, 4: 1, 5: 2}
+    want = [[Fraction(0)] * D, [Fraction(float(x[row[4]][d])) for d in range(D)], [Fraction(0)] * D,
+            [2 * Fraction(float(x[row[5]][d])) for d in range(D)]]
+    for g in range(4):
+        for d in range(D):
+            assert p[g, d] == F32(float(want[g][d])), (g, d)
+    after = t.table_export(0)
+    for f in ("keys", "x", "m", "v"):
+        assert np.array_equal(before[f], after[f])
+    # error conventions as for a pull
+    assert t.lookup_pool(0, np.array([1, 2 ** 64 - 1], np.uint64), np.array([0, 2], np.uint32))[0] == O.E_BADKEY
+    assert t.lookup_pool(0, keys, np.array([0, 4, 3, 6], np.uint32))[0] == O.E_INVAL
+    assert t.lookup_pool(1, keys, off2)[0] == O.E_INVAL
