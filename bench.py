@@ -138,6 +138,9 @@ def main():
                     help="row update: Algorithm 2's Adam (default), AdaGrad, the prose reading of the merge, "
                          "bias-corrected Adam")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--predict", action="store_true",
+                    help="full workload: the timed steps are predictions (lookup without insert + tower forward) "
+                         "on a table filled by the warm-up's training steps")
     ap.add_argument("--no-tune", action="store_true",
                     help="full workload: skip the tower's set-up search for the fastest product kernels")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -159,6 +162,9 @@ def main():
     w = WL.WORKLOADS[args.workload]
     kstep = w.k_step > 0
     full = w.name == "full"
+    if args.predict and not full:
+        print("bench.py: --predict goes with --workload full", file=sys.stderr)
+        sys.exit(2)
     if full and args.variant != "alg2":
         print("bench.py: the full step is timed with Algorithm 2's update only", file=sys.stderr)
         sys.exit(2)
@@ -212,6 +218,19 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    def predict_step(s):
+        b = batches[s]
+        st, _ = table.lookup_pool(0, b["keys"], b["offsets"], out=pooled_bf16)
+        if st != CTR_OK:
+            raise RuntimeError("ctr_lookup_pool: %d" % st)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        st, _ = tower.forward(0, pooled_bf16.view(w.batch, in_dim))
+        e1.record()
+        tower_events.append((e0, e1))
+        if st != CTR_OK:
+            raise RuntimeError("ctr_mlp_forward: %d" % st)
+
     def run_step(s):
         mode = CTR_STEP_LOCAL
         merge_now = kstep and (s + 1) % w.k_step == 0
@@ -258,7 +277,10 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(Wm, total_steps):
-        run_step(s)
+        if args.predict:
+            predict_step(s)
+        else:
+            run_step(s)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
 
@@ -330,20 +352,26 @@ def main():
     if full:
         tower_ms = sum(a.elapsed_time(b) for a, b in tower_events) / len(tower_events)
         fl = tower_flops(w.batch, in_dim, WL.FULL_STEP_HIDDEN)
-        out["metric"] = "full training step (pull, dense tower, push): " + out["metric"]
+        if args.predict:
+            fl //= 3                       # forward products only
+        out["metric"] = ("prediction (lookup without insert, tower forward): " if args.predict else
+                         "full training step (pull, dense tower, push): ") + out["metric"]
         out["dtype"] = "f32 table, bf16 x bf16 -> f32 tower products"
         out["samples_per_s"] = w.batch * K / elapsed
-        out["final_loss"] = float(loss.cpu()[0])
+        out["final_loss"] = None if args.predict else float(loss.cpu()[0])
         out["stage_ms"]["tower"] = tower_ms
         out["config"]["tower"] = "%d-%s-1, click rate %g, product kernels %s" % (
             in_dim, "-".join(str(h) for h in WL.FULL_STEP_HIDDEN), WL.FULL_STEP_CLICK_RATE,
             "as the library picks them" if args.no_tune else "picked by a timed search at set-up")
         out["roofline_tower"] = {
-            "bound": "mfma", "kernel": "ctr_mlp_step (all products and element-wise kernels of one tower step)",
+            "bound": "mfma", "kernel": ("ctr_mlp_forward" if args.predict else "ctr_mlp_step") +
+            " (all products and element-wise kernels of one tower call)",
             "achieved": fl / (tower_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": fl / (tower_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
         }
-    if not args.no_cpu_baseline:
+    if args.predict:                       # the byte model above is the training step's
+        out["step_algorithmic_GBps"] = out["step_frac_of_hbm_peak"] = None
+    if not args.no_cpu_baseline and not args.predict:
         out["cpu_baseline"] = cpu_baseline(w, WL)
     print(json.dumps(out))
 

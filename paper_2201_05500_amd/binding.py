@@ -253,12 +253,15 @@ class CtrTable:
                                        self.stream)
         return st, batch, pooled_bf16, pooled
 
-    def lookup_pool(self, replica, keys, offsets, bf16=False):
+    def lookup_pool(self, replica, keys, offsets, bf16=False, out=None):
         """Pooling without insert (prediction).  Returns (status, pooled[G, D] fp32 or bf16)."""
         torch = self._torch
         n_keys, n_seg = keys.numel(), offsets.numel() - 1
         self.reserve(max(n_keys, 1), n_seg)
-        pooled = torch.empty((n_seg, self.D), dtype=torch.bfloat16 if bf16 else torch.float32, device=self.device)
+        if out is not None:
+            bf16 = out.dtype == torch.bfloat16
+        pooled = out if out is not None else torch.empty(
+            (n_seg, self.D), dtype=torch.bfloat16 if bf16 else torch.float32, device=self.device)
         ptr = pooled.data_ptr() if n_seg else None
         st = lib().ctr_lookup_pool(self._handle, replica, keys.data_ptr() if n_keys else None, n_keys,
                                    offsets.data_ptr(), n_seg, None if bf16 else ptr, ptr if bf16 else None,
