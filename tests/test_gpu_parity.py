@@ -1,4 +1,6 @@
 """GPU parity: the HIP path through the C ABI against the CPU oracle, element by element."""
+import os
+
 import numpy as np
 import pytest
 
@@ -295,8 +297,8 @@ def test_same_calls_give_bit_identical_results():
 def test_random_small_cases_differential():
     """Seeded random shapes: dims, replicas, k, ragged segments with empties, heavy duplication, table
     sizes that are not powers of two, several steps and merges - every state compared with the oracle."""
-    rng = np.random.default_rng(2024)
-    for case in range(32):
+    rng = np.random.default_rng(int(os.environ.get("CTR_TEST_RANDOM_SEED", "2024")))
+    for case in range(int(os.environ.get("CTR_TEST_RANDOM_CASES", "32"))):   # more cases / other seeds for a soak on demand
         D = int(rng.choice([4, 8, 16, 20, 32, 64, 96]))
         W = int(rng.choice([1, 1, 2, 3, 5]))
         kstep = W > 1 or bool(rng.integers(0, 2))
@@ -354,3 +356,39 @@ def test_bf16_pooled_output():
     ea, eb, ec = ta.table_export(0), tb.table_export(0), tc.table_export(0)
     for k in ("keys", "x", "m", "v"):
         assert np.array_equal(ea[k], eb[k]) and np.array_equal(ea[k], ec[k]), k
+
+
+def test_random_medium_cases_differential():
+    """Seeded random batches of 20 K - 400 K occurrences (several probe tiles, sort chunks and span blocks; hot
+    keys crossing many spans) under random work geometries, a few steps each, every state compared."""
+    from paper_2201_05500_amd.binding import CtrTable
+    rng = np.random.default_rng(int(os.environ.get("CTR_TEST_RANDOM_SEED", "7")))
+    for case in range(int(os.environ.get("CTR_TEST_MEDIUM_CASES", "8"))):
+        D = int(rng.choice([4, 16, 32, 64, 128]))
+        W = int(rng.choice([1, 1, 2, 4]))
+        kstep = W > 1
+        R = int(rng.integers(20000, 200000))
+        universe = int(rng.integers(1000, R))
+        zipf = bool(rng.integers(0, 2))
+        gt = CtrTable(R, D, n_replicas=W, kstep=kstep, init_seed=100 + case)
+        assert gt.set_geometry(*GEOMETRIES[int(rng.integers(0, len(GEOMETRIES)))]) == 0
+        ot = O.OracleTable(R, D, n_replicas=W, kstep=kstep, init_seed=100 + case)
+        for step in range(3):
+            mode = O.STEP_MERGE_PENDING if (kstep and step == 2) else O.STEP_LOCAL
+            for j in range(W):
+                G = int(rng.integers(5000, 60000))
+                counts = rng.poisson(rng.uniform(1.0, 7.0), G)
+                off = np.concatenate([[0], np.cumsum(counts)]).astype(np.uint32)
+                n = int(off[-1])
+                if zipf:
+                    ranks = np.minimum((universe ** rng.random(n)).astype(np.uint64), np.uint64(universe - 1))
+                else:
+                    ranks = rng.integers(0, universe, n).astype(np.uint64)
+                keys = (ranks + np.uint64(1)) * np.uint64(0x9E3779B97F4A7C15)
+                bn = {"keys": keys, "offsets": off, "grad": rng.standard_normal((G, D)).astype(np.float32)}
+                what = "medium case %d step %d replica %d (D=%d W=%d R=%d n=%d)" % (case, step, j, D, W, R, n)
+                run_step(gt, ot, to_device(bn), bn, replica=j, mode=mode, what=what)
+            if mode == O.STEP_MERGE_PENDING:
+                assert gt.kstep_merge() == 0 and ot.kstep_merge() == 0
+        compare_tables(gt, ot, what="medium case %d" % case)
+        gt.close()
