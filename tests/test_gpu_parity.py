@@ -6,7 +6,7 @@ import pytest
 
 from oracle import ctr_oracle as O
 from paper_2201_05500_amd import workloads as WL
-from tests.parity_util import (assert_close, compare_batch, compare_tables, run_step, to_device)
+from tests.parity_util import (assert_close, compare_batch, compare_tables, pooled_tolerance, run_step, to_device)
 
 pytestmark = pytest.mark.gpu
 
@@ -392,3 +392,43 @@ def test_random_medium_cases_differential():
                 assert gt.kstep_merge() == 0 and ot.kstep_merge() == 0
         compare_tables(gt, ot, what="medium case %d" % case)
         gt.close()
+
+
+def test_random_overflow_and_rollback_differential():
+    """Random batches against tables that are too small for them: a pull that does not fit must leave index, rows
+    and counters exactly as they were (the oracle refuses it up front, the GPU rolls its tentative inserts back),
+    and training must go on afterwards as if it had never been issued."""
+    from paper_2201_05500_amd import binding as B
+    from paper_2201_05500_amd.binding import CtrTable
+    rng = np.random.default_rng(int(os.environ.get("CTR_TEST_RANDOM_SEED", "11")))
+    n_full = 0
+    for case in range(int(os.environ.get("CTR_TEST_OVERFLOW_CASES", "24"))):
+        D = int(rng.choice([4, 8, 32]))
+        R = int(rng.integers(20, 600))
+        universe = int(rng.integers(R // 2 + 2, 3 * R))       # more keys around than rows
+        gt = CtrTable(R, D, init_seed=case)
+        assert gt.set_geometry(*GEOMETRIES[case % len(GEOMETRIES)]) == 0
+        ot = O.OracleTable(R, D, init_seed=case)
+        for step in range(int(rng.integers(3, 8))):
+            G = int(rng.integers(1, 120))
+            counts = rng.poisson(rng.uniform(0.5, 5.0), G)
+            off = np.concatenate([[0], np.cumsum(counts)]).astype(np.uint32)
+            keys = (rng.integers(0, universe, int(off[-1])).astype(np.uint64) + np.uint64(1)) * np.uint64(0x9E3779B97F4A7C15)
+            bn = {"keys": keys, "offsets": off, "grad": rng.standard_normal((G, D)).astype(np.float32)}
+            bt = to_device(bn)
+            st, h, pooled = gt.pull_pool(0, bt["keys"], bt["offsets"])
+            assert st == B.CTR_OK
+            ost, opooled = ot.pull_pool(0, bn["keys"], bn["offsets"])
+            if ost == O.E_FULL:
+                n_full += 1
+                assert gt.push_adam(0, h, bt["grad"]) == B.CTR_OK          # enqueued, a no-op on the device
+                assert gt.last_status() == B.CTR_E_FULL and gt.last_status() == B.CTR_OK
+            else:
+                assert ost == O.OK and gt.last_status() == B.CTR_OK
+                _, orows, oinv = ot.batch_export(keys.size)
+                assert_close(pooled.cpu().numpy(), opooled, "case %d step %d pooled" % (case, step),
+                             pooled_tolerance(ot.table_export(0)["x"], orows, oinv, off))
+                assert gt.push_adam(0, h, bt["grad"]) == B.CTR_OK and ot.push_adam(0, bn["grad"]) == O.OK
+            compare_tables(gt, ot, what="overflow case %d step %d (status %d)" % (case, step, ost))
+        gt.close()
+    assert n_full > 0
