@@ -107,6 +107,14 @@ size_t ctr_mlp_n_params(const ctr_mlp_config* cfg);
 int ctr_mlp_export(ctr_mlp* m, uint32_t replica, float* h_params, float* h_m, float* h_v, float* h_vhat,
                    void* hip_stream);
 
+/* The inverse of ctr_mlp_export (restoring a checkpoint): copies HOST arrays of ctr_mlp_n_params
+ * floats into a replica's parameters, first and second moments and into the shared denominator
+ * (any may be NULL: left as it is), refreshes the bf16 copy of the parameters, and sets whether
+ * the replica's last step was a merge step that the next ctr_mlp_kstep_merge still has to apply
+ * (pending: 0 or 1).  Synchronises the stream.  Errors: CTR_E_INVAL, CTR_E_DEVICE. */
+int ctr_mlp_import(ctr_mlp* m, uint32_t replica, const float* h_params, const float* h_m, const float* h_v,
+                   const float* h_vhat, uint32_t pending, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -9,7 +9,7 @@ from .binding import CTR_OK, CTR_STEP_LOCAL, lib as _base_lib
 
 CTR_MLP_MAX_HIDDEN = 6
 EXPORTED = ("ctr_mlp_bytes", "ctr_mlp_workspace_bytes", "ctr_mlp_create", "ctr_mlp_destroy", "ctr_mlp_step",
-            "ctr_mlp_forward", "ctr_mlp_step_bf16", "ctr_mlp_forward_bf16", "ctr_mlp_tune_workspace_bytes", "ctr_mlp_tune", "ctr_mlp_kstep_merge", "ctr_mlp_n_params", "ctr_mlp_export")
+            "ctr_mlp_forward", "ctr_mlp_step_bf16", "ctr_mlp_forward_bf16", "ctr_mlp_tune_workspace_bytes", "ctr_mlp_tune", "ctr_mlp_kstep_merge", "ctr_mlp_n_params", "ctr_mlp_export", "ctr_mlp_import")
 
 
 class ctr_mlp_config(C.Structure):
@@ -62,6 +62,8 @@ def lib():
         L.ctr_mlp_kstep_merge.argtypes = [vp, vp]
         L.ctr_mlp_export.restype = ci
         L.ctr_mlp_export.argtypes = [vp, u32, vp, vp, vp, vp, vp]
+        L.ctr_mlp_import.restype = ci
+        L.ctr_mlp_import.argtypes = [vp, u32, vp, vp, vp, vp, u32, vp]
         _ready = True
     return L
 
@@ -158,6 +160,16 @@ class CtrMlp:
 
     def kstep_merge(self):
         return lib().ctr_mlp_kstep_merge(self._handle, self.stream)
+
+    def load(self, replica=0, params=None, m=None, v=None, vhat=None, pending=False):
+        """Restores state exported earlier (float32 numpy arrays of n_params elements; None = keep)."""
+        arrs = [None if a is None else np.ascontiguousarray(a, dtype=np.float32) for a in (params, m, v, vhat)]
+        for a in arrs:
+            if a is not None and a.size != self.n_params:
+                raise ValueError("wrong length")
+        ptr = lambda a: None if a is None else a.ctypes.data_as(C.c_void_p)
+        return lib().ctr_mlp_import(self._handle, replica, ptr(arrs[0]), ptr(arrs[1]), ptr(arrs[2]), ptr(arrs[3]),
+                                    1 if pending else 0, self.stream)
 
     def export(self, replica=0):
         n = self.n_params

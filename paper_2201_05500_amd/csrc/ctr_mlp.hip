@@ -680,4 +680,26 @@ int ctr_mlp_export(ctr_mlp* t, uint32_t replica, float* h_params, float* h_m, fl
   return ok ? CTR_OK : CTR_E_DEVICE;
 }
 
+int ctr_mlp_import(ctr_mlp* t, uint32_t replica, const float* h_params, const float* h_m, const float* h_v,
+                   const float* h_vhat, uint32_t pending, void* hip_stream) {
+  if (!t || replica >= t->cfg.n_replicas) return CTR_E_INVAL;
+  if (h_vhat && !t->vhat) return CTR_E_INVAL;
+  if (pending > 1 || (pending && !t->cfg.kstep)) return CTR_E_INVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const size_t nb = (size_t)t->L.n_params * sizeof(float);
+  const u64 off = (u64)replica * t->M.stride;
+  bool ok = true;
+  if (h_params) ok = ok && hipMemcpyAsync(t->params + off, h_params, nb, hipMemcpyHostToDevice, st) == hipSuccess;
+  if (h_m) ok = ok && hipMemcpyAsync(t->m + off, h_m, nb, hipMemcpyHostToDevice, st) == hipSuccess;
+  if (h_v) ok = ok && hipMemcpyAsync(t->v + off, h_v, nb, hipMemcpyHostToDevice, st) == hipSuccess;
+  if (h_vhat) ok = ok && hipMemcpyAsync(t->vhat, h_vhat, nb, hipMemcpyHostToDevice, st) == hipSuccess;
+  if (!ok) return CTR_E_DEVICE;
+  if (h_params)
+    hipLaunchKernelGGL(k_refresh_bf16, dim3(blocks_for(t->L.n_params)), dim3(BLOCK), 0, st, t->params + off,
+                       t->pb + off, t->L.n_params);
+  ok = hipStreamSynchronize(st) == hipSuccess;  // the host arrays may be pageable: they are free again on return
+  t->pend_mask = pending ? (t->pend_mask | (1u << replica)) : (t->pend_mask & ~(1u << replica));
+  return ok ? launch_status() : CTR_E_DEVICE;
+}
+
 }  // extern "C"

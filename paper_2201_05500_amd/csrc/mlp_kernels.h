@@ -177,6 +177,12 @@ __global__ void k_mlp_init(MlpLayout L, u64 seed_mul, float eps, u32 W, u64 stri
   if (vhat) vhat[i] = eps;
 }
 
+// bf16 copy of a flat fp32 vector (any length).
+__global__ void k_refresh_bf16(const float* __restrict__ src, bf16_t* __restrict__ dst, u64 n) {
+  const u64 i = (u64)blockIdx.x * BLOCK + threadIdx.x;
+  if (i < n) dst[i] = to_bf16(src[i]);
+}
+
 // Dense Adam step (Algorithm 2's m, v and model lines) on one replica's flat parameter vector;
 // every assignment in binary64 from the stored fp32 values, rounded once; refreshes the bf16 copy.
 //   mode 0: x -= lr m / sqrt(own v)   1: x -= lr m / sqrt(shared v)   2: moments only (merge pending)

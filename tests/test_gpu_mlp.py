@@ -30,7 +30,7 @@ def close_enough(gpu, ref, what, rtol=1e-2, frac_atol=2e-3, norm_tol=2e-3, outli
 
 
 def close_rows(gpu, ref, what, row_len, rtol=1e-2, frac_atol=2e-3, round_rows=0.05, round_err=1e-2,
-               mask_rows=2e-2, mask_err=0.6, norm_tol=1e-2):
+               mask_rows=2e-2, mask_err=0.6, norm_tol=3e-3):
     """Per-sample outputs (one row per sample) at sizes where rare rounding events are certain to occur somewhere.
     A back-propagated hidden gradient that sits on a bf16 rounding boundary may round the other way on the GPU
     (2^-8 relative on that element); everything downstream of it in that sample then moves by up to about
@@ -43,7 +43,7 @@ def close_rows(gpu, ref, what, row_len, rtol=1e-2, frac_atol=2e-3, round_rows=0.
     its spread, and one of 512 of them lies that close to zero with probability ~0.1: about 1 % of the samples.
     So: rows with any element outside atol + rtol |ref| may be at
     most `round_rows` of all rows; of those, rows with a norm-wise error above `round_err` at most `mask_rows`
-    (but one is always allowed), none above `mask_err`; and the whole tensor within `norm_tol` norm-wise."""
+    (but one is always allowed), none above `mask_err`; and all the other rows together within `norm_tol` norm-wise."""
     gpu = np.asarray(gpu, np.float64).reshape(-1, row_len)
     ref = np.asarray(ref, np.float64).reshape(-1, row_len)
     assert gpu.shape == ref.shape, what
@@ -56,8 +56,9 @@ def close_rows(gpu, ref, what, row_len, rtol=1e-2, frac_atol=2e-3, round_rows=0.
     n_mask = int((rowerr > round_err).sum())
     assert n_mask <= max(1, int(mask_rows * n)), "%s: %d of %d rows off by more than %g" % (what, n_mask, n, round_err)
     assert rowerr.max() <= mask_err, "%s: worst row error %.3g" % (what, rowerr.max())
-    nerr = np.linalg.norm(diff) / (np.linalg.norm(ref) + 1e-30)
-    assert nerr <= norm_tol, "%s: norm-wise error %.3g" % (what, nerr)
+    keep = rowerr <= round_err                      # the flipped-mask rows are bounded above, one by one
+    nerr = np.linalg.norm(diff[keep]) / (np.linalg.norm(ref[keep]) + 1e-30)
+    assert nerr <= norm_tol, "%s: norm-wise error %.3g over the rows without a flipped mask" % (what, nerr)
     return int(badrow.sum()), n_mask
 
 
@@ -209,3 +210,110 @@ def test_rocblas_fallback_path(monkeypatch):
         assert abs(float(loss.cpu()[0]) - float(oloss)) <= 1e-4 * max(1.0, float(oloss))
         close_rows(gp.cpu().numpy(), ogp, "fallback grad of pooled step %d" % s, in_dim)
     close_enough(g.export()["params"], o.params[0], "fallback parameters", rtol=1e-3, norm_tol=1e-3)
+
+
+def layerwise_close(gpu, ref, shapes, what, tol):
+    """Norm-wise comparison of a flat parameter-shaped vector, layer by layer (weights and biases apart): sums over
+    the batch average the rare per-sample rounding events out, but single elements near zero do not survive an
+    element-wise relative test."""
+    gpu = np.asarray(gpu, np.float64)
+    ref = np.asarray(ref, np.float64)
+    off = 0
+    for l, (i, k) in enumerate(shapes):
+        for name, n in (("weights", i * k), ("biases", k)):
+            a, b = gpu[off:off + n], ref[off:off + n]
+            off += n
+            err = np.linalg.norm(a - b)
+            assert err <= tol * np.linalg.norm(b) + 1e-12, "%s: layer %d %s off by %.3g norm-wise" % (
+                what, l, name, err / (np.linalg.norm(b) + 1e-30))
+
+
+def _sync_from_oracle(g, o):
+    """The GPU tower takes the oracle's state (so that a test of several steps compares single steps: the first
+    Adam steps are sign-like, and rounding-level differences between two runs of the dynamics grow)."""
+    for j in range(o.W):
+        assert g.load(j, o.params[j], o.m[j], o.v[j], o.vhat if (o.kstep and j == 0) else None,
+                      pending=o.pending[j]) == 0
+
+
+def test_export_import_round_trip():
+    rng = np.random.default_rng(3)
+    in_dim, hidden, B = 64, [32, 16], 32
+    a, o = _pair(in_dim, hidden, n_replicas=2, kstep=True)
+    b, _ = _pair(in_dim, hidden, seed=99, n_replicas=2, kstep=True)        # different initial weights
+    from paper_2201_05500_amd.binding import CTR_STEP_MERGE_PENDING
+    pooled, labels, dp, dl = _batch(rng, B, in_dim)
+    assert a.step(0, dp, dl)[0] == 0 and a.step(1, dp, dl, mode=CTR_STEP_MERGE_PENDING)[0] == 0
+    for j in range(2):                                                       # b := a, including the pending merge step
+        e = a.export(j)
+        assert b.load(j, e["params"], e["m"], e["v"], e["vhat"], pending=(j == 1)) == 0
+    for t in (a, b):
+        assert t.kstep_merge() == 0
+        assert t.step(0, dp, dl)[0] == 0
+    for j in range(2):
+        ea, eb = a.export(j), b.export(j)
+        for f in ("params", "m", "v", "vhat"):
+            assert np.array_equal(ea[f], eb[f]), (j, f)
+    with pytest.raises(ValueError):
+        b.load(0, np.zeros(5, np.float32))
+
+
+def test_random_tower_cases_differential():
+    """Seeded random towers (widths, depths, batch sizes, replicas, k, learning rates, input scales, bf16 or fp32
+    input), a few steps each with merges where due; before every step the GPU tower is given the oracle's state,
+    so each step is compared on its own: loss, per-sample gradients, moments, parameters, merged model.  The
+    bounds on the parameter-shaped quantities are loose (a flipped ReLU mask in a 32-wide layer moves one
+    sample's gradient by a quarter, and small batches do not average that away): this test is for gross errors
+    over many shapes, the fixed-shape tests above hold the tight bounds."""
+    import os
+    import torch
+    from paper_2201_05500_amd.binding import CTR_STEP_LOCAL, CTR_STEP_MERGE_PENDING
+    rng = np.random.default_rng(int(os.environ.get("CTR_TEST_RANDOM_SEED", "5")))
+    for case in range(int(os.environ.get("CTR_TEST_TOWER_CASES", "10"))):
+        in_dim = 8 * int(rng.integers(1, 80))
+        hidden = [8 * int(rng.integers(1, 40)) for _ in range(int(rng.integers(1, 5)))]
+        B = 8 * int(rng.integers(1, 100))
+        W = int(rng.choice([1, 1, 2, 3]))
+        kstep = W > 1 or bool(rng.integers(0, 2))
+        k = int(rng.integers(1, 3))
+        lr = float(rng.choice([1e-4, 1e-3, 1e-2]))
+        scale = float(rng.choice([0.01, 0.1, 1.0]))
+        as_bf16 = bool(rng.integers(0, 2))
+        g, o = _pair(in_dim, hidden, seed=case, n_replicas=W, kstep=kstep, lr=lr)
+        what = "tower case %d (in %d hidden %s B %d W %d k %d lr %g scale %g bf16 %s)" % (
+            case, in_dim, hidden, B, W, k, lr, scale, as_bf16)
+        for s in range(1, 4):
+            mode = CTR_STEP_MERGE_PENDING if (kstep and s % k == 0) else CTR_STEP_LOCAL
+            _sync_from_oracle(g, o)
+            before = [o.params[j].copy() for j in range(W)]
+            for j in range(W):
+                pooled, labels, dp, dl = _batch(rng, B, in_dim, scale=scale, p=0.3)
+                if as_bf16:
+                    dp = dp.to(torch.bfloat16)
+                    pooled = dp.float().cpu().numpy()
+                st, loss, gp = g.step(j, dp, dl, mode=mode)
+                assert st == 0, what
+                oloss, ogp = o.step(j, pooled, labels, mode)
+                assert abs(float(loss.cpu()[0]) - float(oloss)) <= 2e-4 * max(1.0, float(oloss)), what
+                close_rows(gp.cpu().numpy(), ogp, what + " grad of pooled, step %d replica %d" % (s, j), in_dim,
+                           round_rows=0.1, mask_rows=0.05)
+                e = g.export(j)
+                tag = what + ", step %d replica %d" % (s, j)
+                layerwise_close(e["m"], o.m[j], o.shapes, tag + " first moment", 3e-2)
+                layerwise_close(e["v"], o.v[j], o.shapes, tag + " second moment", 6e-2)
+                if mode == CTR_STEP_LOCAL:
+                    # one step from the same state: compared on the update itself, not on the (much larger) model
+                    layerwise_close(e["params"] - before[j], o.params[j] - before[j], o.shapes, tag + " model update", 1e-1)
+                else:
+                    assert np.array_equal(e["params"], before[j]), tag + ": a merge step moves nothing yet"
+            if mode == CTR_STEP_MERGE_PENDING:
+                _sync_from_oracle(g, o)
+                assert g.kstep_merge() == 0
+                o.kstep_merge()
+                for j in range(W):
+                    e = g.export(j)
+                    close_enough(e["params"], o.params[j], what + " merged model, step %d" % s, rtol=1e-5,
+                                 frac_atol=1e-5, norm_tol=1e-6, outliers=0.0)
+                    close_enough(e["vhat"], o.vhat, what + " shared denominator, step %d" % s, rtol=1e-6,
+                                 frac_atol=1e-6, norm_tol=1e-6, outliers=0.0)
+        g.close()
