@@ -122,7 +122,8 @@ class MlpOracle:
         y = np.asarray(labels, np.float64)
         B = y.size
         loss = np.mean(np.maximum(logits, 0.0) - logits * y + np.log1p(np.exp(-np.abs(logits))))
-        dz = ((1.0 / (1.0 + np.exp(-logits)) - y) / B)[:, None]     # output layer: kept in full precision
+        with np.errstate(over="ignore"):                            # exp(-z) may overflow to inf: 1 / (1 + inf) = 0, as it should
+            dz = ((1.0 / (1.0 + np.exp(-logits)) - y) / B)[:, None]  # output layer: kept in full precision
         grads = []
         for l in range(len(layers) - 1, -1, -1):
             W, b = layers[l]
