@@ -184,15 +184,17 @@ def main():
     # every input of every step resident in HBM before timing; for the k-step workload a "step"
     # is one local step of every replica (plus the merge on every k-th)
     reps = w.n_replicas if kstep else 1
-    batches = []
+    staged = []                                  # the configuration's own number of distinct batches, then repeated
     max_keys = 1
-    for s in range(total_steps):
+    for s in range(min(total_steps, w.steps)):
         for j in range(reps):
-            b = WL.make_batch(w, s % w.steps, replica=j, device=dev, with_grad=not full)   # the configuration's own step count, then repeat
+            b = WL.make_batch(w, s, replica=j, device=dev, with_grad=not full)
             if full:
-                b["labels"] = WL.make_labels(w, s % w.steps, device=dev)
-            batches.append(b)
+                b["labels"] = WL.make_labels(w, s, device=dev)
+            staged.append(b)
             max_keys = max(max_keys, b["keys"].numel())
+    # batches[s * reps + j]: the inputs of step s, replica j (a bounded set of device buffers however many steps)
+    batches = [staged[(s % w.steps) * reps + j] for s in range(total_steps) for j in range(reps)]
     G = w.n_segments
     table.reserve(max_keys, G)
     pooled = torch.empty((G, w.dim), dtype=torch.float32, device=dev)
