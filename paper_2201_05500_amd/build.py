@@ -7,6 +7,9 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libctr_sparse.so")
+SMOKE_SRC = os.path.join(CSRC, "standalone", "abi_smoke.c")   # plain C user of the ABI (no Python, no PyTorch)
+SMOKE_BIN = os.path.join(_HERE, "abi_smoke")
+INCLUDE = os.path.join(os.path.dirname(_HERE), "include")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall",
@@ -24,6 +27,14 @@ def build(verbose: bool = False) -> str:
     if verbose:
         print(" ".join(cmd))
     subprocess.check_call(cmd)
+    # the stand-alone C program: host compiler only, linked against the library just built
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cc = ["gcc", "-std=gnu11", "-O2", "-Wall", "-Wextra", "-D__HIP_PLATFORM_AMD__", "-I" + INCLUDE,
+          "-I" + os.path.join(rocm, "include"), SMOKE_SRC, "-o", SMOKE_BIN, "-L" + _HERE, "-lctr_sparse",
+          "-L" + os.path.join(rocm, "lib"), "-lamdhip64", "-lm", "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    if verbose:
+        print(" ".join(cc))
+    subprocess.check_call(cc)
     return LIB
 
 

@@ -104,3 +104,14 @@ def test_null_and_misaligned_arguments():
     assert L.ctr_kstep_merge(None, None) == B.CTR_E_INVAL
     assert L.ctr_push_adam(None, 0, None, None, 0, None) == B.CTR_E_INVAL
     assert L.ctr_last_status(None, None) == B.CTR_E_INVAL
+
+
+def test_headers_are_plain_c99(tmp_path):
+    """The boundary is a C ABI: both headers compile as strict C99 on their own."""
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "hdr.c"
+    src.write_text('#include "ctr_sparse.h"\n#include "ctr_mlp.h"\nint main(void) { return 0; }\n')
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I" + os.path.join(root, "include"),
+                           "-fsyntax-only", str(src)])

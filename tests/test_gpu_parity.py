@@ -432,3 +432,13 @@ def test_random_overflow_and_rollback_differential():
             compare_tables(gt, ot, what="overflow case %d step %d (status %d)" % (case, step, ost))
         gt.close()
     assert n_full > 0
+
+
+def test_plain_c_program_uses_the_abi_without_python():
+    """abi_smoke (plain C, HIP runtime only; built next to the library) runs one cycle and checks it against
+    Algorithm 2's first step in closed form."""
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2201_05500_amd", "abi_smoke")
+    assert os.path.exists(exe), "abi_smoke is not built: run paper_2201_05500_amd/build.py"
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and "abi_smoke ok" in r.stdout, r.stdout + r.stderr
