@@ -27,9 +27,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix-core rate
 # HBM traffic of the dominant kernel per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this script (profiles/large_step_kernels.txt), each counter scaled by what it reads for a 1 GiB
 # device copy in the same run (fetch x2.0, write x1.0).  Only known for the workload it was taken on.
-MEASURED_TRAFFIC_BYTES = {("large", "k_push_span"): 7654646 * 1024 * 2.0 + 4455023 * 1024 * 1.0}
+MEASURED_TRAFFIC_BYTES = {("large", "k_push_span"): 7454869 * 1024 * 2.0 + 4454775 * 1024 * 1.0}
 # the same counters summed over every library kernel of one step (the last of that run)
-MEASURED_STEP_TRAFFIC_BYTES = {"large": 12845572 * 1024 * 2.0 + 8719977 * 1024 * 1.0}
+MEASURED_STEP_TRAFFIC_BYTES = {"large": 12563482 * 1024 * 2.0 + 8621401 * 1024 * 1.0}
 
 
 def algorithmic_bytes_step(L, G, U, n_new, D, kstep, n_state=3):
