@@ -32,7 +32,7 @@ MEASURED_TRAFFIC_BYTES = {("large", "k_push_span"): 7454869 * 1024 * 2.0 + 44547
 MEASURED_STEP_TRAFFIC_BYTES = {"large": 12563482 * 1024 * 2.0 + 8621401 * 1024 * 1.0}
 
 
-def algorithmic_bytes_step(L, G, U, n_new, D, kstep, n_state=3):
+def algorithmic_bytes_step(L, G, U, n_new, D, kstep, n_state=3, grad_bytes=4):
     """Bytes one step must move (no sort scratch, no re-reads of hot rows)."""
     b = 8 * L                   # keys read
     b += 2 * 4 * (G + 1)        # offsets read by pull and by push-side bookkeeping
@@ -41,16 +41,16 @@ def algorithmic_bytes_step(L, G, U, n_new, D, kstep, n_state=3):
     b += 16 * U + 16 * n_new    # index probe (key + row id) per distinct key, plus inserts
     b += 4 * D * U              # compulsory row reads for pooling
     b += 4 * D * G              # pooled write
-    b += 4 * D * G              # pooled-gradient read
+    b += grad_bytes * D * G     # pooled-gradient read
     b += 2 * n_state * 4 * D * U  # optimizer: read + write x, m, v (x, G for AdaGrad)
     if kstep:
         b += 4 * D * U          # shared denominator read
     return b
 
 
-def algorithmic_bytes_push_kernel(L, G, U, D, kstep, n_state=3):
+def algorithmic_bytes_push_kernel(L, G, U, D, kstep, n_state=3, grad_bytes=4):
     """The push kernel's share: occurrence map read, pooled-gradient read, row state read + write."""
-    return 4 * L + 4 * D * G + 2 * n_state * 4 * D * U + (4 * D * U if kstep else 0)
+    return 4 * L + grad_bytes * D * G + 2 * n_state * 4 * D * U + (4 * D * U if kstep else 0)
 
 
 def algorithmic_bytes_pool_kernel(L, G, U, D, out_bytes=4):
@@ -143,6 +143,9 @@ def main():
                          "on a table filled by the warm-up's training steps")
     ap.add_argument("--no-tune", action="store_true",
                     help="full workload: skip the tower's set-up search for the fastest product kernels")
+    ap.add_argument("--grad-bf16", action="store_true",
+                    help="the pooled gradients reach the push as bfloat16 (ctr_push_adam_bf16): not the "
+                         "configuration the metric is quoted on, which has fp32 gradients")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy, so that a counter run has a kernel of known traffic")
     args = ap.parse_args()
@@ -191,6 +194,8 @@ def main():
             b = WL.make_batch(w, s, replica=j, device=dev, with_grad=not full)
             if full:
                 b["labels"] = WL.make_labels(w, s, device=dev)
+            elif args.grad_bf16:
+                b["grad"] = b["grad"].to(torch.bfloat16)
             staged.append(b)
             max_keys = max(max_keys, b["keys"].numel())
     # batches[s * reps + j]: the inputs of step s, replica j (a bounded set of device buffers however many steps)
@@ -208,7 +213,7 @@ def main():
         if not args.no_tune:          # set-up, before anything is timed
             if tower.tune(w.batch) != CTR_OK:
                 raise RuntimeError("ctr_mlp_tune failed")
-        grad_pooled = torch.empty((G, w.dim), dtype=torch.float32, device=dev)
+        grad_pooled = torch.empty((G, w.dim), dtype=torch.bfloat16 if args.grad_bf16 else torch.float32, device=dev)
         pooled_bf16 = torch.empty((G, w.dim), dtype=torch.bfloat16, device=dev)
         loss = torch.empty(1, dtype=torch.float32, device=dev)
         tower_events = []
@@ -301,11 +306,12 @@ def main():
     n_new_mean = (rows_after - rows_before) / (K * reps)
 
     D = w.dim
-    step_bytes = algorithmic_bytes_step(L_mean, G, U_mean, n_new_mean, D, shared_den, n_state)
+    gb = 2 if args.grad_bf16 else 4
+    step_bytes = algorithmic_bytes_step(L_mean, G, U_mean, n_new_mean, D, shared_den, n_state, gb)
     ms_step = elapsed * 1e3 / K
     stage_ms = {n: (ms / c if c else 0.0) for n, (ms, c) in stages.items()}
     kernel_bytes = {
-        "push": algorithmic_bytes_push_kernel(L_mean, G, U_mean, D, shared_den, n_state),
+        "push": algorithmic_bytes_push_kernel(L_mean, G, U_mean, D, shared_den, n_state, gb),
         "pool": algorithmic_bytes_pool_kernel(L_mean, G, U_mean, D, 2 if full else 4),
     }
     dominant = max(kernel_bytes, key=lambda n: stage_ms[n])
@@ -328,7 +334,8 @@ def main():
             "workload": "%s: R=%d rows, dim %d, batch %d x %d slots, Zipf s=%g over %d ranks, %d-bit keys%s" % (
                 w.name, w.capacity_rows, w.dim, w.batch, w.slots, w.zipf_s, w.zipf_universe, w.key_bits,
                 (", W=%d replicas, k=%d" % (w.n_replicas, w.k_step)) if kstep else "") + (
-                "" if args.variant == "alg2" else ", row update: " + args.variant),
+                "" if args.variant == "alg2" else ", row update: " + args.variant) + (
+                ", pooled gradients bf16" if args.grad_bf16 else ""),
             "keys_per_batch": L_mean,
             "distinct_keys_per_batch": U_mean,
             "new_rows_per_batch": n_new_mean,
@@ -338,7 +345,8 @@ def main():
         "step_algorithmic_GBps": step_bytes * reps / (ms_step * 1e-3) / 1e9,
         "step_frac_of_hbm_peak": step_bytes * reps / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "step_counter_traffic_GBps": (MEASURED_STEP_TRAFFIC_BYTES[w.name] / (ms_step * 1e-3) / 1e9
-                                      if (w.name in MEASURED_STEP_TRAFFIC_BYTES and args.variant == "alg2") else None),
+                                      if (w.name in MEASURED_STEP_TRAFFIC_BYTES and args.variant == "alg2" and not args.grad_bf16)
+                                      else None),
         "stage_ms": stage_ms,
         "roofline": {
             "bound": "hbm",
@@ -348,7 +356,7 @@ def main():
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBPS,
             "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, {"push": "k_push_span", "pool": "k_pool"}[dominant]))
-            if args.variant == "alg2" else None,
+            if (args.variant == "alg2" and not args.grad_bf16) else None,
         },
     }
     if full:

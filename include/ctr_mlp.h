@@ -83,6 +83,14 @@ int ctr_mlp_step_bf16(ctr_mlp* m, uint32_t replica, const uint16_t* d_pooled_bf1
 int ctr_mlp_forward_bf16(ctr_mlp* m, uint32_t replica, const uint16_t* d_pooled_bf16, uint32_t batch,
                          float* d_logits, void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ctr_mlp_step_bf16 with the gradient of the pooled embeddings written as bfloat16 too
+ * (d_grad_pooled_bf16[batch * in_dim], the input of ctr_push_adam_bf16): the first layer's
+ * input-gradient product rounds its fp32 sums to bf16 (nearest-even) on the way out, one more
+ * rounding point beside those listed above.  Everything else is as in ctr_mlp_step_bf16. */
+int ctr_mlp_step_bf16_grad_bf16(ctr_mlp* m, uint32_t replica, const uint16_t* d_pooled_bf16, const float* d_labels,
+                                uint32_t batch, uint16_t* d_grad_pooled_bf16, float* d_loss, void* d_workspace,
+                                size_t workspace_bytes, uint32_t mode, void* hip_stream);
+
 /* Optional set-up call: for every matrix product of a step at this batch size, times each
  * applicable matrix-core kernel of the vendor library on synthetic operands and keeps the fastest
  * one whose result agrees with the default kernel's (to 1e-3 of the largest element) and repeats

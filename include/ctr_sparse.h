@@ -181,6 +181,15 @@ int ctr_lookup_pool(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint
 int ctr_push_adam(ctr_table* t, uint32_t replica, ctr_batch* batch, const float* d_grad_pooled,
                   uint32_t mode, void* hip_stream);
 
+/* ctr_push_adam with the pooled gradients held as bfloat16 (the 16 high bits of the fp32 value
+ * they stand for; 8-byte aligned): what a bf16 tower hands back when it writes the input gradient
+ * in its own precision.  Every value is widened exactly and summed in binary64 like an fp32 one,
+ * so the result is that of ctr_push_adam on the widened gradients; each occurrence reads half the
+ * bytes.
+ *   d_grad_pooled_bf16[n_seg * D]  device, in */
+int ctr_push_adam_bf16(ctr_table* t, uint32_t replica, ctr_batch* batch, const uint16_t* d_grad_pooled_bf16,
+                       uint32_t mode, void* hip_stream);
+
 /* k-step merge (Algorithm 2, "global averaging" branch), over every row touched
  * by any replica since the previous merge:
  *   vhat = (1/W) sum_j v_j;

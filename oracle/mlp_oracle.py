@@ -137,8 +137,10 @@ class MlpOracle:
                 dpooled = da
         return loss, np.concatenate(grads[::-1]), dpooled
 
-    def step(self, replica, pooled, labels, mode=STEP_LOCAL):
-        """One training step; returns (loss float32, grad_pooled float32)."""
+    def step(self, replica, pooled, labels, mode=STEP_LOCAL, grad_bf16=False):
+        """One training step; returns (loss float32, grad_pooled float32).  With grad_bf16 the returned
+        gradient is rounded to bf16 (as float32 values): the HIP path's variant that hands the input
+        gradient back in the input's precision rounds it there, once, from the fp32 sums."""
         if mode == STEP_MERGE_PENDING and not self.kstep:
             raise ValueError("single-replica mode has no merge step")
         loss, g, dpooled = self.loss_and_grads(replica, pooled, labels)
@@ -151,6 +153,8 @@ class MlpOracle:
             x[:] = (x.astype(np.float64) - self.lr * m.astype(np.float64) / np.sqrt(den)).astype(np.float32)
         else:
             self.pending[replica] = True
+        if grad_bf16 and not self.exact:
+            return np.float32(loss), bf16_round(dpooled.astype(np.float32))
         return np.float32(loss), dpooled.astype(np.float32)
 
     def kstep_merge(self):

@@ -24,7 +24,7 @@ STAGE_NAMES = ("probe", "insert", "pool", "sort", "push", "fixup", "merge")
 
 EXPORTED = (
     "ctr_table_bytes", "ctr_workspace_bytes", "ctr_table_create", "ctr_table_destroy",
-    "ctr_pull_pool", "ctr_pull_pool_bf16", "ctr_lookup_pool", "ctr_push_adam", "ctr_kstep_merge", "ctr_table_load", "ctr_table_collect", "ctr_table_clear",
+    "ctr_pull_pool", "ctr_pull_pool_bf16", "ctr_lookup_pool", "ctr_push_adam", "ctr_push_adam_bf16", "ctr_kstep_merge", "ctr_table_load", "ctr_table_collect", "ctr_table_clear",
     "ctr_table_size", "ctr_table_export",
     "ctr_batch_export", "ctr_batch_stats", "ctr_last_status", "ctr_debug_set_geometry", "ctr_profile_enable",
     "ctr_profile_read",
@@ -82,6 +82,8 @@ def lib():
     L.ctr_pull_pool_bf16.argtypes = [vp, u32, vp, u64, vp, u32, vp, vp, vp, sz, C.POINTER(vp), vp]
     L.ctr_push_adam.restype = ci
     L.ctr_push_adam.argtypes = [vp, u32, vp, vp, u32, vp]
+    L.ctr_push_adam_bf16.restype = ci
+    L.ctr_push_adam_bf16.argtypes = [vp, u32, vp, vp, u32, vp]
     L.ctr_kstep_merge.restype = ci
     L.ctr_kstep_merge.argtypes = [vp, vp]
     L.ctr_table_load.restype = ci
@@ -269,8 +271,11 @@ class CtrTable:
         return st, pooled
 
     def push_adam(self, replica, batch, grad, mode=CTR_STEP_LOCAL):
-        return ctr_push_adam(self._handle, replica, batch, grad.data_ptr() if grad.numel() else None,
-                             mode, self.stream)
+        """grad: float32 or bfloat16 [n_seg, D] device tensor (the dtype picks the entry point)."""
+        ptr = grad.data_ptr() if grad.numel() else None
+        if grad.dtype == self._torch.bfloat16:
+            return lib().ctr_push_adam_bf16(self._handle, replica, batch, ptr, mode, self.stream)
+        return ctr_push_adam(self._handle, replica, batch, ptr, mode, self.stream)
 
     def kstep_merge(self):
         return ctr_kstep_merge(self._handle, self.stream)

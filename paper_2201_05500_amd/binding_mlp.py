@@ -9,7 +9,7 @@ from .binding import CTR_OK, CTR_STEP_LOCAL, lib as _base_lib
 
 CTR_MLP_MAX_HIDDEN = 6
 EXPORTED = ("ctr_mlp_bytes", "ctr_mlp_workspace_bytes", "ctr_mlp_create", "ctr_mlp_destroy", "ctr_mlp_step",
-            "ctr_mlp_forward", "ctr_mlp_step_bf16", "ctr_mlp_forward_bf16", "ctr_mlp_tune_workspace_bytes", "ctr_mlp_tune", "ctr_mlp_kstep_merge", "ctr_mlp_n_params", "ctr_mlp_export", "ctr_mlp_import")
+            "ctr_mlp_forward", "ctr_mlp_step_bf16", "ctr_mlp_step_bf16_grad_bf16", "ctr_mlp_forward_bf16", "ctr_mlp_tune_workspace_bytes", "ctr_mlp_tune", "ctr_mlp_kstep_merge", "ctr_mlp_n_params", "ctr_mlp_export", "ctr_mlp_import")
 
 
 class ctr_mlp_config(C.Structure):
@@ -52,6 +52,8 @@ def lib():
         L.ctr_mlp_forward.argtypes = [vp, u32, vp, u32, vp, vp, sz, vp]
         L.ctr_mlp_step_bf16.restype = ci
         L.ctr_mlp_step_bf16.argtypes = L.ctr_mlp_step.argtypes
+        L.ctr_mlp_step_bf16_grad_bf16.restype = ci
+        L.ctr_mlp_step_bf16_grad_bf16.argtypes = L.ctr_mlp_step.argtypes
         L.ctr_mlp_forward_bf16.restype = ci
         L.ctr_mlp_forward_bf16.argtypes = L.ctr_mlp_forward.argtypes
         L.ctr_mlp_tune_workspace_bytes.restype = sz
@@ -123,7 +125,8 @@ class CtrMlp:
             pass
 
     def step(self, replica, pooled, labels, grad_pooled=None, mode=CTR_STEP_LOCAL, loss=None):
-        """pooled f32 or bf16 [B, in], labels f32 [B] (device).  Returns (status, loss tensor[1], grad_pooled f32)."""
+        """pooled f32 or bf16 [B, in], labels f32 [B] (device).  Returns (status, loss tensor[1], grad_pooled):
+        the gradient is fp32 unless a bfloat16 `grad_pooled` is passed in (bf16 input only)."""
         torch = self._torch
         B = pooled.shape[0]
         self.reserve(B)
@@ -131,7 +134,12 @@ class CtrMlp:
             grad_pooled = torch.empty(pooled.shape, dtype=torch.float32, device=self.device)
         if loss is None:
             loss = torch.empty(1, dtype=torch.float32, device=self.device)
-        fn = lib().ctr_mlp_step_bf16 if pooled.dtype == torch.bfloat16 else lib().ctr_mlp_step
+        if grad_pooled.dtype == torch.bfloat16:
+            if pooled.dtype != torch.bfloat16:
+                raise ValueError("a bfloat16 gradient needs a bfloat16 input")
+            fn = lib().ctr_mlp_step_bf16_grad_bf16
+        else:
+            fn = lib().ctr_mlp_step_bf16 if pooled.dtype == torch.bfloat16 else lib().ctr_mlp_step
         st = fn(self._handle, replica, pooled.data_ptr(), labels.data_ptr(), B, grad_pooled.data_ptr(),
                 loss.data_ptr(), self._ws.data_ptr(), self.ws_bytes, mode, self.stream)
         return st, loss, grad_pooled

@@ -187,8 +187,15 @@ struct StageTimer {
         (void)hipEventDestroy(a);
         return;
       }
-      t->ev_start[stage].push_back(a);
-      t->ev_stop[stage].push_back(b);
+      try {
+        t->ev_start[stage].push_back(a);
+        t->ev_stop[stage].push_back(b);
+      } catch (...) {  // no timing for this execution; the lists stay of equal length
+        if (t->ev_start[stage].size() > t->ev_stop[stage].size()) t->ev_start[stage].pop_back();
+        (void)hipEventDestroy(a);
+        (void)hipEventDestroy(b);
+        return;
+      }
     }
     on = hipEventRecord(t->ev_start[stage][idx], st) == hipSuccess;
   }
@@ -478,8 +485,9 @@ int ctr_lookup_pool(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint
   return launch_status();
 }
 
-int ctr_push_adam(ctr_table* t, uint32_t replica, ctr_batch* handle, const float* d_grad_pooled, uint32_t mode,
-                  void* hip_stream) {
+// grad_bf16: d_grad_pooled points at bf16 rows instead of fp32 rows
+static int push_adam_impl(ctr_table* t, uint32_t replica, ctr_batch* handle, const void* d_grad_pooled, bool grad_bf16,
+                          uint32_t mode, void* hip_stream) {
   if (!t || !handle) return CTR_E_INVAL;
   if (replica >= t->W) return CTR_E_INVAL;
   if (mode != CTR_STEP_LOCAL && mode != CTR_STEP_MERGE_PENDING) return CTR_E_INVAL;
@@ -528,11 +536,20 @@ int ctr_push_adam(ctr_table* t, uint32_t replica, ctr_batch* handle, const float
     {
       StageTimer tm(t, CTR_STAGE_PUSH, st);
       const u32 grid = blocks_for((u64)wl.n_spans * t->lpr);
-      switch (kind) {
-        case STEP_ADAM_SHARED: CTR_SPAN_LAUNCH(k_push_span_shared); break;
-        case STEP_ADAGRAD: CTR_SPAN_LAUNCH(k_push_span_adagrad); break;
-        case STEP_ADAM_KINGMA: CTR_SPAN_LAUNCH(k_push_span_kingma); break;
-        default: CTR_SPAN_LAUNCH(k_push_span); break;
+      if (grad_bf16) {
+        switch (kind) {
+          case STEP_ADAM_SHARED: CTR_SPAN_LAUNCH(k_push_span_shared_g16); break;
+          case STEP_ADAGRAD: CTR_SPAN_LAUNCH(k_push_span_adagrad_g16); break;
+          case STEP_ADAM_KINGMA: CTR_SPAN_LAUNCH(k_push_span_kingma_g16); break;
+          default: CTR_SPAN_LAUNCH(k_push_span_g16); break;
+        }
+      } else {
+        switch (kind) {
+          case STEP_ADAM_SHARED: CTR_SPAN_LAUNCH(k_push_span_shared); break;
+          case STEP_ADAGRAD: CTR_SPAN_LAUNCH(k_push_span_adagrad); break;
+          case STEP_ADAM_KINGMA: CTR_SPAN_LAUNCH(k_push_span_kingma); break;
+          default: CTR_SPAN_LAUNCH(k_push_span); break;
+        }
       }
     }
     {
@@ -554,6 +571,17 @@ int ctr_push_adam(ctr_table* t, uint32_t replica, ctr_batch* handle, const float
   }
   t->has_live = false;
   return launch_status();
+}
+
+int ctr_push_adam(ctr_table* t, uint32_t replica, ctr_batch* handle, const float* d_grad_pooled, uint32_t mode,
+                  void* hip_stream) {
+  return push_adam_impl(t, replica, handle, d_grad_pooled, false, mode, hip_stream);
+}
+
+int ctr_push_adam_bf16(ctr_table* t, uint32_t replica, ctr_batch* handle, const uint16_t* d_grad_pooled_bf16,
+                       uint32_t mode, void* hip_stream) {
+  if (((uintptr_t)d_grad_pooled_bf16 & 7) != 0) return CTR_E_INVAL;
+  return push_adam_impl(t, replica, handle, d_grad_pooled_bf16, true, mode, hip_stream);
 }
 
 int ctr_kstep_merge(ctr_table* t, void* hip_stream) {
@@ -687,32 +715,36 @@ int ctr_batch_export(ctr_table* t, ctr_batch* handle, uint64_t* n_unique, uint64
   const size_t n = batch->n_keys;
   // Re-expression of device results for comparison: the device keeps the batch's
   // distinct set as row ids; the canonical form lists the keys in ascending order.
-  std::vector<u32> occ(n);
-  std::vector<u64> row_key(h.n_rows);
-  if (n && hipMemcpyAsync(occ.data(), batch->ws + batch->wl.off_occ_row, n * sizeof(u32), hipMemcpyDeviceToHost,
-                          st) != hipSuccess)
-    return CTR_E_DEVICE;
-  if (h.n_rows && hipMemcpyAsync(row_key.data(), t->row_key, (size_t)h.n_rows * sizeof(u64),
-                                 hipMemcpyDeviceToHost, st) != hipSuccess)
-    return CTR_E_DEVICE;
-  if (hipStreamSynchronize(st) != hipSuccess) return CTR_E_DEVICE;
-  std::vector<u32> rows(occ);
-  std::sort(rows.begin(), rows.end());
-  rows.erase(std::unique(rows.begin(), rows.end()), rows.end());
-  for (u32 r : rows)
-    if (r >= h.n_rows) return CTR_E_DEVICE;
-  std::vector<std::pair<u64, u32>> kr(rows.size());
-  for (size_t i = 0; i < rows.size(); ++i) kr[i] = {row_key[rows[i]], rows[i]};
-  std::sort(kr.begin(), kr.end());
-  if (n_unique) *n_unique = kr.size();
-  if (h_uniq)
-    for (size_t i = 0; i < kr.size(); ++i) h_uniq[i] = kr[i].first;
-  if (h_rows)
-    for (size_t i = 0; i < kr.size(); ++i) h_rows[i] = kr[i].second;
-  if (h_inverse) {
-    std::vector<u32> index_of_row(h.n_rows, 0);
-    for (size_t i = 0; i < kr.size(); ++i) index_of_row[kr[i].second] = (u32)i;
-    for (size_t p = 0; p < n; ++p) h_inverse[p] = index_of_row[occ[p]];
+  try {  // host containers below: no exception may cross the C boundary
+    std::vector<u32> occ(n);
+    std::vector<u64> row_key(h.n_rows);
+    if (n && hipMemcpyAsync(occ.data(), batch->ws + batch->wl.off_occ_row, n * sizeof(u32), hipMemcpyDeviceToHost,
+                            st) != hipSuccess)
+      return CTR_E_DEVICE;
+    if (h.n_rows && hipMemcpyAsync(row_key.data(), t->row_key, (size_t)h.n_rows * sizeof(u64),
+                                   hipMemcpyDeviceToHost, st) != hipSuccess)
+      return CTR_E_DEVICE;
+    if (hipStreamSynchronize(st) != hipSuccess) return CTR_E_DEVICE;
+    std::vector<u32> rows(occ);
+    std::sort(rows.begin(), rows.end());
+    rows.erase(std::unique(rows.begin(), rows.end()), rows.end());
+    for (u32 r : rows)
+      if (r >= h.n_rows) return CTR_E_DEVICE;
+    std::vector<std::pair<u64, u32>> kr(rows.size());
+    for (size_t i = 0; i < rows.size(); ++i) kr[i] = {row_key[rows[i]], rows[i]};
+    std::sort(kr.begin(), kr.end());
+    if (n_unique) *n_unique = kr.size();
+    if (h_uniq)
+      for (size_t i = 0; i < kr.size(); ++i) h_uniq[i] = kr[i].first;
+    if (h_rows)
+      for (size_t i = 0; i < kr.size(); ++i) h_rows[i] = kr[i].second;
+    if (h_inverse) {
+      std::vector<u32> index_of_row(h.n_rows, 0);
+      for (size_t i = 0; i < kr.size(); ++i) index_of_row[kr[i].second] = (u32)i;
+      for (size_t p = 0; p < n; ++p) h_inverse[p] = index_of_row[occ[p]];
+    }
+  } catch (const std::bad_alloc&) {
+    return CTR_E_NOMEM;
   }
   return CTR_OK;
 }

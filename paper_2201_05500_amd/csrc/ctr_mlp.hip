@@ -14,6 +14,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <new>
 #include <vector>
 
 #include "common.h"
@@ -117,7 +118,9 @@ inline int launch_status() { return hipGetLastError() == hipSuccess ? CTR_OK : C
 //   OP_FWD  Z[B x o]  = H[B x i] W[i x o]      -> gemm(N, N, m = o, n = B, k = i)
 //   OP_DW   dW[i x o] = H^T[i x B] dZ[B x o]   -> gemm(N, T, m = o, n = i, k = B)
 //   OP_DH   dH[B x i] = dZ[B x o] W^T[o x i]   -> gemm(T, N, m = i, n = B, k = o)
-enum { OP_FWD = 0, OP_DW = 1, OP_DH = 2, N_OPS = 3 };
+//   OP_DH16 the first layer's OP_DH with the result rounded to bf16 on the way out (the gradient of a
+//           bf16 input handed back in the input's precision); planned for layer 0 only
+enum { OP_FWD = 0, OP_DW = 1, OP_DH = 2, OP_DH16 = 3, N_OPS = 4 };
 
 struct LtPlan {
   bool ready = false;  // descriptors exist and an algorithm was found
@@ -185,7 +188,8 @@ bool make_plan(ctr_mlp* t, u32 l, int op, u32 B, LtPlan* p) {
                                               g.opa == HIPBLAS_OP_N ? g.k : g.m, g.lda) == HIPBLAS_STATUS_SUCCESS &&
                   hipblasLtMatrixLayoutCreate(&p->lb, HIP_R_16BF, g.opb == HIPBLAS_OP_N ? g.k : g.n,
                                               g.opb == HIPBLAS_OP_N ? g.n : g.k, g.ldb) == HIPBLAS_STATUS_SUCCESS &&
-                  hipblasLtMatrixLayoutCreate(&p->lc, HIP_R_32F, g.m, g.n, g.ldc) == HIPBLAS_STATUS_SUCCESS;
+                  hipblasLtMatrixLayoutCreate(&p->lc, op == OP_DH16 ? HIP_R_16BF : HIP_R_32F, g.m, g.n, g.ldc) ==
+                      HIPBLAS_STATUS_SUCCESS;
   if (!ok) return false;
   p->m = g.m; p->n = g.n; p->k = g.k;
   hipblasLtMatmulPreference_t pref = nullptr;
@@ -216,24 +220,33 @@ void ensure_plans(ctr_mlp* t, u32 B) {
   destroy_plans(t);
   for (u32 l = 0; l + 1 < t->L.n_layers; ++l)
     for (int op = 0; op < N_OPS; ++op)
-      if (!make_plan(t, l, op, B, &t->plans[l][op])) destroy_plan(&t->plans[l][op]);
+      if ((op == OP_DH16 && l != 0) || !make_plan(t, l, op, B, &t->plans[l][op])) destroy_plan(&t->plans[l][op]);
   t->plan_batch = B;
 }
 
+// rocBLAS's default kernel for a product (bf16 operands, fp32 accumulation; the result fp32, or
+// bf16 for OP_DH16).
+bool rocblas_product(ctr_mlp* t, u32 l, int op, u32 B, const void* a, const void* b, void* c) {
+  const float alpha = 1.0f, beta = 0.0f;
+  const GemmShape g = shape_of(t->L, l, op, B);
+  const rocblas_datatype ct = op == OP_DH16 ? rocblas_datatype_bf16_r : rocblas_datatype_f32_r;
+  return rocblas_gemm_ex(t->blas, g.opa == HIPBLAS_OP_N ? rocblas_operation_none : rocblas_operation_transpose,
+                         g.opb == HIPBLAS_OP_N ? rocblas_operation_none : rocblas_operation_transpose, g.m, g.n, g.k,
+                         &alpha, a, rocblas_datatype_bf16_r, g.lda, b, rocblas_datatype_bf16_r, g.ldb, &beta, c, ct,
+                         g.ldc, c, ct, g.ldc, rocblas_datatype_f32_r, rocblas_gemm_algo_standard, 0, 0) ==
+         rocblas_status_success;
+}
+
 // One product on the matrix cores: the planned hipBLASLt kernel, else rocBLAS's default.
-bool product(ctr_mlp* t, u32 l, int op, u32 B, const void* a, const void* b, float* c, char* ws, const WsLayout& S,
+// c: fp32, except bf16 for OP_DH16.
+bool product(ctr_mlp* t, u32 l, int op, u32 B, const void* a, const void* b, void* c, char* ws, const WsLayout& S,
              hipStream_t st) {
   const float alpha = 1.0f, beta = 0.0f;
   const LtPlan& p = t->plans[l][op];
   if (t->plan_batch == B && p.ready)
     return hipblasLtMatmul(t->lt, p.desc, &alpha, a, p.la, b, p.lb, &beta, c, p.lc, c, p.lc, &p.algo,
                            ws + S.off_lt_ws, p.ws, st) == HIPBLAS_STATUS_SUCCESS;
-  const GemmShape g = shape_of(t->L, l, op, B);
-  return rocblas_gemm_ex(t->blas, g.opa == HIPBLAS_OP_N ? rocblas_operation_none : rocblas_operation_transpose,
-                         g.opb == HIPBLAS_OP_N ? rocblas_operation_none : rocblas_operation_transpose, g.m, g.n, g.k,
-                         &alpha, a, rocblas_datatype_bf16_r, g.lda, b, rocblas_datatype_bf16_r, g.ldb, &beta, c,
-                         rocblas_datatype_f32_r, g.ldc, c, rocblas_datatype_f32_r, g.ldc, rocblas_datatype_f32_r,
-                         rocblas_gemm_algo_standard, 0, 0) == rocblas_status_success;
+  return rocblas_product(t, l, op, B, a, b, c);
 }
 
 // ---------------------------------------------------------------- kernel search (ctr_mlp_tune)
@@ -269,7 +282,7 @@ struct Tuner {
   }
 
   // Milliseconds of one run of `algo` into `out`, or a negative value if the library refuses it.
-  float run(const LtPlan& p, const hipblasLtMatmulAlgo_t& algo, size_t wsz, const void* a, const void* b, float* out) {
+  float run(const LtPlan& p, const hipblasLtMatmulAlgo_t& algo, size_t wsz, const void* a, const void* b, void* out) {
     const float alpha = 1.0f, beta = 0.0f;
     if (hipEventRecord(e0, st) != hipSuccess) return -1.0f;
     const hipblasStatus_t rc = hipblasLtMatmul(t->lt, p.desc, &alpha, a, p.la, b, p.lb, &beta, out, p.lc, out, p.lc,
@@ -287,25 +300,38 @@ struct Tuner {
   }
 
   // The candidate agrees with the reference (accumulation order aside) and repeats bit for bit.
+  // fp32 results: to 1e-3 of the largest element.  bf16 results (n even): two correct kernels may
+  // round an element to neighbouring bf16 values, one unit in the last place of the largest
+  // element (2^-7 of it) at most.
   bool valid(const LtPlan& p, const hipblasLtMatmulAlgo_t& algo, size_t wsz, const void* a, const void* b,
-             const float* ref, float* cand, u64 n) {
+             const void* ref, void* cand, u64 n, bool out_bf16) {
     u32 h1[4], h2[4];
     for (int rep = 0; rep < 2; ++rep) {
       if (hipMemsetAsync(d_words, 0, 4 * sizeof(u32), st) != hipSuccess) return false;
       if (run(p, algo, wsz, a, b, cand) < 0.0f) return false;
-      hipLaunchKernelGGL(k_max_diff, dim3(2048), dim3(BLOCK), 0, st, ref, cand, n, d_words);
-      hipLaunchKernelGGL(k_hash_bits, dim3(2048), dim3(BLOCK), 0, st, cand, n, (unsigned long long*)(d_words + 2));
+      if (out_bf16) {
+        hipLaunchKernelGGL(k_max_diff_bf16, dim3(2048), dim3(BLOCK), 0, st, (const bf16_t*)ref, (const bf16_t*)cand, n,
+                           d_words);
+        hipLaunchKernelGGL(k_hash_bits, dim3(2048), dim3(BLOCK), 0, st, (const float*)cand, n / 2,
+                           (unsigned long long*)(d_words + 2));
+      } else {
+        hipLaunchKernelGGL(k_max_diff, dim3(2048), dim3(BLOCK), 0, st, (const float*)ref, (const float*)cand, n,
+                           d_words);
+        hipLaunchKernelGGL(k_hash_bits, dim3(2048), dim3(BLOCK), 0, st, (const float*)cand, n,
+                           (unsigned long long*)(d_words + 2));
+      }
       if (!read_words(rep ? h2 : h1)) return false;
     }
     float md, ma;
     memcpy(&md, &h1[0], 4);
     memcpy(&ma, &h1[1], 4);
-    return md <= 1e-3f * ma && h1[2] == h2[2] && h1[3] == h2[3];
+    return md <= (out_bf16 ? 0.0078125f : 1e-3f) * ma && h1[2] == h2[2] && h1[3] == h2[3];
   }
 
   // Replaces the plan's kernel by the fastest applicable one that passes valid().  A product for
   // which nothing better is found keeps the library's choice.  Returns false on a device error only.
   bool tune_one(u32 l, int op, u32 B, float* ref, float* cand) {
+    if (op == OP_DH16 && l != 0) return true;  // exists for the first layer only
     LtPlan& p = t->plans[l][op];
     if (!p.ready) {
       if (getenv("CTR_MLP_TUNE_LOG")) fprintf(stderr, "ctr_mlp_tune: layer %u product %d: no plan (rocBLAS runs it)\n", l, op);
@@ -316,25 +342,17 @@ struct Tuner {
     bf16_t* dzb = (bf16_t*)(ws + S.off_dz[0]);                                              // B x out_l
     const bf16_t* w = t->pb + L.w_off[l];
     const void* a = op == OP_DW ? (const void*)dzb : (const void*)w;
-    const void* b = op == OP_DH ? (const void*)dzb : (const void*)act_in;
+    const void* b = (op == OP_DH || op == OP_DH16) ? (const void*)dzb : (const void*)act_in;
     const u64 n = (u64)p.m * p.n;
     hipLaunchKernelGGL(k_fill_pattern_bf16, dim3(2048), dim3(BLOCK), 0, st, act_in, (u64)B * L.in[l], 0x1234u + l);
     hipLaunchKernelGGL(k_fill_pattern_bf16, dim3(2048), dim3(BLOCK), 0, st, dzb, (u64)B * L.out[l], 0x9876u + l);
     // reference: rocBLAS's own kernel for the same product
-    {
-      const float alpha = 1.0f, beta = 0.0f;
-      const GemmShape g = shape_of(L, l, op, B);
-      if (rocblas_gemm_ex(t->blas, g.opa == HIPBLAS_OP_N ? rocblas_operation_none : rocblas_operation_transpose,
-                          g.opb == HIPBLAS_OP_N ? rocblas_operation_none : rocblas_operation_transpose, g.m, g.n, g.k,
-                          &alpha, a, rocblas_datatype_bf16_r, g.lda, b, rocblas_datatype_bf16_r, g.ldb, &beta, ref,
-                          rocblas_datatype_f32_r, g.ldc, ref, rocblas_datatype_f32_r, g.ldc, rocblas_datatype_f32_r,
-                          rocblas_gemm_algo_standard, 0, 0) != rocblas_status_success)
-        return true;  // nothing to compare against: keep the plan as it is
-    }
+    if (!rocblas_product(t, l, op, B, a, b, ref)) return true;  // nothing to compare against: keep the plan as it is
     std::vector<hipblasLtMatmulHeuristicResult_t> all;
     const GemmShape g = shape_of(L, l, op, B);
+    const hipDataType out_t = op == OP_DH16 ? HIP_R_16BF : HIP_R_32F;
     if (hipblaslt_ext::getAllAlgos(t->lt, hipblaslt_ext::GemmType::HIPBLASLT_GEMM, g.opa, g.opb, HIP_R_16BF, HIP_R_16BF,
-                                   HIP_R_32F, HIP_R_32F, HIPBLAS_COMPUTE_32F, all) != HIPBLAS_STATUS_SUCCESS)
+                                   out_t, out_t, HIPBLAS_COMPUTE_32F, all) != HIPBLAS_STATUS_SUCCESS)
       return true;
     struct Timed { float ms; size_t idx, wsz; };
     std::vector<Timed> timed;
@@ -377,7 +395,7 @@ struct Tuner {
                 hipblaslt_ext::getKernelNameFromAlgo(t->lt, all[timed[r].idx].algo).substr(0, 110).c_str());
     for (const Timed& c : timed) {
       if (c.ms >= 0.97f * current) break;  // not better than what the library chose by itself
-      const bool good = valid(p, all[c.idx].algo, c.wsz, a, b, ref, cand, n);
+      const bool good = valid(p, all[c.idx].algo, c.wsz, a, b, ref, cand, n, op == OP_DH16);
       if (log) fprintf(stderr, "ctr_mlp_tune:   candidate %zu at %.3f ms: %s\n", c.idx, c.ms, good ? "taken" : "rejected");
       if (good) {
         p.algo = all[c.idx].algo;
@@ -517,10 +535,12 @@ static int mlp_forward_impl(ctr_mlp* t, uint32_t replica, const float* d_pooled,
   return launch_status();
 }
 
+// The gradient of the pooled input goes to d_grad_pooled (fp32) or to d_grad_pooled_bf16: exactly one is given.
 static int mlp_step_impl(ctr_mlp* t, uint32_t replica, const float* d_pooled, const bf16_t* d_pooled_bf16,
-                         const float* d_labels, uint32_t batch, float* d_grad_pooled, float* d_loss,
-                         void* d_workspace, size_t workspace_bytes, uint32_t mode, void* hip_stream) {
-  if (!t || (!d_pooled && !d_pooled_bf16) || !d_labels || !d_grad_pooled || !d_loss || !d_workspace)
+                         const float* d_labels, uint32_t batch, float* d_grad_pooled, bf16_t* d_grad_pooled_bf16,
+                         float* d_loss, void* d_workspace, size_t workspace_bytes, uint32_t mode, void* hip_stream) {
+  if (!t || (!d_pooled && !d_pooled_bf16) || !d_labels || (!d_grad_pooled == !d_grad_pooled_bf16) || !d_loss ||
+      !d_workspace)
     return CTR_E_INVAL;
   if (replica >= t->cfg.n_replicas || batch == 0 || batch % 8 != 0 || batch > CTR_MLP_MAX_BATCH) return CTR_E_INVAL;
   if (mode != CTR_STEP_LOCAL && mode != CTR_STEP_MERGE_PENDING) return CTR_E_INVAL;
@@ -574,8 +594,12 @@ static int mlp_step_impl(ctr_mlp* t, uint32_t replica, const float* d_pooled, co
     hipLaunchKernelGGL(k_colsum_final, dim3(blocks_for(o)), dim3(BLOCK), 0, st, partial, (u32)o,
                        grads + L.w_off[l] + (u64)i * o);
     // dH_prev[B x i] = dZ[B x o] W^T[o x i]; for the first layer this is the gradient of the pooled input
-    float* dst = l == 0 ? d_grad_pooled : da;
-    if (!product(t, (u32)l, OP_DH, B, PB + L.w_off[l], dz, dst, ws, S, st)) return CTR_E_DEVICE;
+    if (l == 0 && d_grad_pooled_bf16) {
+      if (!product(t, 0, OP_DH16, B, PB + L.w_off[0], dz, d_grad_pooled_bf16, ws, S, st)) return CTR_E_DEVICE;
+    } else {
+      float* dst = l == 0 ? d_grad_pooled : da;
+      if (!product(t, (u32)l, OP_DH, B, PB + L.w_off[l], dz, dst, ws, S, st)) return CTR_E_DEVICE;
+    }
     if (l > 0) {
       const u64 n = (u64)B * i;
       hipLaunchKernelGGL(k_relu_bwd_bf16, dim3(blocks_for(n / 4)), dim3(BLOCK), 0, st, da, h_prev, n, dz_next);
@@ -609,7 +633,7 @@ int ctr_mlp_step(ctr_mlp* t, uint32_t replica, const float* d_pooled, const floa
                  float* d_grad_pooled, float* d_loss, void* d_workspace, size_t workspace_bytes, uint32_t mode,
                  void* hip_stream) {
   if (!d_pooled) return CTR_E_INVAL;
-  return mlp_step_impl(t, replica, d_pooled, nullptr, d_labels, batch, d_grad_pooled, d_loss, d_workspace,
+  return mlp_step_impl(t, replica, d_pooled, nullptr, d_labels, batch, d_grad_pooled, nullptr, d_loss, d_workspace,
                        workspace_bytes, mode, hip_stream);
 }
 
@@ -617,8 +641,16 @@ int ctr_mlp_step_bf16(ctr_mlp* t, uint32_t replica, const uint16_t* d_pooled_bf1
                       uint32_t batch, float* d_grad_pooled, float* d_loss, void* d_workspace,
                       size_t workspace_bytes, uint32_t mode, void* hip_stream) {
   if (!d_pooled_bf16) return CTR_E_INVAL;
-  return mlp_step_impl(t, replica, nullptr, d_pooled_bf16, d_labels, batch, d_grad_pooled, d_loss, d_workspace,
-                       workspace_bytes, mode, hip_stream);
+  return mlp_step_impl(t, replica, nullptr, d_pooled_bf16, d_labels, batch, d_grad_pooled, nullptr, d_loss,
+                       d_workspace, workspace_bytes, mode, hip_stream);
+}
+
+int ctr_mlp_step_bf16_grad_bf16(ctr_mlp* t, uint32_t replica, const uint16_t* d_pooled_bf16, const float* d_labels,
+                                uint32_t batch, uint16_t* d_grad_pooled_bf16, float* d_loss, void* d_workspace,
+                                size_t workspace_bytes, uint32_t mode, void* hip_stream) {
+  if (!d_pooled_bf16 || !d_grad_pooled_bf16) return CTR_E_INVAL;
+  return mlp_step_impl(t, replica, nullptr, d_pooled_bf16, d_labels, batch, nullptr, d_grad_pooled_bf16, d_loss,
+                       d_workspace, workspace_bytes, mode, hip_stream);
 }
 
 size_t ctr_mlp_tune_workspace_bytes(const ctr_mlp_config* cfg, uint32_t batch) {
@@ -648,9 +680,15 @@ int ctr_mlp_tune(ctr_mlp* t, uint32_t batch, void* d_workspace, size_t workspace
   u32* d_words = (u32*)(ws + S.total + 2 * res_bytes);  // [0..1] max diff / max abs, [2..3] a 64-bit hash
   Tuner tu(t, st, ws, S, d_words);
   if (!tu.ok) return CTR_E_DEVICE;
-  for (u32 l = 0; l + 1 < t->L.n_layers; ++l)
-    for (int op = 0; op < N_OPS; ++op)
-      if (!tu.tune_one(l, op, batch, ref, cand)) return CTR_E_DEVICE;
+  try {  // the candidate lists are host containers: no exception may cross the C boundary
+    for (u32 l = 0; l + 1 < t->L.n_layers; ++l)
+      for (int op = 0; op < N_OPS; ++op)
+        if (!tu.tune_one(l, op, batch, ref, cand)) return CTR_E_DEVICE;
+  } catch (const std::bad_alloc&) {
+    return CTR_E_NOMEM;
+  } catch (...) {
+    return CTR_E_DEVICE;
+  }
   return launch_status();
 }
 

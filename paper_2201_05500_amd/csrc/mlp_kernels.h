@@ -261,6 +261,27 @@ __global__ void k_max_diff(const float* __restrict__ a, const float* __restrict_
   }
 }
 
+// k_max_diff for two bf16 arrays.
+__global__ void k_max_diff_bf16(const bf16_t* __restrict__ a, const bf16_t* __restrict__ b, u64 n,
+                                u32* __restrict__ out) {
+  float md = 0.0f, ma = 0.0f;
+  for (u64 i = (u64)blockIdx.x * BLOCK + threadIdx.x; i < n; i += (u64)gridDim.x * BLOCK) {
+    const float x = from_bf16(a[i]), y = from_bf16(b[i]);
+    float d = fabsf(x - y);
+    if (!(d == d)) d = __uint_as_float(0x7F800000u);
+    md = fmaxf(md, d);
+    ma = fmaxf(ma, fabsf(x));
+  }
+  for (int off = WAVE / 2; off > 0; off >>= 1) {
+    md = fmaxf(md, __shfl_xor(md, off, WAVE));
+    ma = fmaxf(ma, __shfl_xor(ma, off, WAVE));
+  }
+  if (lane_id() == 0) {
+    atomicMax(&out[0], __float_as_uint(md));
+    atomicMax(&out[1], __float_as_uint(ma));
+  }
+}
+
 // Order-independent 64-bit sum of (bit pattern x per-index odd multiplier): equal for equal contents.
 __global__ void k_hash_bits(const float* __restrict__ a, u64 n, unsigned long long* __restrict__ out) {
   u64 h = 0;

@@ -151,10 +151,11 @@ __device__ __forceinline__ void add_partial(const double* __restrict__ part, u32
 // the PB gradient-row loads and the x/m/v loads of every row that ends inside
 // the batch, so that a group keeps several KB in flight instead of one
 // dependent row at a time.
-template <int LPR, int KIND>
+// GB: the gradient rows are bf16 (two bytes per component, widened exactly) instead of fp32.
+template <int LPR, int KIND, bool GB>
 __device__ __forceinline__ void push_span_body(const DevHeader* hdr, const u32* __restrict__ sr,
                                                const u32* __restrict__ ss, u32 n, u32 span,
-                                               const float* __restrict__ grad, float* __restrict__ values,
+                                               const void* __restrict__ grad_any, float* __restrict__ values,
                                                const float* __restrict__ vhat, u32* __restrict__ row_state, u32 D,
                                                u32 rf, const AdamParams& P, double* __restrict__ head_part,
                                                double* __restrict__ tail_part, u32* __restrict__ span_flags,
@@ -219,7 +220,17 @@ __device__ __forceinline__ void push_span_body(const DevHeader* hdr, const u32* 
 #pragma unroll
     for (int i = 0; i < PB; ++i) {
       gv[i].x = gv[i].y = gv[i].z = gv[i].w = 0.0f;
-      if (valid[i] && col_ok) gv[i] = ldg4(grad + (u64)g[i] * D + 4 * c);
+      if (valid[i] && col_ok) {
+        if constexpr (GB) {
+          const uint2 raw = *reinterpret_cast<const uint2*>(static_cast<const bf16_t*>(grad_any) + (u64)g[i] * D + 4 * c);
+          gv[i].x = __uint_as_float(raw.x << 16);
+          gv[i].y = __uint_as_float(raw.x & 0xFFFF0000u);
+          gv[i].z = __uint_as_float(raw.y << 16);
+          gv[i].w = __uint_as_float(raw.y & 0xFFFF0000u);
+        } else {
+          gv[i] = ldg4(static_cast<const float*>(grad_any) + (u64)g[i] * D + 4 * c);
+        }
+      }
     }
 #pragma unroll
     for (int i = 0; i < PB; ++i)
@@ -265,17 +276,21 @@ __device__ __forceinline__ void push_span_body(const DevHeader* hdr, const u32* 
 
 #define CTR_PUSH_SPAN_ARGS                                                                                      \
   const DevHeader *hdr, const u32 *__restrict__ sr, const u32 *__restrict__ ss, u32 n, u32 span,               \
-      const float *__restrict__ grad, float *__restrict__ values, const float *__restrict__ vhat,              \
+      const void *__restrict__ grad, float *__restrict__ values, const float *__restrict__ vhat,               \
       u32 *__restrict__ row_state, u32 D, u32 rf, AdamParams P, double *__restrict__ head_part,                \
       double *__restrict__ tail_part, u32 *__restrict__ span_flags, u32 *__restrict__ span_rows
 #define CTR_PUSH_SPAN_PASS \
   hdr, sr, ss, n, span, grad, values, vhat, row_state, D, rf, P, head_part, tail_part, span_flags, span_rows
 
 // one kernel per step kind (the dispatch macro on the host takes kernels templated on LPR only)
-#define CTR_DEFINE_PUSH_SPAN(NAME, KIND)                                                       \
-  template <int LPR>                                                                           \
-  __global__ void __launch_bounds__(BLOCK, CTR_PUSH_MIN_WAVES) NAME(CTR_PUSH_SPAN_ARGS) {      \
-    push_span_body<LPR, KIND>(CTR_PUSH_SPAN_PASS);                                             \
+#define CTR_DEFINE_PUSH_SPAN(NAME, KIND)                                                          \
+  template <int LPR>                                                                              \
+  __global__ void __launch_bounds__(BLOCK, CTR_PUSH_MIN_WAVES) NAME(CTR_PUSH_SPAN_ARGS) {         \
+    push_span_body<LPR, KIND, false>(CTR_PUSH_SPAN_PASS);                                         \
+  }                                                                                               \
+  template <int LPR>                                                                              \
+  __global__ void __launch_bounds__(BLOCK, CTR_PUSH_MIN_WAVES) NAME##_g16(CTR_PUSH_SPAN_ARGS) {   \
+    push_span_body<LPR, KIND, true>(CTR_PUSH_SPAN_PASS);                                          \
   }
 CTR_DEFINE_PUSH_SPAN(k_push_span, STEP_ADAM_OWN)
 CTR_DEFINE_PUSH_SPAN(k_push_span_shared, STEP_ADAM_SHARED)

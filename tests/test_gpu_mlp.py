@@ -168,6 +168,66 @@ def test_bf16_input_equals_fp32_input_bit_for_bit():
         assert np.array_equal(ea[k], eb[k]), k
 
 
+@pytest.mark.parametrize("fallback", [False, True])
+@pytest.mark.parametrize("tuned", [False, True])
+def test_bf16_gradient_output(monkeypatch, fallback, tuned):
+    """ctr_mlp_step_bf16_grad_bf16: the gradient of the pooled input rounded to bf16 on the way out of the first
+    layer's product (vendor kernel, searched kernel, or the rocBLAS fallback).  Against the oracle's gradient
+    rounded the same way (a value on a rounding boundary may land on the neighbouring bf16 value: 2^-8 relative,
+    inside the element bound); the tower's own state is bit for bit that of the fp32-gradient step."""
+    import torch
+    if fallback:
+        monkeypatch.setenv("CTR_MLP_NO_HIPBLASLT", "1")
+    rng = np.random.default_rng(41)
+    in_dim, hidden, B = 384, [256, 64], 512
+    ga, o = _pair(in_dim, hidden)
+    gb, _ = _pair(in_dim, hidden)
+    if fallback:
+        monkeypatch.delenv("CTR_MLP_NO_HIPBLASLT")
+    if tuned:
+        assert ga.tune(B) == 0 and gb.tune(B) == 0
+    for s in range(3):
+        pooled, labels, dp, dl = _batch(rng, B, in_dim)
+        dpb = dp.to(torch.bfloat16)
+        g16 = torch.full((B, in_dim), float("nan"), dtype=torch.bfloat16, device="cuda")
+        sa, lossa, gpa = ga.step(0, dpb, dl)
+        sb, lossb, gpb = gb.step(0, dpb, dl, grad_pooled=g16)
+        assert sa == 0 and sb == 0 and gpb.dtype == torch.bfloat16 and gpb.data_ptr() == g16.data_ptr()
+        if not tuned:                                            # a search may pick differently for the twin
+            assert torch.equal(lossa, lossb)
+        oloss, ogp = o.step(0, pooled, labels, grad_bf16=True)
+        assert abs(float(lossb.cpu()[0]) - float(oloss)) <= 1e-4 * max(1.0, float(oloss))
+        assert not (ogp.view(np.uint32) & 0xFFFF).any()
+        got = gpb.to(torch.float32).cpu().numpy()
+        close_rows(got, ogp, "bf16 grad of pooled step %d" % s, in_dim)
+        # against the fp32 gradient of the twin tower: one bf16 rounding apart (2^-9 relative), unless the two
+        # products took kernels with different summation orders, which the row criteria allow for
+        close_rows(got, gpa.cpu().numpy(), "bf16 against fp32 gradient step %d" % s, in_dim)
+        if not tuned:
+            ea, eb = ga.export(), gb.export()
+            for k in ("params", "m", "v"):
+                assert np.array_equal(ea[k], eb[k]), k
+    close_enough(gb.export()["params"], o.params[0], "parameters", rtol=1e-3, norm_tol=1e-3)
+
+
+def test_bf16_gradient_output_argument_checks():
+    import torch
+    from paper_2201_05500_amd import binding as B
+    from paper_2201_05500_amd import binding_mlp as BM
+    g, _ = _pair(64, [32])
+    x16 = torch.zeros((16, 64), dtype=torch.bfloat16, device="cuda")
+    y = torch.zeros(16, device="cuda")
+    g.reserve(16)
+    fn = BM.lib().ctr_mlp_step_bf16_grad_bf16
+    assert fn(g._handle, 0, x16.data_ptr(), y.data_ptr(), 16, None, y.data_ptr(), g._ws.data_ptr(), g.ws_bytes, 0,
+              g.stream) == B.CTR_E_INVAL
+    assert fn(g._handle, 0, None, y.data_ptr(), 16, x16.data_ptr(), y.data_ptr(), g._ws.data_ptr(), g.ws_bytes, 0,
+              g.stream) == B.CTR_E_INVAL
+    with pytest.raises(ValueError):
+        g.step(0, torch.zeros((16, 64), device="cuda"), y, grad_pooled=x16)      # fp32 input, bf16 gradient
+    torch.cuda.synchronize()
+
+
 def test_kernel_search_keeps_the_results():
     """ctr_mlp_tune may swap the product kernels: outputs stay within the accumulation-order tolerance of the
     untuned tower's, parity with the oracle holds, and the tuned tower repeats its results bit for bit."""

@@ -191,3 +191,22 @@ def test_bf16_rounding_points_change_the_result_only_slightly():
     assert 0 < abs(la - lb) < 2e-2
     assert np.linalg.norm(ga - gb) / np.linalg.norm(ga) < 3e-2
     assert np.linalg.norm(da - db) / np.linalg.norm(da) < 3e-2
+
+
+def test_bf16_gradient_option_rounds_the_returned_gradient_only():
+    """step(grad_bf16=True): the returned input gradient is the plain one rounded once to bf16 (checked against
+    a library's conversion); loss, parameters and moments are those of the plain step."""
+    import torch
+    rng = np.random.default_rng(5)
+    a = M.MlpOracle(48, [24, 8], init_seed=2)
+    b = M.MlpOracle(48, [24, 8], init_seed=2)
+    for _ in range(2):
+        pooled = (0.1 * rng.standard_normal((16, 48))).astype(F32)
+        labels = (rng.random(16) < 0.3).astype(F32)
+        la, ga = a.step(0, pooled, labels)
+        lb, gb = b.step(0, pooled, labels, grad_bf16=True)
+        assert la == lb
+        assert np.array_equal(gb, torch.from_numpy(ga).to(torch.bfloat16).to(torch.float32).numpy())
+        assert (gb != ga).any()
+        assert np.array_equal(a.params[0], b.params[0]) and np.array_equal(a.m[0], b.m[0])
+        assert np.array_equal(a.v[0], b.v[0])
