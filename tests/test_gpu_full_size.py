@@ -83,10 +83,12 @@ def test_large_config_two_steps_full_table(capsys):
 
 
 @pytest.mark.timeout(1200)
-def test_full_step_config_one_step(capsys):
+@pytest.mark.parametrize("grad_bf16", [False, True])
+def test_full_step_config_one_step(capsys, grad_bf16):
     """The whole training step at the size bench.py --workload full times: batch 16384 x 300 slots into the
     2^24-row table, tower 19200-1024-512-256-1.  The tower is compared with its oracle on the very pooled
-    input the GPU produced; the table with the table oracle fed the very gradient the GPU tower produced."""
+    input the GPU produced; the table with the table oracle fed the very gradient the GPU tower produced.
+    grad_bf16: the tower hands the gradient of the pooled input to the push as bf16 (bench.py --grad-bf16)."""
     import torch
     from oracle import mlp_oracle as M
     from paper_2201_05500_amd.binding import CTR_OK, CtrTable
@@ -104,13 +106,14 @@ def test_full_step_config_one_step(capsys):
     labels = WL.make_labels(w, 0, device="cuda:0")
     bn = WL.as_numpy(bt)
     L = bn["keys"].size
-    _say(capsys, "full step, L", L)
+    _say(capsys, "full step, L", L, "(bf16 gradient hand-over)" if grad_bf16 else "")
 
     st, gb, pooled16, pooled = gt.pull_pool_bf16(0, bt["keys"], bt["offsets"], want_f32=True)
     assert st == CTR_OK and gt.last_status() == CTR_OK
     assert torch.equal(pooled16, pooled.to(torch.bfloat16))
-    st, loss, gp = gm.step(0, pooled16.view(w.batch, in_dim), labels)
-    assert st == CTR_OK
+    g16 = torch.empty((w.batch, in_dim), dtype=torch.bfloat16, device="cuda:0") if grad_bf16 else None
+    st, loss, gp = gm.step(0, pooled16.view(w.batch, in_dim), labels, grad_pooled=g16)
+    assert st == CTR_OK and gp.dtype == (torch.bfloat16 if grad_bf16 else torch.float32)
     assert gt.push_adam(0, gb, gp.view(w.n_segments, w.dim)) == CTR_OK
     assert gt.last_status() == CTR_OK
     _say(capsys, "GPU step done, loss", float(loss.cpu()[0]))
@@ -132,10 +135,10 @@ def test_full_step_config_one_step(capsys):
 
     pooled_h = pooled.cpu().numpy().reshape(w.batch, in_dim)
     del pooled, pooled16
-    oloss, ogp = om.step(0, pooled_h, labels.cpu().numpy())
+    oloss, ogp = om.step(0, pooled_h, labels.cpu().numpy(), grad_bf16=grad_bf16)
     _say(capsys, "oracle tower done, loss", float(oloss))
     assert abs(float(loss.cpu()[0]) - float(oloss)) <= 1e-4 * max(1.0, float(oloss))
-    gp_h = gp.cpu().numpy()
+    gp_h = gp.to(torch.float32).cpu().numpy()                           # widening a bf16 value is exact
     n_round, n_mask = close_rows(gp_h, ogp, "gradient of the pooled input", in_dim)
     _say(capsys, "gradient rows with rounding cascades:", n_round, "with a flipped mask:", n_mask, "of", w.batch)
     e = gm.export()
