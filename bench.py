@@ -128,6 +128,78 @@ def cpu_baseline(w, WL, seconds_hint=20.0):
     }
 
 
+def seam_bench(args, torch, WL, CtrTable, CTR_OK, dev):
+    """Working-set seam at the size of the benchmarked table: ctr_table_load of every row of the table in
+    chunks (the keys are new, so this is insert + state write), ctr_table_collect of the same keys,
+    ctr_table_clear.  One JSON line; `steps` is the number of load / collect / clear cycles timed."""
+    w = WL.WORKLOADS[args.workload]
+    D, R = w.dim, w.capacity_rows
+    chunk = min(R, 1 << 22)
+    n_chunks = R // chunk
+    table = CtrTable(R, D, lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, init_seed=1, init_std=w.init_std,
+                     load_factor=w.load_factor, device=dev)
+    table.reserve(chunk, 0)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(5)
+    x = torch.randn((chunk, D), device=dev, generator=gen) * 0.01
+    m = torch.randn((chunk, D), device=dev, generator=gen) * 0.01
+    v = torch.rand((chunk, D), device=dev, generator=gen) + 1e-8
+    # distinct keys: an odd multiplier is a bijection of the integers modulo 2^key_bits
+    idx = torch.arange(n_chunks * chunk, dtype=torch.int64, device=dev)
+    keys = ((idx * -7046029254386353131) & ((1 << w.key_bits) - 1)).view(n_chunks, chunk)  # 0x9E37...7C15 as int64
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    t_load = t_collect = t_clear = 0.0
+    cycles = max(1, args.steps)
+    for c in range(args.warmup + cycles):
+        e = [ev() for _ in range(4)]
+        e[0].record()
+        for i in range(n_chunks):
+            if table.table_load(keys[i], x, m, v) != CTR_OK:
+                raise RuntimeError("ctr_table_load failed")
+        e[1].record()
+        for i in range(n_chunks):
+            st, gx, gm, gv, found = table.table_collect(0, keys[i])
+            if st != CTR_OK:
+                raise RuntimeError("ctr_table_collect failed")
+        e[2].record()
+        if c == 0:                         # once, untimed: the state read back is the state loaded
+            torch.cuda.synchronize()
+            if table.last_status() != CTR_OK or table.n_rows != n_chunks * chunk:
+                raise RuntimeError("load did not create every row")
+            if not (bool(found.all()) and torch.equal(gx, x) and torch.equal(gm, m) and torch.equal(gv, v)):
+                raise RuntimeError("collect does not return what load wrote")
+        del gx, gm, gv, found
+        if table.table_clear() != CTR_OK:
+            raise RuntimeError("ctr_table_clear failed")
+        e[3].record()
+        torch.cuda.synchronize()
+        if c >= args.warmup:
+            t_load += e[0].elapsed_time(e[1])
+            t_collect += e[1].elapsed_time(e[2])
+            t_clear += e[2].elapsed_time(e[3])
+    rows = n_chunks * chunk
+    row_bytes = 8 + 16 + 2 * 3 * 4 * D     # key read, index slot, state read from the caller + written to the table
+    n_slots = 1 << max(6, (int(R / w.load_factor) - 1).bit_length())
+    ms_load, ms_collect, ms_clear = t_load / cycles, t_collect / cycles, t_clear / cycles
+    out = {
+        "metric": "working-set seam: rows loaded into / collected from the table per second (1 GPU)",
+        "value": rows / (ms_load * 1e-3), "unit": "rows/s (load)", "n_gpus": 1, "steps": cycles, "warmup": args.warmup,
+        "ms_per_step": ms_load + ms_collect + ms_clear, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "seam of %s: %d rows of dim %d (x, m, v) in %d chunks of %d keys, %d-bit keys, every key new"
+                   % (w.name, rows, D, n_chunks, chunk, w.key_bits)},
+        "load": {"ms": ms_load, "rows_per_s": rows / (ms_load * 1e-3),
+                 "algorithmic_GBps": rows * row_bytes / (ms_load * 1e-3) / 1e9,
+                 "frac_of_hbm_peak": rows * row_bytes / (ms_load * 1e-3) / 1e9 / HBM_PEAK_GBPS},
+        "collect": {"ms": ms_collect, "rows_per_s": rows / (ms_collect * 1e-3),
+                    "algorithmic_GBps": rows * (row_bytes + 4) / (ms_collect * 1e-3) / 1e9,
+                    "frac_of_hbm_peak": rows * (row_bytes + 4) / (ms_collect * 1e-3) / 1e9 / HBM_PEAK_GBPS},
+        "clear": {"ms": ms_clear, "algorithmic_GBps": (16 * n_slots + 4 * R) / (ms_clear * 1e-3) / 1e9,
+                  "frac_of_hbm_peak": (16 * n_slots + 4 * R) / (ms_clear * 1e-3) / 1e9 / HBM_PEAK_GBPS},
+    }
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -146,6 +218,9 @@ def main():
     ap.add_argument("--grad-bf16", action="store_true",
                     help="the pooled gradients reach the push as bfloat16 (ctr_push_adam_bf16): not the "
                          "configuration the metric is quoted on, which has fp32 gradients")
+    ap.add_argument("--seam", action="store_true",
+                    help="time the working-set seam instead of training steps: ctr_table_load of every row of the "
+                         "workload's table, ctr_table_collect of the same keys, ctr_table_clear (one cycle per step)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy, so that a counter run has a kernel of known traffic")
     args = ap.parse_args()
@@ -162,6 +237,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     dev = "cuda:0"
+    if args.seam:
+        seam_bench(args, torch, WL, CtrTable, CTR_OK, dev)
+        return
     w = WL.WORKLOADS[args.workload]
     kstep = w.k_step > 0
     full = w.name == "full"

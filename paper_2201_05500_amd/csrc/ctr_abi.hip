@@ -234,8 +234,9 @@ int status_code_from_bits(u32 bits) {
 // Key -> row for every occurrence, inserting unseen keys (rows numbered by first occurrence, state
 // initialised); on return of the enqueued work occ_row[p] holds the row of keys[p], or the pull has
 // failed and was rolled back (device status set).  d_offsets may be null (nothing to validate).
+// init_new_rows = false: the caller overwrites the state of every row of the batch anyway (a working-set load).
 static void enqueue_lookup_insert(ctr_table* t, const WorkLayout& wl, char* ws, const u64* d_keys, u32 n,
-                                  const u32* d_offsets, u32 n_segments, hipStream_t st) {
+                                  const u32* d_offsets, u32 n_segments, bool init_new_rows, hipStream_t st) {
   u32* occ_row = (u32*)(ws + wl.off_occ_row);
   u32* tile_count = (u32*)(ws + wl.off_tile_count);
   u32* first_bits = (u32*)(ws + wl.off_first_bits);
@@ -261,10 +262,12 @@ static void enqueue_lookup_insert(ctr_table* t, const WorkLayout& wl, char* ws, 
     if (n > 0) {
       hipLaunchKernelGGL(k_assign_rows, dim3(wl.n_bit_tiles), dim3(BLOCK), 0, st, t->hdr, t->slots, occ_row,
                          first_bits, wl.n_bit_words, tile_count, t->row_key);
-      const u32 grid = std::min<u32>(blocks_for((u64)n * t->lpr), 4096);
-      LPR_DISPATCH(t->lpr, k_init_rows, grid, st, t->hdr, t->row_key, t->values, t->tl.replica_stride, t->W,
-                   t->vhat, t->D, t->rf, t->seed_mul, t->init_scale,
-                   (t->cfg.flags & CTR_F_BIAS_CORRECTION) ? 0.0f : t->cfg.eps);
+      if (init_new_rows) {
+        const u32 grid = std::min<u32>(blocks_for((u64)n * t->lpr), 4096);
+        LPR_DISPATCH(t->lpr, k_init_rows, grid, st, t->hdr, t->row_key, t->values, t->tl.replica_stride, t->W,
+                     t->vhat, t->D, t->rf, t->seed_mul, t->init_scale,
+                     (t->cfg.flags & CTR_F_BIAS_CORRECTION) ? 0.0f : t->cfg.eps);
+      }
       hipLaunchKernelGGL(k_resolve, dim3(wl.n_probe_tiles), dim3(BLOCK), 0, st, t->hdr, t->slots, occ_row,
                          pend_list, tile_pending, wl.probe_tile);
     }
@@ -371,7 +374,7 @@ static int pull_pool_impl(ctr_table* t, uint32_t replica, const uint64_t* d_keys
   const u32 n = (u32)n_keys;
   u32* occ_row = (u32*)(b->ws + wl.off_occ_row);
   u32* seg_of = (u32*)(b->ws + wl.off_seg_of);
-  enqueue_lookup_insert(t, wl, b->ws, (const u64*)d_keys, n, d_offsets, n_segments, st);
+  enqueue_lookup_insert(t, wl, b->ws, (const u64*)d_keys, n, d_offsets, n_segments, true, st);
   if (n_segments > 0) {
     StageTimer tm(t, CTR_STAGE_POOL, st);
     const float* vals = t->values + (u64)replica * t->tl.replica_stride;
@@ -614,7 +617,7 @@ int ctr_table_load(ctr_table* t, const uint64_t* d_keys, uint64_t n_keys, const 
   ++t->generation;
   hipStream_t st = (hipStream_t)hip_stream;
   const u32 n = (u32)n_keys;
-  enqueue_lookup_insert(t, wl, (char*)d_workspace, (const u64*)d_keys, n, nullptr, 0, st);
+  enqueue_lookup_insert(t, wl, (char*)d_workspace, (const u64*)d_keys, n, nullptr, 0, false, st);
   if (n > 0) {
     const u32* occ_row = (const u32*)((char*)d_workspace + wl.off_occ_row);
     LPR_DISPATCH(t->lpr, k_load_rows, blocks_for((u64)n * t->lpr), st, t->hdr, occ_row, n, t->values,

@@ -127,8 +127,7 @@ k_probe_insert(DevHeader* hdr, Slot* slots, u32 slot_mask, const u64* __restrict
 
 // ---------------------------------------------------------------- ranking of new keys
 
-constexpr int BITS_WORDS_PER_THREAD = 8;
-constexpr int BITS_TILE_WORDS = BLOCK * BITS_WORDS_PER_THREAD;  // 2048 words = 65536 occurrences per tile
+constexpr int BITS_TILE_WORDS = BLOCK;  // one bitmap word per thread: 8192 occurrences per tile
 
 // Over the pending occurrences (one block per probe tile): marks those that are the first
 // occurrence of their (new) key.
@@ -149,11 +148,8 @@ __global__ void k_count_first(const DevHeader* hdr, const u32* __restrict__ firs
                               u32* __restrict__ tile_count) {
   if (hdr->status) return;
   __shared__ u32 lds[4];
-  const u32 w0 = blockIdx.x * BITS_TILE_WORDS + threadIdx.x * BITS_WORDS_PER_THREAD;
-  u32 cnt = 0;
-#pragma unroll
-  for (int i = 0; i < BITS_WORDS_PER_THREAD; ++i)
-    if (w0 + i < n_words) cnt += (u32)__popc(first_bits[w0 + i]);
+  const u32 w = blockIdx.x * BITS_TILE_WORDS + threadIdx.x;
+  const u32 cnt = (w < n_words) ? (u32)__popc(first_bits[w]) : 0u;
   u32 total;
   block_exclusive_scan(cnt, lds, total);
   if (threadIdx.x == 0) tile_count[blockIdx.x] = total;
@@ -197,37 +193,39 @@ __global__ void k_scan_tiles(DevHeader* hdr, u32* __restrict__ tile_count, u32 n
 // Gives the first occurrence of every new key its row id (tile base + rank in
 // occurrence order), or, when the pull failed, frees the slot again: clearing
 // exactly the slots claimed by this pull restores the index as it was.
+// A block takes one tile of the bitmap: the words and their exclusive popcount prefix go to LDS,
+// then every thread looks at 32 occurrences of its own (consecutive lanes, consecutive
+// occurrences), so the slot accesses of a block are independent of each other.
 __global__ void k_assign_rows(const DevHeader* hdr, Slot* slots, const u32* __restrict__ occ_row,
                               const u32* __restrict__ first_bits, u32 n_words, const u32* __restrict__ tile_base,
                               u64* __restrict__ row_key) {
   const u32 rollback = hdr->rollback;
   if (hdr->status && !rollback) return;
   __shared__ u32 lds[4];
-  const u32 w0 = blockIdx.x * BITS_TILE_WORDS + threadIdx.x * BITS_WORDS_PER_THREAD;
-  u32 bits[BITS_WORDS_PER_THREAD];
-  u32 cnt = 0;
-#pragma unroll
-  for (int i = 0; i < BITS_WORDS_PER_THREAD; ++i) {
-    bits[i] = (w0 + i < n_words) ? first_bits[w0 + i] : 0u;
-    cnt += (u32)__popc(bits[i]);
-  }
+  __shared__ u32 wbits[BITS_TILE_WORDS];
+  __shared__ u32 wrank[BITS_TILE_WORDS];
+  const u32 word0 = blockIdx.x * BITS_TILE_WORDS;
+  const u32 mine = (word0 + threadIdx.x < n_words) ? first_bits[word0 + threadIdx.x] : 0u;
   u32 total;
-  u32 rank = block_exclusive_scan(cnt, lds, total);
+  const u32 ex = block_exclusive_scan((u32)__popc(mine), lds, total);
   if (total == 0) return;
+  wbits[threadIdx.x] = mine;
+  wrank[threadIdx.x] = ex;
+  __syncthreads();
   const u32 row0 = hdr->n_rows_base + tile_base[blockIdx.x];
-#pragma unroll
-  for (int i = 0; i < BITS_WORDS_PER_THREAD; ++i) {
-    u32 b = bits[i];
-    while (b) {
-      const u32 bit = (u32)__ffs((int)b) - 1u;
-      b &= b - 1u;
-      const u32 p = (w0 + i) * 32u + bit;
+  const u32 bit = threadIdx.x & 31u;
+#pragma unroll 4
+  for (u32 i = 0; i < 32; ++i) {
+    const u32 word = i * (BLOCK / 32) + (threadIdx.x >> 5);
+    const u32 b = wbits[word];
+    if ((b >> bit) & 1u) {
+      const u32 p = (word0 + word) * 32u + bit;
       Slot* s = &slots[occ_row[p] & ~OCC_PEND_FLAG];
       if (rollback) {
         s->first_p = 0xFFFFFFFFu;
         s->key = KEY_EMPTY;
       } else {
-        const u32 row = row0 + rank++;
+        const u32 row = row0 + wrank[word] + (u32)__popc(b & ((1u << bit) - 1u));
         s->row = row;
         row_key[row] = s->key;
       }
