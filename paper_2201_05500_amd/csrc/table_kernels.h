@@ -130,17 +130,27 @@ k_probe_insert(DevHeader* hdr, Slot* slots, u32 slot_mask, const u64* __restrict
 constexpr int BITS_TILE_WORDS = BLOCK;  // one bitmap word per thread: 8192 occurrences per tile
 
 // Over the pending occurrences (one block per probe tile): marks those that are the first
-// occurrence of their (new) key.
+// occurrence of their (new) key.  A probe tile owns whole words of the bitmap (its size is a
+// multiple of 32 occurrences), so the bits are gathered in LDS and the words that hold any are
+// stored plainly; the probe launch has zeroed the bitmap.
 __global__ void k_flag_first(const DevHeader* hdr, const Slot* __restrict__ slots, const u32* __restrict__ occ_row,
                              const u32* __restrict__ pend_list, const u32* __restrict__ tile_pending,
                              u32 probe_tile, u32* __restrict__ first_bits) {
   if (hdr->status) return;
   const u32 cnt = tile_pending[blockIdx.x];
+  if (cnt == 0) return;
+  __shared__ u32 bits[PROBE_MAX_ITEMS * BLOCK / 32];
+  const u32 tile_words = probe_tile / 32u, tile0 = blockIdx.x * probe_tile;
+  for (u32 i = threadIdx.x; i < tile_words; i += BLOCK) bits[i] = 0;
+  __syncthreads();
   for (u32 i = threadIdx.x; i < cnt; i += BLOCK) {
-    const u32 p = pend_list[blockIdx.x * probe_tile + i];
+    const u32 p = pend_list[tile0 + i];
     const u32 h = occ_row[p] & ~OCC_PEND_FLAG;
-    if (slots[h].first_p == p) atomicOr(&first_bits[p >> 5], 1u << (p & 31u));
+    if (slots[h].first_p == p) atomicOr(&bits[(p - tile0) >> 5], 1u << (p & 31u));
   }
+  __syncthreads();
+  for (u32 i = threadIdx.x; i < tile_words; i += BLOCK)
+    if (bits[i]) first_bits[(tile0 >> 5) + i] = bits[i];
 }
 
 // Number of first occurrences per tile of the bitmap.
@@ -162,14 +172,16 @@ __global__ void k_scan_tiles(DevHeader* hdr, u32* __restrict__ tile_count, u32 n
     return;
   }
   __shared__ u32 lds[4];
-  u32 carry = 0;
-  for (u32 t0 = 0; t0 < n_tiles; t0 += BLOCK) {
-    const u32 t = t0 + threadIdx.x;
-    const u32 v = (t < n_tiles) ? tile_count[t] : 0;
-    u32 total;
-    const u32 ex = block_exclusive_scan(v, lds, total);
-    if (t < n_tiles) tile_count[t] = carry + ex;
-    carry += total;
+  const u32 per = (n_tiles + BLOCK - 1) / BLOCK;  // consecutive tiles per thread, one block-wide scan in all
+  const u32 c0 = min(threadIdx.x * per, n_tiles), c1 = min(c0 + per, n_tiles);
+  u32 sum = 0;
+  for (u32 t = c0; t < c1; ++t) sum += tile_count[t];
+  u32 carry;
+  u32 ex = block_exclusive_scan(sum, lds, carry);
+  for (u32 t = c0; t < c1; ++t) {
+    const u32 v = tile_count[t];
+    tile_count[t] = ex;
+    ex += v;
   }
   if (threadIdx.x == 0) {
     u32 err = hdr->pull_err;
