@@ -115,3 +115,15 @@ def test_headers_are_plain_c99(tmp_path):
     src.write_text('#include "ctr_sparse.h"\n#include "ctr_mlp.h"\nint main(void) { return 0; }\n')
     subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I" + os.path.join(root, "include"),
                            "-fsyntax-only", str(src)])
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    """No CPU fallback exists: without the built HIP library the binding raises instead of computing."""
+    from paper_2201_05500_amd import binding as B
+    from paper_2201_05500_amd import binding_mlp as BM
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "libctr_sparse.so"))
+    monkeypatch.setattr(B, "_lib", None)
+    with pytest.raises(RuntimeError, match="missing"):
+        B.lib()
+    with pytest.raises(RuntimeError, match="missing"):          # the tower's binding loads the same library
+        BM.lib()
