@@ -93,6 +93,17 @@ def test_workspace_bytes_grow_with_keys_and_dim():
     assert B.ctr_workspace_bytes(_cfg(), 1 << 31, 10) == 0           # n_keys limit
 
 
+def test_workspace_bytes_never_shrink_with_the_batch_size():
+    """The work geometry changes at 2, 4 and 8 Mi occurrences (shorter spans below each threshold need more
+    partial sums): a workspace sized for max_keys must cover every smaller batch."""
+    for dim in (16, 64):
+        sizes = [1, 1000, (1 << 20), (2 << 20) - 1, 2 << 20, (3 << 20), (4 << 20) - 1, 4 << 20, (6 << 20),
+                 (8 << 20) - 1, 8 << 20, 12 << 20, 40 << 20]
+        need = [B.ctr_workspace_bytes(_cfg(dim=dim), n, 10) for n in sizes]
+        assert all(a <= b for a, b in zip(need, need[1:])), (dim, need)
+        assert all(n > 0 for n in need)
+
+
 def test_null_and_misaligned_arguments():
     L = B.lib()
     out = C.c_void_p()

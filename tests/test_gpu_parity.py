@@ -274,6 +274,32 @@ def test_host_detected_errors():
     torch.cuda.synchronize()
 
 
+def test_workspace_sized_once_for_the_largest_batch_serves_smaller_ones():
+    """A C caller sizes the workspace once with ctr_workspace_bytes(max_keys) and sends batches of varying
+    size: none may be refused, also just below the batch sizes where the work geometry changes."""
+    import torch
+    from paper_2201_05500_amd import binding as B
+    D, max_keys = 64, 2 << 20
+    gt = B.CtrTable(1 << 12, D, init_seed=3)
+    need = B.ctr_workspace_bytes(gt.cfg, max_keys, 64)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    gen = torch.Generator(device="cuda").manual_seed(11)
+    for n in (max_keys, max_keys - 1, max_keys - 12345, (3 << 19) + 7, 1 << 20, 1000):
+        keys = torch.randint(1, 3000, (n,), dtype=torch.int64, device="cuda", generator=gen)
+        offs = torch.linspace(0, n, 65, device="cuda").to(torch.int32)
+        offs[-1] = n
+        pooled = torch.empty((64, D), dtype=torch.float32, device="cuda")
+        st, h = B.ctr_pull_pool(gt._handle, 0, keys.data_ptr(), n, offs.data_ptr(), 64, pooled.data_ptr(),
+                                ws.data_ptr(), need, gt.stream)
+        assert st == B.CTR_OK, n
+        grad = torch.ones((64, D), dtype=torch.float32, device="cuda")
+        assert B.ctr_push_adam(gt._handle, 0, h, grad.data_ptr(), B.CTR_STEP_LOCAL, gt.stream) == B.CTR_OK
+        assert gt.last_status() == B.CTR_OK
+        # every occurrence was pooled: a row's x starts within +-3.5 init_std, so sums stay finite and non-trivial
+        assert torch.isfinite(pooled).all()
+    torch.cuda.synchronize()
+
+
 def test_same_calls_give_bit_identical_results():
     w = WL.scaled(WL.WORKLOADS["large"], capacity_rows=1 << 15, zipf_universe=20000, batch=64)
     outs = []
