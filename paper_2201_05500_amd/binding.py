@@ -189,6 +189,7 @@ class CtrTable:
         self.table_bytes = nbytes
         self._mem = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
         self._ws = None
+        self._ws_of_live_batch = None
         self.ws_bytes = 0
         self._handle = None
         st, h = ctr_table_create(self.cfg, self._mem.data_ptr(), nbytes, self.stream)
@@ -209,6 +210,9 @@ class CtrTable:
         need += getattr(self, "_ws_slack", 0)
         if need > self.ws_bytes:
             self._torch.cuda.synchronize(self.device)
+            # a batch that was pulled and not yet pushed keeps its lists in the old workspace: that
+            # tensor stays alive until the next pull makes the batch stale
+            self._ws_of_live_batch = self._ws
             self._ws = self._torch.empty(need, dtype=self._torch.uint8, device=self.device)
             self.ws_bytes = need
 
@@ -231,6 +235,7 @@ class CtrTable:
         torch = self._torch
         n_keys, n_seg = keys.numel(), offsets.numel() - 1
         self.reserve(max(n_keys, 1), n_seg)
+        self._ws_of_live_batch = None              # the previous batch goes stale with this pull
         if pooled is None:
             pooled = torch.empty((n_seg, self.D), dtype=torch.float32, device=self.device)
         st, batch = ctr_pull_pool(self._handle, replica, keys.data_ptr() if n_keys else None, n_keys,
@@ -244,6 +249,7 @@ class CtrTable:
         torch = self._torch
         n_keys, n_seg = keys.numel(), offsets.numel() - 1
         self.reserve(max(n_keys, 1), n_seg)
+        self._ws_of_live_batch = None
         if pooled_bf16 is None:
             pooled_bf16 = torch.empty((n_seg, self.D), dtype=torch.bfloat16, device=self.device)
         if pooled is None and want_f32:

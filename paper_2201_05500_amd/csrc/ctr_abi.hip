@@ -284,9 +284,20 @@ size_t ctr_table_bytes(const ctr_config* cfg) {
 size_t ctr_workspace_bytes(const ctr_config* cfg, uint64_t max_keys, uint32_t max_segments) {
   (void)max_segments;
   if (!config_ok(cfg) || max_keys >= (1ull << 31)) return 0;
+  // The work geometry (span length, probe tile) is chosen from the size of each batch, and a batch just
+  // below a threshold needs more span partials than one just above it: the answer covers every batch of
+  // at most max_keys occurrences, i.e. the largest layout over max_keys itself and the last size of
+  // every geometry class below it (inside a class the layout only grows with the size).
   WorkLayout L;
   work_layout(cfg->dim, max_keys, &L);
-  return L.total;
+  size_t need = L.total;
+  for (u64 threshold : {(u64)2 << 20, (u64)4 << 20, (u64)8 << 20}) {
+    if (threshold - 1 < max_keys) {
+      work_layout(cfg->dim, threshold - 1, &L);
+      need = std::max(need, L.total);
+    }
+  }
+  return need;
 }
 
 int ctr_table_create(const ctr_config* cfg, void* d_mem, size_t bytes, void* hip_stream, ctr_table** out) {
