@@ -164,6 +164,26 @@ int ctr_lookup_pool(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint
                     uint16_t* d_pooled_bf16, void* d_workspace, size_t workspace_bytes,
                     void* hip_stream);
 
+/* ctr_lookup_pool for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  The two per-occurrence lists
+ * that ctr_lookup_pool keeps in the caller's workspace live in a fixed device array inside the library
+ * instead (CTR_NOALLOC_SCRATCH_BYTES = 32 MiB, held on every GPU that loads the library until the
+ * process ends; its address is looked up per device by ctr_table_create or by the first call).  The
+ * call makes no hipMalloc / hipFree and no allocating library call, records no stage timers, and only
+ * enqueues kernels on `hip_stream`.
+ *   n_keys <= CTR_NOALLOC_MAX_KEYS, else CTR_E_NOMEM (nothing is enqueued)
+ * Arguments, results and the other errors as ctr_lookup_pool; outputs are bit-identical to it.
+ * All calls on one GPU share that GPU's array (also calls on different tables), which keeps the
+ * previous call's lists: each call overwrites the entries of its own n_keys occurrences before
+ * reading them, so nothing has to be cleared, but two calls that overlap in time on one GPU
+ * (different streams without ordering, different threads) race.  A live batch of a pull is not
+ * affected. */
+#define CTR_NOALLOC_MAX_KEYS (1u << 22)
+#define CTR_NOALLOC_SCRATCH_BYTES ((size_t)CTR_NOALLOC_MAX_KEYS * 2u * sizeof(uint32_t))
+int ctr_lookup_pool_noalloc(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint64_t n_keys,
+                            const uint32_t* d_offsets, uint32_t n_segments, float* d_pooled,
+                            uint16_t* d_pooled_bf16, void* hip_stream);
+
 /* Push (Algorithm 1: push_parameters_updates_back; Algorithm 2: the m, v and
  * model lines).  The gradient of sum pooling hands grad_pooled[g, :] to every
  * key occurrence of segment g; per distinct key the occurrences' gradients are

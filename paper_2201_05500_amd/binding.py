@@ -20,11 +20,12 @@ CTR_OK, CTR_E_INVAL, CTR_E_NOMEM, CTR_E_FULL, CTR_E_BADKEY, CTR_E_STATE, CTR_E_D
 CTR_F_KSTEP, CTR_F_ADAGRAD, CTR_F_KSTEP_PROSE, CTR_F_BIAS_CORRECTION = 1, 2, 4, 8
 CTR_STEP_LOCAL, CTR_STEP_MERGE_PENDING = 0, 1
 CTR_N_STAGES = 7
+CTR_NOALLOC_MAX_KEYS = 1 << 22
 STAGE_NAMES = ("probe", "insert", "pool", "sort", "push", "fixup", "merge")
 
 EXPORTED = (
     "ctr_table_bytes", "ctr_workspace_bytes", "ctr_table_create", "ctr_table_destroy",
-    "ctr_pull_pool", "ctr_pull_pool_bf16", "ctr_lookup_pool", "ctr_push_adam", "ctr_push_adam_bf16", "ctr_kstep_merge", "ctr_table_load", "ctr_table_collect", "ctr_table_clear",
+    "ctr_pull_pool", "ctr_pull_pool_bf16", "ctr_lookup_pool", "ctr_lookup_pool_noalloc", "ctr_push_adam", "ctr_push_adam_bf16", "ctr_kstep_merge", "ctr_table_load", "ctr_table_collect", "ctr_table_clear",
     "ctr_table_size", "ctr_table_export",
     "ctr_batch_export", "ctr_batch_stats", "ctr_last_status", "ctr_debug_set_geometry", "ctr_profile_enable",
     "ctr_profile_read",
@@ -76,6 +77,8 @@ def lib():
     L.ctr_debug_set_geometry.argtypes = [vp, u32, u32]
     L.ctr_lookup_pool.restype = ci
     L.ctr_lookup_pool.argtypes = [vp, u32, vp, u64, vp, u32, vp, vp, vp, sz, vp]
+    L.ctr_lookup_pool_noalloc.restype = ci
+    L.ctr_lookup_pool_noalloc.argtypes = [vp, u32, vp, u64, vp, u32, vp, vp, vp]
     L.ctr_table_clear.restype = ci
     L.ctr_table_clear.argtypes = [vp, vp]
     L.ctr_pull_pool_bf16.restype = ci
@@ -141,6 +144,12 @@ def ctr_pull_pool_bf16(table, replica, d_keys, n_keys, d_offsets, n_segments, d_
     st = lib().ctr_pull_pool_bf16(table, replica, d_keys, n_keys, d_offsets, n_segments, d_pooled, d_pooled_bf16,
                                   d_ws, ws_bytes, C.byref(out), stream)
     return st, out.value
+
+
+def ctr_lookup_pool_noalloc(table, replica, d_keys, n_keys, d_offsets, n_segments, d_pooled, d_pooled_bf16,
+                            stream) -> int:
+    return lib().ctr_lookup_pool_noalloc(table, replica, d_keys, n_keys, d_offsets, n_segments, d_pooled,
+                                         d_pooled_bf16, stream)
 
 
 def ctr_push_adam(table, replica, batch, d_grad, mode, stream) -> int:

@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -129,6 +130,35 @@ inline u32 lanes_per_row(u32 D) {
 }
 
 inline u32 blocks_for(u64 threads) { return (u32)((threads + BLOCK - 1) / BLOCK); }
+
+}  // namespace
+
+// Device memory of the entry point that allocates nothing (ctr_lookup_pool_noalloc): a fixed array inside
+// the code object, one copy per GPU that loads the library, alive until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress; the address kernels can use is looked up once per
+// device (with that device current) and kept here.
+static __device__ __align__(256) unsigned char scratch[CTR_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+char* g_scratch_ptr[MAX_DEVICES] = {};
+
+// The current device's copy of `scratch`.  The first call on a device asks the runtime for the address;
+// later calls (also under stream capture) only read the cached pointer.
+int scratch_of_current_device(char** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return CTR_E_DEVICE;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return CTR_E_DEVICE;
+    g_scratch_ptr[dev] = (char*)p;
+  }
+  *out = g_scratch_ptr[dev];
+  return CTR_OK;
+}
 
 }  // namespace
 
@@ -306,6 +336,10 @@ int ctr_table_create(const ctr_config* cfg, void* d_mem, size_t bytes, void* hip
   if (!table_layout(cfg, &L)) return CTR_E_INVAL;
   if (((uintptr_t)d_mem & 255) != 0) return CTR_E_INVAL;
   if (bytes < L.total) return CTR_E_NOMEM;
+  {  // set-up is the place to learn the address of the fixed scratch on this device (ctr_lookup_pool_noalloc)
+    char* unused = nullptr;
+    if (scratch_of_current_device(&unused) != CTR_OK) return CTR_E_DEVICE;
+  }
   ctr_table* t = new (std::nothrow) ctr_table();
   if (!t) return CTR_E_NOMEM;
   t->cfg = *cfg;
@@ -454,24 +488,14 @@ int ctr_pull_pool_bf16(ctr_table* t, uint32_t replica, const uint64_t* d_keys, u
                         workspace_bytes, batch_out, hip_stream);
 }
 
-int ctr_lookup_pool(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint64_t n_keys,
-                    const uint32_t* d_offsets, uint32_t n_segments, float* d_pooled, uint16_t* d_pooled_bf16,
-                    void* d_workspace, size_t workspace_bytes, void* hip_stream) {
-  if (!t || !d_offsets || !d_workspace) return CTR_E_INVAL;
-  if (replica >= t->W) return CTR_E_INVAL;
-  if (n_keys >= (1ull << 31) || n_segments == 0xFFFFFFFFu) return CTR_E_INVAL;
-  if (n_keys > 0 && !d_keys) return CTR_E_INVAL;
-  if (n_segments > 0 && !d_pooled && !d_pooled_bf16) return CTR_E_INVAL;
-  if (((uintptr_t)d_workspace & 255) != 0 || ((uintptr_t)d_pooled_bf16 & 7) != 0) return CTR_E_INVAL;
-  WorkLayout wl;
-  work_layout(t->D, n_keys, &wl, t->force_span, t->force_items);
-  if (workspace_bytes < wl.total) return CTR_E_NOMEM;
-  if (t->has_live && t->cur.ws == (char*)d_workspace) t->has_live = false;  // the live batch's lists are overwritten
-  hipStream_t st = (hipStream_t)hip_stream;
-  char* ws = (char*)d_workspace;
-  u32* occ_row = (u32*)(ws + wl.off_occ_row);
-  u32* seg_of = (u32*)(ws + wl.off_seg_of);
-  const u32 n = (u32)n_keys;
+// Enqueues the lookup-only pooling with its two per-occurrence lists in the given device arrays.
+// `timed`: record the stage timers (they create HIP events on first use, so the entry point that
+// must not allocate passes false).
+static int lookup_pool_enqueue(ctr_table* t, uint32_t replica, const uint64_t* d_keys, u32 n,
+                               const uint32_t* d_offsets, uint32_t n_segments, float* d_pooled, bf16_t* pb,
+                               u32* occ_row, u32* seg_of, bool timed, hipStream_t st) {
+  const bool profile = t->profile;
+  if (!timed) t->profile = false;
   {
     StageTimer tm(t, CTR_STAGE_PROBE, st);
     const u64 work = std::max<u64>(n, (u64)n_segments + 1);
@@ -484,7 +508,6 @@ int ctr_lookup_pool(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint
     const float* vals = t->values + (u64)replica * t->tl.replica_stride;
     const u32 segs_per_block = (BLOCK / t->lpr) * POOL_NS * POOL_ROUNDS;
     const u32 pgrid = (n_segments + segs_per_block - 1) / segs_per_block;
-    bf16_t* pb = (bf16_t*)d_pooled_bf16;
 #define CTR_POOL_LAUNCH(KERNEL) \
   LPR_DISPATCH(t->lpr, KERNEL, pgrid, st, t->hdr, occ_row, seg_of, d_offsets, n_segments, vals, t->D, t->rf, d_pooled, pb)
     if (d_pooled && pb) {
@@ -496,7 +519,52 @@ int ctr_lookup_pool(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint
     }
 #undef CTR_POOL_LAUNCH
   }
+  t->profile = profile;
   return launch_status();
+}
+
+static int lookup_pool_args_ok(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint64_t n_keys,
+                               const uint32_t* d_offsets, uint32_t n_segments, float* d_pooled,
+                               uint16_t* d_pooled_bf16) {
+  if (!t || !d_offsets) return CTR_E_INVAL;
+  if (replica >= t->W) return CTR_E_INVAL;
+  if (n_keys >= (1ull << 31) || n_segments == 0xFFFFFFFFu) return CTR_E_INVAL;
+  if (n_keys > 0 && !d_keys) return CTR_E_INVAL;
+  if (n_segments > 0 && !d_pooled && !d_pooled_bf16) return CTR_E_INVAL;
+  if (((uintptr_t)d_pooled_bf16 & 7) != 0) return CTR_E_INVAL;
+  return CTR_OK;
+}
+
+int ctr_lookup_pool(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint64_t n_keys,
+                    const uint32_t* d_offsets, uint32_t n_segments, float* d_pooled, uint16_t* d_pooled_bf16,
+                    void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  const int rc = lookup_pool_args_ok(t, replica, d_keys, n_keys, d_offsets, n_segments, d_pooled, d_pooled_bf16);
+  if (rc != CTR_OK) return rc;
+  if (!d_workspace || ((uintptr_t)d_workspace & 255) != 0) return CTR_E_INVAL;
+  WorkLayout wl;
+  work_layout(t->D, n_keys, &wl, t->force_span, t->force_items);
+  if (workspace_bytes < wl.total) return CTR_E_NOMEM;
+  if (t->has_live && t->cur.ws == (char*)d_workspace) t->has_live = false;  // the live batch's lists are overwritten
+  char* ws = (char*)d_workspace;
+  return lookup_pool_enqueue(t, replica, d_keys, (u32)n_keys, d_offsets, n_segments, d_pooled,
+                             (bf16_t*)d_pooled_bf16, (u32*)(ws + wl.off_occ_row), (u32*)(ws + wl.off_seg_of), true,
+                             (hipStream_t)hip_stream);
+}
+
+int ctr_lookup_pool_noalloc(ctr_table* t, uint32_t replica, const uint64_t* d_keys, uint64_t n_keys,
+                            const uint32_t* d_offsets, uint32_t n_segments, float* d_pooled,
+                            uint16_t* d_pooled_bf16, void* hip_stream) {
+  const int rc = lookup_pool_args_ok(t, replica, d_keys, n_keys, d_offsets, n_segments, d_pooled, d_pooled_bf16);
+  if (rc != CTR_OK) return rc;
+  if (n_keys > CTR_NOALLOC_MAX_KEYS) return CTR_E_NOMEM;  // the fixed scratch holds two lists of that many entries
+  char* base = nullptr;
+  if (scratch_of_current_device(&base) != CTR_OK) return CTR_E_DEVICE;
+  // layout of the scratch: occ_row[CTR_NOALLOC_MAX_KEYS] | seg_of[CTR_NOALLOC_MAX_KEYS]; both lists are
+  // written in full for the n_keys occurrences of the call before they are read, so nothing needs clearing
+  u32* occ_row = (u32*)base;
+  u32* seg_of = (u32*)(base + (size_t)CTR_NOALLOC_MAX_KEYS * sizeof(u32));
+  return lookup_pool_enqueue(t, replica, d_keys, (u32)n_keys, d_offsets, n_segments, d_pooled,
+                             (bf16_t*)d_pooled_bf16, occ_row, seg_of, false, (hipStream_t)hip_stream);
 }
 
 // grad_bf16: d_grad_pooled points at bf16 rows instead of fp32 rows
