@@ -24,12 +24,28 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix-core rate
 
-# HBM traffic of the dominant kernel per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
-# this script (profiles/large_step_kernels.txt), each counter scaled by what it reads for a 1 GiB
-# device copy in the same run (fetch x2.0, write x1.0).  Only known for the workload it was taken on.
-MEASURED_TRAFFIC_BYTES = {("large", "k_push_span"): 7454869 * 1024 * 2.0 + 4454775 * 1024 * 1.0}
-# the same counters summed over every library kernel of one step (the last of that run)
-MEASURED_STEP_TRAFFIC_BYTES = {"large": 12563482 * 1024 * 2.0 + 8621401 * 1024 * 1.0}
+KERNEL_OF_STAGE = {"push": "k_push_span", "pool": "k_pool", "merge": "k_merge"}
+
+
+def measured_traffic(workload):
+    """HBM traffic per launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs whose figures are committed as
+    profiles/<workload>_step_traffic.json (written by paper_2201_05500_amd/profile_summary.py from the counter
+    output, each counter scaled by what it reads for a copy of known size in the same run).  Returns
+    (per-kernel bytes, whole-step bytes, provenance) or ({}, None, None) when there is no such file.  The
+    provenance says at which commit and source hash the counters were taken and whether the sources the
+    library was built from still hash the same."""
+    path = os.path.join(ROOT, "profiles", "%s_step_traffic.json" % workload)
+    if not os.path.exists(path):
+        return {}, None, None
+    from paper_2201_05500_amd.build import source_hash
+    with open(path) as f:
+        rec = json.load(f)
+    fs, wsf = rec["scale"]["fetch"], rec["scale"]["write"]
+    per = {k: v["fetch_KiB"] * 1024 * fs + v["write_KiB"] * 1024 * wsf for k, v in rec["kernels"].items()}
+    step = rec["step"]["fetch_KiB"] * 1024 * fs + rec["step"]["write_KiB"] * 1024 * wsf
+    prov = {"file": "profiles/%s_step_traffic.json" % workload, "commit": rec.get("commit"),
+            "source_hash": rec.get("source_hash"), "matches_current_sources": rec.get("source_hash") == source_hash()}
+    return per, step, prov
 
 
 def algorithmic_bytes_step(L, G, U, n_new, D, kstep, n_state=3, grad_bytes=4):
@@ -56,6 +72,40 @@ def algorithmic_bytes_push_kernel(L, G, U, D, kstep, n_state=3, grad_bytes=4):
 def algorithmic_bytes_pool_kernel(L, G, U, D, out_bytes=4):
     """The pool kernel's share: offsets and occurrence map read, compulsory row reads, pooled write."""
     return 4 * (G + 1) + 4 * L + 4 * D * U + out_bytes * D * G
+
+
+def algorithmic_bytes_merge_kernel(rows_merged, pending_pairs, n_rows, D, W, shared_den):
+    """One k-step merge: the state word of every row in use; per merged row the second moment and the model of
+    every replica read, the model of every replica written, the shared denominator written (Algorithm 2 as
+    printed) or every replica's second moment written (prose reading); the first moment of the (row, replica)
+    pairs whose last step is applied inside the merge."""
+    per_row = (2 * W + W + (1 if shared_den else W)) * 4 * D
+    return 4 * n_rows + rows_merged * per_row + pending_pairs * 4 * D
+
+
+def copy_ceiling(torch, dev, nbytes=1 << 30, reps=5):
+    """GB/s (read + write) of the library's streaming copy kernel on nbytes, best of the plain and the
+    non-temporal form: the practical rate of this GPU's memory system, measured in this run."""
+    from paper_2201_05500_amd.binding import CTR_OK, ctr_stream_copy
+    src = torch.ones(nbytes // 4, dtype=torch.float32, device=dev)
+    dst = torch.empty_like(src)
+    stream = int(torch.cuda.current_stream(dev).cuda_stream)
+    best, which = 0.0, None
+    for nt in (0, 1):
+        for r in range(reps + 1):                                  # the first one warms up
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            if ctr_stream_copy(dst.data_ptr(), src.data_ptr(), nbytes, nt, stream) != CTR_OK:
+                raise RuntimeError("ctr_stream_copy failed")
+            e1.record()
+            torch.cuda.synchronize()
+            rate = 2 * nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
+            if r and rate > best:
+                best, which = rate, "non-temporal" if nt else "plain"
+    if not bool((dst[:: 1 << 16] == 1).all()):
+        raise RuntimeError("ctr_stream_copy copied wrongly")
+    del src, dst
+    return best, which
 
 
 def tower_flops(batch, in_dim, hidden):
@@ -221,8 +271,6 @@ def main():
     ap.add_argument("--seam", action="store_true",
                     help="time the working-set seam instead of training steps: ctr_table_load of every row of the "
                          "workload's table, ctr_table_collect of the same keys, ctr_table_clear (one cycle per step)")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one 1 GiB device copy, so that a counter run has a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one shard of the parameter server); "
@@ -296,13 +344,6 @@ def main():
         loss = torch.empty(1, dtype=torch.float32, device=dev)
         tower_events = []
     torch.cuda.synchronize()
-    if args.calibrate_copy:
-        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-
     def predict_step(s):
         b = batches[s]
         st, _ = table.lookup_pool(0, b["keys"], b["offsets"], out=pooled_bf16)
@@ -348,6 +389,8 @@ def main():
             if st != CTR_OK:
                 raise RuntimeError("ctr_kstep_merge: %d" % st)
 
+    ceiling_GBps, ceiling_kind = copy_ceiling(torch, dev)   # same run, before the timed region
+
     table.profile_enable(True)
     for s in range(Wm):
         run_step(s)
@@ -358,16 +401,23 @@ def main():
     if full:
         tower_events.clear()
     rows_before = table.n_rows
+    merged_before = table.merge_stats() if kstep else (0, 0)
 
+    step_marks = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(Wm, total_steps):
+        step_marks[s - Wm].record()
         if args.predict:
             predict_step(s)
         else:
             run_step(s)
+    step_marks[K].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    step_ms = sorted(step_marks[i].elapsed_time(step_marks[i + 1]) for i in range(K))
+    steady = sorted(step_marks[i].elapsed_time(step_marks[i + 1]) for i in range(K // 5, K))   # the last 80 %
+    median = lambda v: 0.5 * (v[(len(v) - 1) // 2] + v[len(v) // 2])
 
     stages = table.profile_read()              # HIP events recorded on the launch stream, timed steps only
     status = table.last_status()
@@ -392,8 +442,18 @@ def main():
         "push": algorithmic_bytes_push_kernel(L_mean, G, U_mean, D, shared_den, n_state, gb),
         "pool": algorithmic_bytes_pool_kernel(L_mean, G, U_mean, D, 2 if full else 4),
     }
+    n_merges = stages["merge"][1]
+    if kstep and n_merges:
+        merged_after = table.merge_stats()
+        rows_merged = (merged_after[0] - merged_before[0]) / n_merges
+        pending_pairs = (merged_after[1] - merged_before[1]) / n_merges
+        kernel_bytes["merge"] = algorithmic_bytes_merge_kernel(rows_merged, pending_pairs, rows_after, D,
+                                                               w.n_replicas, shared_den)
+    # the dominant kernel: the one whose single launch takes longest (stage times are per launch)
     dominant = max(kernel_bytes, key=lambda n: stage_ms[n])
     achieved = kernel_bytes[dominant] / (stage_ms[dominant] * 1e-3) / 1e9 if stage_ms[dominant] else 0.0
+    standard = args.variant == "alg2" and not args.grad_bf16 and not full
+    traffic_kernel, traffic_step, traffic_prov = measured_traffic(w.name) if standard else ({}, None, None)
 
     out = {
         "metric": "pulled+updated keys/sec per step and achieved HBM GB/s vs peak (1 GPU)",
@@ -403,6 +463,8 @@ def main():
         "steps": K,
         "warmup": Wm,
         "ms_per_step": ms_step,
+        "ms_per_step_median": median(step_ms),
+        "ms_per_step_median_last_80pct": median(steady),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -422,21 +484,33 @@ def main():
         "rows_per_s": U_mean * K * reps / elapsed,
         "step_algorithmic_GBps": step_bytes * reps / (ms_step * 1e-3) / 1e9,
         "step_frac_of_hbm_peak": step_bytes * reps / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-        "step_counter_traffic_GBps": (MEASURED_STEP_TRAFFIC_BYTES[w.name] / (ms_step * 1e-3) / 1e9
-                                      if (w.name in MEASURED_STEP_TRAFFIC_BYTES and args.variant == "alg2" and not args.grad_bf16)
-                                      else None),
+        "copy_ceiling_GBps": ceiling_GBps,
+        "copy_ceiling_kernel": "ctr_stream_copy (%s), 1 GiB, best of 5, timed in this run" % ceiling_kind,
+        "step_frac_of_copy_ceiling": step_bytes * reps / (ms_step * 1e-3) / 1e9 / ceiling_GBps,
+        "step_counter_traffic_GBps": traffic_step / (ms_step * 1e-3) / 1e9 if traffic_step else None,
         "stage_ms": stage_ms,
+        "stage_launches_per_step": {n: c / K for n, (ms, c) in stages.items()},
         "roofline": {
             "bound": "hbm",
-            "kernel": {"push": "k_push_span", "pool": "k_pool"}[dominant],
+            "kernel": KERNEL_OF_STAGE[dominant],
             "achieved": achieved,
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBPS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, {"push": "k_push_span", "pool": "k_pool"}[dominant]))
-            if (args.variant == "alg2" and not args.grad_bf16) else None,
+            "frac_of_copy_ceiling": achieved / ceiling_GBps,
+            "algorithmic_bytes_per_launch": kernel_bytes[dominant],
+            "traffic": traffic_kernel.get(KERNEL_OF_STAGE[dominant]),
+            "traffic_source": traffic_prov,
         },
     }
+    # every kernel with a byte model, not only the dominant one
+    out["kernel_rooflines"] = {
+        KERNEL_OF_STAGE[n]: {"ms_per_launch": stage_ms[n], "algorithmic_bytes_per_launch": kernel_bytes[n],
+                             "achieved_GBps": kernel_bytes[n] / (stage_ms[n] * 1e-3) / 1e9,
+                             "frac": kernel_bytes[n] / (stage_ms[n] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                             "frac_of_copy_ceiling": kernel_bytes[n] / (stage_ms[n] * 1e-3) / 1e9 / ceiling_GBps,
+                             "traffic": traffic_kernel.get(KERNEL_OF_STAGE[n])}
+        for n in kernel_bytes if stage_ms[n]}
     if full:
         tower_ms = sum(a.elapsed_time(b) for a, b in tower_events) / len(tower_events)
         fl = tower_flops(w.batch, in_dim, WL.FULL_STEP_HIDDEN)

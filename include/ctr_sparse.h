@@ -271,6 +271,19 @@ int ctr_batch_export(ctr_table* t, ctr_batch* batch, uint64_t* n_unique, uint64_
  * the push) and rows created by the pull. */
 int ctr_batch_stats(ctr_table* t, uint64_t* n_unique, uint64_t* n_new, void* hip_stream);
 
+/* Rows averaged by all ctr_kstep_merge calls on this table so far (a merge covers the rows touched
+ * by any replica since the merge before; Algorithm 2, global-averaging branch) and, in
+ * *pending_applied (may be NULL), the number of (row, replica) pairs whose deferred k-th step those
+ * merges applied: the unit counts of the merge's byte accounting.  Reset by ctr_table_clear. */
+int ctr_merge_stats(ctr_table* t, uint64_t* rows_merged, uint64_t* pending_applied, void* hip_stream);
+
+/* Measurement aid, no part of the method: enqueues a plain streaming copy of `bytes` bytes (a multiple
+ * of 16; both pointers device, 16-byte aligned, not overlapping) with the library's own copy kernel,
+ * so that a benchmark can report the kernels' rates against this GPU's practical copy rate measured
+ * in the same run, beside the published peak.  non_temporal != 0 uses streaming loads and stores.
+ * Errors: CTR_E_INVAL. */
+int ctr_stream_copy(void* d_dst, const void* d_src, size_t bytes, int non_temporal, void* hip_stream);
+
 /* Returns the deferred device status (a ctr_status) and clears it. */
 int ctr_last_status(ctr_table* t, void* hip_stream);
 

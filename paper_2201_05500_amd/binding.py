@@ -14,7 +14,9 @@ from typing import Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libctr_sparse.so")
+# CTR_SPARSE_LIB: another build of the same library (a compile-time variant made by build.py --define ... --out),
+# for A/B measurements; it must exist, like the in-tree one
+LIB_PATH = os.environ.get("CTR_SPARSE_LIB") or os.path.join(_HERE, "libctr_sparse.so")
 
 CTR_OK, CTR_E_INVAL, CTR_E_NOMEM, CTR_E_FULL, CTR_E_BADKEY, CTR_E_STATE, CTR_E_DEVICE = range(7)
 CTR_F_KSTEP, CTR_F_ADAGRAD, CTR_F_KSTEP_PROSE, CTR_F_BIAS_CORRECTION = 1, 2, 4, 8
@@ -27,7 +29,7 @@ EXPORTED = (
     "ctr_table_bytes", "ctr_workspace_bytes", "ctr_table_create", "ctr_table_destroy",
     "ctr_pull_pool", "ctr_pull_pool_bf16", "ctr_lookup_pool", "ctr_lookup_pool_noalloc", "ctr_push_adam", "ctr_push_adam_bf16", "ctr_kstep_merge", "ctr_table_load", "ctr_table_collect", "ctr_table_clear",
     "ctr_table_size", "ctr_table_export",
-    "ctr_batch_export", "ctr_batch_stats", "ctr_last_status", "ctr_debug_set_geometry", "ctr_profile_enable",
+    "ctr_batch_export", "ctr_batch_stats", "ctr_merge_stats", "ctr_stream_copy", "ctr_last_status", "ctr_debug_set_geometry", "ctr_profile_enable",
     "ctr_profile_read",
 )
 
@@ -103,6 +105,10 @@ def lib():
     L.ctr_batch_stats.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), vp]
     L.ctr_last_status.restype = ci
     L.ctr_last_status.argtypes = [vp, vp]
+    L.ctr_merge_stats.restype = ci
+    L.ctr_merge_stats.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), vp]
+    L.ctr_stream_copy.restype = ci
+    L.ctr_stream_copy.argtypes = [vp, vp, sz, ci, vp]
     L.ctr_profile_enable.restype = ci
     L.ctr_profile_enable.argtypes = [vp, ci]
     L.ctr_profile_read.restype = ci
@@ -166,6 +172,10 @@ def ctr_table_load(table, d_keys, n_keys, d_x, d_m, d_v, d_ws, ws_bytes, stream)
 
 def ctr_table_collect(table, replica, d_keys, n_keys, d_x, d_m, d_v, d_found, stream) -> int:
     return lib().ctr_table_collect(table, replica, d_keys, n_keys, d_x, d_m, d_v, d_found, stream)
+
+
+def ctr_stream_copy(d_dst, d_src, nbytes, non_temporal, stream) -> int:
+    return lib().ctr_stream_copy(d_dst, d_src, nbytes, 1 if non_temporal else 0, stream)
 
 
 def ctr_last_status(table, stream) -> int:
@@ -337,6 +347,14 @@ class CtrTable:
         if st != CTR_OK:
             raise RuntimeError("ctr_batch_stats: %d" % st)
         return int(u.value), int(n.value)
+
+    def merge_stats(self):
+        """(rows merged, pending (row, replica) steps applied) by all merges so far."""
+        n, q = C.c_uint64(), C.c_uint64()
+        st = lib().ctr_merge_stats(self._handle, C.byref(n), C.byref(q), self.stream)
+        if st != CTR_OK:
+            raise RuntimeError("ctr_merge_stats: %d" % st)
+        return int(n.value), int(q.value)
 
     def batch_export(self, batch, n_keys):
         nu = C.c_uint64()

@@ -21,6 +21,28 @@ def sources():
     return [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC)) if f.endswith(".hip")]
 
 
+def source_hash() -> str:
+    """Short hash of every kernel and host source of the library: ties a measurement to the code it was taken on."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(CSRC)):
+        if name.endswith((".hip", ".h")):
+            with open(os.path.join(CSRC, name), "rb") as f:
+                h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
+
+
+def build_variant(out: str, defines, verbose: bool = False) -> str:
+    """The library alone, with extra -D switches, written to `out` (for A/B measurements of the compile-time
+    variants the kernels' headers document; load it with CTR_SPARSE_LIB=<out>)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc] + HIPCC_FLAGS + ["-D" + d for d in defines] + ["-o", out] + sources() + ["-lrocblas", "-lhipblaslt"]
+    if verbose:
+        print(" ".join(cmd))
+    subprocess.check_call(cmd)
+    return out
+
+
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB] + sources() + ["-lrocblas", "-lhipblaslt"]  # bf16 GEMMs of the dense tower
@@ -39,4 +61,9 @@ def build(verbose: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import argparse
+    ap = argparse.ArgumentParser(description="build libctr_sparse.so, or a variant of it with extra defines")
+    ap.add_argument("--define", "-D", action="append", default=[], help="NAME=VALUE, repeatable")
+    ap.add_argument("--out", help="write a variant build here instead of building the in-tree library")
+    a = ap.parse_args()
+    print(build_variant(a.out, a.define, verbose=True) if a.out else build(verbose=True))

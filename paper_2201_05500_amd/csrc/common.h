@@ -37,8 +37,13 @@ struct DevHeader {
   u32 n_rows_base;  // n_rows before the pull in flight
   u32 n_new;        // rows created by the last pull
   u32 n_unique;     // distinct keys of the last pushed batch
-  u32 pad[57];
+  u32 n_push;       // pushes accepted so far: the step count t of the bias-corrected row update
+  double bc1, bc2;  // 1 / (1 - beta1^t), 1 / (1 - beta2^t) of the push in flight (bias-corrected form only)
+  u64 rows_merged;  // rows averaged by all k-step merges so far (those touched since the merge before)
+  u64 merge_pending;  // (row, replica) pairs whose deferred model step those merges applied
+  u32 pad[48];
 };
+constexpr int HDR_WORD_N_PUSH = 7;  // index of n_push among the header's 32-bit words
 static_assert(sizeof(DevHeader) == 256, "header is one 256-byte block");
 
 // 64-bit finalizer of MurmurHash3 (public domain): slot choice in the key index.
@@ -111,6 +116,17 @@ struct d4 {
 
 __device__ __forceinline__ f4 ldg4(const float* p) { return *reinterpret_cast<const f4*>(p); }
 __device__ __forceinline__ void stg4(float* p, f4 v) { *reinterpret_cast<f4*>(p) = v; }
+
+// Streaming variants for data that is used once: the access carries the non-temporal hint, so the
+// line is not kept in the caches at the expense of data that will be used again.
+typedef float vf4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ f4 ldg4_stream(const float* p) {
+  const vf4 v = __builtin_nontemporal_load(reinterpret_cast<const vf4*>(p));
+  return f4{v.x, v.y, v.z, v.w};
+}
+__device__ __forceinline__ void stg4_stream(float* p, f4 v) {
+  __builtin_nontemporal_store(vf4{v.x, v.y, v.z, v.w}, reinterpret_cast<vf4*>(p));
+}
 
 // bfloat16 as its 16-bit pattern; rounding from fp32 is nearest-even on the bit pattern.
 typedef uint16_t bf16_t;

@@ -1,5 +1,6 @@
 // Host side of the C ABI declared in include/ctr_sparse.h: argument checks, memory layout,
-// kernel launches.  No arithmetic of the method happens on the host.
+// kernel launches.  No arithmetic of the method happens on the host (hyper-parameters are
+// promoted to binary64 and complemented here, nothing else).
 #include "../../include/ctr_sparse.h"
 
 #include <algorithm>
@@ -177,7 +178,6 @@ struct ctr_table {
   TableLayout tl;
   u32 D, W, lpr, row_bits, rf;  // rf: floats per row
   u64 R;
-  u64 n_push;  // pushes so far (the step count t of the bias-corrected form)
   char* mem;
   DevHeader* hdr;
   Slot* slots;
@@ -350,7 +350,6 @@ int ctr_table_create(const ctr_config* cfg, void* d_mem, size_t bytes, void* hip
   t->R = cfg->capacity_rows;
   t->lpr = lanes_per_row(t->D);
   t->rf = ((cfg->flags & CTR_F_ADAGRAD) ? 2u : 3u) * t->D;
-  t->n_push = 0;
   t->row_bits = 1;
   while ((1ull << t->row_bits) < t->R) ++t->row_bits;
   t->mem = (char*)d_mem;
@@ -371,7 +370,7 @@ int ctr_table_create(const ctr_config* cfg, void* d_mem, size_t bytes, void* hip
   const u64 work = std::max<u64>(L.n_slots, t->R);
   const u32 grid = (u32)std::min<u64>((work + BLOCK - 1) / BLOCK, 8192);
   hipLaunchKernelGGL(k_table_clear, dim3(grid), dim3(BLOCK), 0, st, t->hdr, t->slots, L.n_slots, t->row_state,
-                     t->R);
+                     t->R, 0u);
   if (launch_status() != CTR_OK) {
     delete t;
     return CTR_E_DEVICE;
@@ -585,7 +584,8 @@ static int push_adam_impl(ctr_table* t, uint32_t replica, ctr_batch* handle, con
   hipStream_t st = (hipStream_t)hip_stream;
   const WorkLayout& wl = batch->wl;
   const u32 n = batch->n_keys;
-  ++t->n_push;
+  if (flags & CTR_F_BIAS_CORRECTION)  // the step count lives on the device: an empty batch counts, a refused one does not
+    hipLaunchKernelGGL(k_push_begin, dim3(1), dim3(WAVE), 0, st, t->hdr, (double)t->cfg.beta1, (double)t->cfg.beta2);
   if (n > 0) {
     AdamParams P;
     P.b1 = (double)t->cfg.beta1;
@@ -593,8 +593,7 @@ static int push_adam_impl(ctr_table* t, uint32_t replica, ctr_batch* handle, con
     P.b2 = (double)t->cfg.beta2;
     P.omb2 = 1.0 - P.b2;
     P.eps = (double)t->cfg.eps;
-    P.bc1 = 1.0 / (1.0 - std::pow(P.b1, (double)t->n_push));
-    P.bc2 = 1.0 / (1.0 - std::pow(P.b2, (double)t->n_push));
+    P.bc1 = P.bc2 = 1.0;  // the bias-corrected update reads its factors from the device header
     P.lr = t->cfg.lr;
     P.kstep = kstep ? 1u : 0u;
     P.mode = (mode == CTR_STEP_MERGE_PENDING) ? 2u : 0u;
@@ -713,7 +712,7 @@ int ctr_table_clear(ctr_table* t, void* hip_stream) {
   const u64 work = std::max<u64>(t->tl.n_slots, t->R);
   const u32 grid = (u32)std::min<u64>((work + BLOCK - 1) / BLOCK, 8192);
   hipLaunchKernelGGL(k_table_clear, dim3(grid), dim3(BLOCK), 0, st, t->hdr, t->slots, t->tl.n_slots, t->row_state,
-                     t->R);
+                     t->R, 1u);
   return launch_status();
 }
 
@@ -840,6 +839,30 @@ int ctr_batch_stats(ctr_table* t, uint64_t* n_unique, uint64_t* n_new, void* hip
   if (n_unique) *n_unique = h.n_unique;
   if (n_new) *n_new = h.n_new;
   return CTR_OK;
+}
+
+int ctr_merge_stats(ctr_table* t, uint64_t* rows_merged, uint64_t* pending_applied, void* hip_stream) {
+  if (!t || !rows_merged) return CTR_E_INVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  DevHeader h;
+  if (hipMemcpyAsync(&h, t->hdr, sizeof(h), hipMemcpyDeviceToHost, st) != hipSuccess) return CTR_E_DEVICE;
+  if (hipStreamSynchronize(st) != hipSuccess) return CTR_E_DEVICE;
+  *rows_merged = h.rows_merged;
+  if (pending_applied) *pending_applied = h.merge_pending;
+  return CTR_OK;
+}
+
+int ctr_stream_copy(void* d_dst, const void* d_src, size_t bytes, int non_temporal, void* hip_stream) {
+  if (!d_dst || !d_src || bytes == 0 || (bytes & 15) != 0) return CTR_E_INVAL;
+  if ((((uintptr_t)d_dst | (uintptr_t)d_src) & 15) != 0) return CTR_E_INVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const u64 n16 = bytes / 16;
+  const u32 grid = (u32)std::min<u64>((n16 + BLOCK - 1) / BLOCK, 256 * 16);  // 16 blocks per compute unit
+  if (non_temporal)
+    hipLaunchKernelGGL(k_stream_copy<true>, dim3(grid), dim3(BLOCK), 0, st, (const vf4*)d_src, (vf4*)d_dst, n16);
+  else
+    hipLaunchKernelGGL(k_stream_copy<false>, dim3(grid), dim3(BLOCK), 0, st, (const vf4*)d_src, (vf4*)d_dst, n16);
+  return launch_status();
 }
 
 int ctr_last_status(ctr_table* t, void* hip_stream) {

@@ -28,6 +28,19 @@ constexpr u32 NO_ROW = 0xFFFFFFFFu;
 #ifndef CTR_PUSH_PB
 #define CTR_PUSH_PB 2  // occurrences per batch of the span walk (2: 71 VGPRs, 7 waves/SIMD; measured best)
 #endif
+// cache hints of the span walk's three traffic classes (0 = plain access, 1 = non-temporal)
+#ifndef CTR_PUSH_NT_GRAD
+#define CTR_PUSH_NT_GRAD 0
+#endif
+#ifndef CTR_PUSH_NT_ROW_LD
+#define CTR_PUSH_NT_ROW_LD 1
+#endif
+#ifndef CTR_PUSH_NT_ROW_ST
+#define CTR_PUSH_NT_ROW_ST 1
+#endif
+#ifndef CTR_MERGE_MB
+#define CTR_MERGE_MB 8  // replicas whose loads the merge issues together
+#endif
 #ifndef CTR_PUSH_MIN_WAVES
 #define CTR_PUSH_MIN_WAVES 1  // waves per SIMD the span kernel is compiled for
 #endif
@@ -44,7 +57,8 @@ enum StepKind : int {
 
 struct AdamParams {
   double b1, omb1, b2, omb2;  // beta and (1 - beta) promoted from binary32
-  double bc1, bc2, eps;       // STEP_ADAM_KINGMA: 1/(1 - beta1^t), 1/(1 - beta2^t), epsilon
+  double bc1, bc2, eps;       // STEP_ADAM_KINGMA: 1/(1 - beta1^t), 1/(1 - beta2^t) (filled in on the device from
+                              // the header), epsilon
   float lr;
   u32 mode;      // 0: moments and model   2: moments only (merge pending)
   u32 kstep;     // maintain the per-row state word
@@ -55,18 +69,33 @@ struct RowState4 {
   f4 x, m, v, den;  // v doubles as AdaGrad's accumulator; den: shared denominator (STEP_ADAM_SHARED only)
 };
 
+__device__ __forceinline__ f4 row_ld4(const float* p) {
+#if CTR_PUSH_NT_ROW_LD
+  return ldg4_stream(p);
+#else
+  return ldg4(p);
+#endif
+}
+__device__ __forceinline__ void row_st4(float* p, f4 v) {
+#if CTR_PUSH_NT_ROW_ST
+  stg4_stream(p, v);
+#else
+  stg4(p, v);
+#endif
+}
+
 // rf = floats per row: 3*D for [x | m | v], 2*D for AdaGrad's [x | G].
 template <int KIND>
 __device__ __forceinline__ RowState4 load_row4(const float* __restrict__ values, const float* __restrict__ vhat,
                                                u32 row, u32 D, u32 rf, u32 c) {
   RowState4 s;
   const float* px = values + (u64)row * rf + 4 * c;
-  s.x = ldg4(px);
+  s.x = row_ld4(px);
   if constexpr (KIND == STEP_ADAGRAD) {
-    s.v = ldg4(px + D);
+    s.v = row_ld4(px + D);
   } else {
-    s.m = ldg4(px + D);
-    s.v = ldg4(px + 2 * D);
+    s.m = row_ld4(px + D);
+    s.v = row_ld4(px + 2 * D);
   }
   if constexpr (KIND == STEP_ADAM_SHARED) s.den = ldg4(vhat + (u64)row * D + 4 * c);
   return s;
@@ -94,12 +123,12 @@ __device__ __forceinline__ void row_apply4(RowState4 s, float* __restrict__ row_
     v.y = (float)((double)v.y + g.y * g.y);
     v.z = (float)((double)v.z + g.z * g.z);
     v.w = (float)((double)v.w + g.w * g.w);
-    stg4(px + D, v);
+    row_st4(px + D, v);
     x.x = (float)((double)x.x - lr * g.x * rsqrt_refined(v.x));
     x.y = (float)((double)x.y - lr * g.y * rsqrt_refined(v.y));
     x.z = (float)((double)x.z - lr * g.z * rsqrt_refined(v.z));
     x.w = (float)((double)x.w - lr * g.w * rsqrt_refined(v.w));
-    stg4(px, x);
+    row_st4(px, x);
     return;
   }
   m.x = (float)(P.b1 * (double)m.x + P.omb1 * g.x);
@@ -110,14 +139,14 @@ __device__ __forceinline__ void row_apply4(RowState4 s, float* __restrict__ row_
   v.y = (float)(P.b2 * (double)v.y + P.omb2 * (g.y * g.y));
   v.z = (float)(P.b2 * (double)v.z + P.omb2 * (g.z * g.z));
   v.w = (float)(P.b2 * (double)v.w + P.omb2 * (g.w * g.w));
-  stg4(px + D, m);
-  stg4(px + 2 * D, v);
+  row_st4(px + D, m);
+  row_st4(px + 2 * D, v);
   if constexpr (KIND == STEP_ADAM_KINGMA) {
     x.x = (float)((double)x.x - lr * ((double)m.x * P.bc1) / (sqrt((double)v.x * P.bc2) + P.eps));
     x.y = (float)((double)x.y - lr * ((double)m.y * P.bc1) / (sqrt((double)v.y * P.bc2) + P.eps));
     x.z = (float)((double)x.z - lr * ((double)m.z * P.bc1) / (sqrt((double)v.z * P.bc2) + P.eps));
     x.w = (float)((double)x.w - lr * ((double)m.w * P.bc1) / (sqrt((double)v.w * P.bc2) + P.eps));
-    stg4(px, x);
+    row_st4(px, x);
   } else if (P.mode != 2u) {
     f4 den = v;
     if constexpr (KIND == STEP_ADAM_SHARED) den = s.den;
@@ -125,7 +154,7 @@ __device__ __forceinline__ void row_apply4(RowState4 s, float* __restrict__ row_
     x.y = (float)((double)x.y - lr * (double)m.y * rsqrt_refined(den.y));
     x.z = (float)((double)x.z - lr * (double)m.z * rsqrt_refined(den.z));
     x.w = (float)((double)x.w - lr * (double)m.w * rsqrt_refined(den.w));
-    stg4(px, x);
+    row_st4(px, x);
   }
 }
 
@@ -147,6 +176,16 @@ __device__ __forceinline__ void add_partial(const double* __restrict__ part, u32
   a.x += p[0]; a.y += p[1]; a.z += p[2]; a.w += p[3];
 }
 
+// First launch of a push under the bias-corrected update: counts the push (only if the table accepts it:
+// while a deferred error is pending every push is a no-op and must not advance the step count) and
+// leaves the two correction factors of step t in the header for the row-update launches that follow.
+__global__ void k_push_begin(DevHeader* hdr, double b1, double b2) {
+  if (threadIdx.x != 0 || blockIdx.x != 0 || hdr->status) return;
+  const u32 t = ++hdr->n_push;
+  hdr->bc1 = 1.0 / (1.0 - pow(b1, (double)t));
+  hdr->bc2 = 1.0 / (1.0 - pow(b2, (double)t));
+}
+
 // Span walk.  Each batch of PB occurrences issues, before anything is consumed,
 // the PB gradient-row loads and the x/m/v loads of every row that ends inside
 // the batch, so that a group keeps several KB in flight instead of one
@@ -157,10 +196,15 @@ __device__ __forceinline__ void push_span_body(const DevHeader* hdr, const u32* 
                                                const u32* __restrict__ ss, u32 n, u32 span,
                                                const void* __restrict__ grad_any, float* __restrict__ values,
                                                const float* __restrict__ vhat, u32* __restrict__ row_state, u32 D,
-                                               u32 rf, const AdamParams& P, double* __restrict__ head_part,
+                                               u32 rf, const AdamParams& P_in, double* __restrict__ head_part,
                                                double* __restrict__ tail_part, u32* __restrict__ span_flags,
                                                u32* __restrict__ span_rows) {
   if (hdr->status) return;
+  AdamParams P = P_in;
+  if constexpr (KIND == STEP_ADAM_KINGMA) {
+    P.bc1 = hdr->bc1;
+    P.bc2 = hdr->bc2;
+  }
   constexpr int PB = CTR_PUSH_PB;
   const u32 s = (blockIdx.x * BLOCK + threadIdx.x) / LPR;
   const u32 c = threadIdx.x % LPR;
@@ -228,7 +272,11 @@ __device__ __forceinline__ void push_span_body(const DevHeader* hdr, const u32* 
           gv[i].z = __uint_as_float(raw.y << 16);
           gv[i].w = __uint_as_float(raw.y & 0xFFFF0000u);
         } else {
+#if CTR_PUSH_NT_GRAD
+          gv[i] = ldg4_stream(static_cast<const float*>(grad_any) + (u64)g[i] * D + 4 * c);
+#else
           gv[i] = ldg4(static_cast<const float*>(grad_any) + (u64)g[i] * D + 4 * c);
+#endif
         }
       }
     }
@@ -348,11 +396,16 @@ template <int LPR, int KIND>
 __device__ __forceinline__ void push_fixup_body(const DevHeader* hdr, const u32* __restrict__ sr, u32 n, u32 n_spans,
                                                 u32 span, float* __restrict__ values,
                                                 const float* __restrict__ vhat, u32* __restrict__ row_state, u32 D,
-                                                u32 rf, const AdamParams& P, const double* __restrict__ head_part,
+                                                u32 rf, const AdamParams& P_in, const double* __restrict__ head_part,
                                                 const double* __restrict__ tail_part,
                                                 const double* __restrict__ block_head,
                                                 const u32* __restrict__ span_flags) {
   if (hdr->status) return;
+  AdamParams P = P_in;
+  if constexpr (KIND == STEP_ADAM_KINGMA) {
+    P.bc1 = hdr->bc1;
+    P.bc2 = hdr->bc2;
+  }
   constexpr int GPW = WAVE / LPR;
   const u32 s = (blockIdx.x * BLOCK + threadIdx.x) / WAVE;  // wave-uniform
   if (s >= n_spans) return;
@@ -425,7 +478,7 @@ __global__ void k_count_unique(DevHeader* hdr, const u32* __restrict__ span_rows
 //   PROSE == true (Section 4's prose: standard Adam locally, weights and v averaged): every
 //     replica's x becomes mean_j x_j and every v_j becomes mean_j v_j.
 template <int LPR, bool PROSE>
-__device__ __forceinline__ void merge_body(const DevHeader* hdr, float* __restrict__ values, u64 replica_stride,
+__device__ __forceinline__ void merge_body(DevHeader* hdr, float* __restrict__ values, u64 replica_stride,
                                            u32 W, float* __restrict__ vhat, u32* __restrict__ row_state, u32 D,
                                            float lr) {
   if (hdr->status) return;
@@ -433,15 +486,26 @@ __device__ __forceinline__ void merge_body(const DevHeader* hdr, float* __restri
   const u32 c = threadIdx.x % LPR;
   const u32 groups = gridDim.x * (BLOCK / LPR);
   const bool col_ok = c * 4 < D;
+  u32 merged = 0, pend = 0;
   for (u32 row = (blockIdx.x * BLOCK + threadIdx.x) / LPR; row < n_rows; row += groups) {
     const u32 st = row_state[row];
     if (!(st & RS_TOUCHED)) continue;
     if (col_ok) {
+      // replicas are taken eight at a time: the eight loads of a batch are independent of each other
+      // and issued together; the sums run over the replicas in ascending order whatever the batching
+      constexpr int MB = CTR_MERGE_MB;
       float* base = values + (u64)row * 3 * D + 4 * c;
       d4 vs = {0.0, 0.0, 0.0, 0.0};
-      for (u32 j = 0; j < W; ++j) {
-        const f4 v = ldg4(base + j * replica_stride + 2 * D);
-        vs.x += (double)v.x; vs.y += (double)v.y; vs.z += (double)v.z; vs.w += (double)v.w;
+      for (u32 j0 = 0; j0 < W; j0 += MB) {
+        f4 vv[MB];
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+          if (j0 + i < W) vv[i] = ldg4(base + (u64)(j0 + i) * replica_stride + 2 * D);
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+          if (j0 + i < W) {
+            vs.x += (double)vv[i].x; vs.y += (double)vv[i].y; vs.z += (double)vv[i].z; vs.w += (double)vv[i].w;
+          }
       }
       const double w = (double)W;
       f4 vh;
@@ -455,37 +519,88 @@ __device__ __forceinline__ void merge_body(const DevHeader* hdr, float* __restri
       }
       const double lrd = (double)lr;
       d4 xs = {0.0, 0.0, 0.0, 0.0};
-      for (u32 j = 0; j < W; ++j) {
-        const f4 x = ldg4(base + j * replica_stride);
-        d4 y = {(double)x.x, (double)x.y, (double)x.z, (double)x.w};
-        if (!PROSE && (st & (1u << j))) {
-          const f4 m = ldg4(base + j * replica_stride + D);
-          y.x -= lrd * (double)m.x * rs.x;
-          y.y -= lrd * (double)m.y * rs.y;
-          y.z -= lrd * (double)m.z * rs.z;
-          y.w -= lrd * (double)m.w * rs.w;
+      for (u32 j0 = 0; j0 < W; j0 += MB) {
+        f4 xx[MB], mm[MB];
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+          mm[i] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+          if (j0 + i < W) {
+            xx[i] = ldg4(base + (u64)(j0 + i) * replica_stride);
+            if (!PROSE && (st & (1u << (j0 + i)))) mm[i] = ldg4(base + (u64)(j0 + i) * replica_stride + D);
+          }
         }
-        xs.x += y.x; xs.y += y.y; xs.z += y.z; xs.w += y.w;
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+          if (j0 + i < W) {
+            d4 y = {(double)xx[i].x, (double)xx[i].y, (double)xx[i].z, (double)xx[i].w};
+            if (!PROSE && (st & (1u << (j0 + i)))) {
+              y.x -= lrd * (double)mm[i].x * rs.x;
+              y.y -= lrd * (double)mm[i].y * rs.y;
+              y.z -= lrd * (double)mm[i].z * rs.z;
+              y.w -= lrd * (double)mm[i].w * rs.w;
+            }
+            xs.x += y.x; xs.y += y.y; xs.z += y.z; xs.w += y.w;
+          }
       }
       f4 xb;
       xb.x = (float)(xs.x / w); xb.y = (float)(xs.y / w); xb.z = (float)(xs.z / w); xb.w = (float)(xs.w / w);
       for (u32 j = 0; j < W; ++j) stg4(base + j * replica_stride, xb);
     }
-    if (c == 0) row_state[row] = 0;
+    if (c == 0) {
+      row_state[row] = 0;
+      ++merged;
+      if (!PROSE) pend += (u32)__popc(st & ~RS_TOUCHED);
+    }
+  }
+  // rows averaged (and deferred steps applied) by this launch, for the byte accounting of the merge:
+  // one atomic per wave and counter
+  for (int off = WAVE / 2; off > 0; off >>= 1) {
+    merged += __shfl_xor(merged, off, WAVE);
+    pend += __shfl_xor(pend, off, WAVE);
+  }
+  if (lane_id() == 0 && merged) {
+    atomicAdd(&hdr->rows_merged, (u64)merged);
+    if (pend) atomicAdd(&hdr->merge_pending, (u64)pend);
   }
 }
 
 template <int LPR>
 __global__ void __launch_bounds__(BLOCK)
-k_merge(const DevHeader* hdr, float* __restrict__ values, u64 replica_stride, u32 W, float* __restrict__ vhat,
+k_merge(DevHeader* hdr, float* __restrict__ values, u64 replica_stride, u32 W, float* __restrict__ vhat,
         u32* __restrict__ row_state, u32 D, float lr) {
   merge_body<LPR, false>(hdr, values, replica_stride, W, vhat, row_state, D, lr);
 }
 template <int LPR>
 __global__ void __launch_bounds__(BLOCK)
-k_merge_prose(const DevHeader* hdr, float* __restrict__ values, u64 replica_stride, u32 W,
+k_merge_prose(DevHeader* hdr, float* __restrict__ values, u64 replica_stride, u32 W,
               float* __restrict__ vhat, u32* __restrict__ row_state, u32 D, float lr) {
   merge_body<LPR, true>(hdr, values, replica_stride, W, vhat, row_state, D, lr);
+}
+
+// Measurement aid: a plain streaming copy (16 bytes per lane and access, grid-stride), the practical
+// ceiling of this GPU's memory system against which the kernels above are also reported.
+// n16 = number of 16-byte units.  STREAM: use the non-temporal hint on both sides.
+template <bool STREAM>
+__global__ void __launch_bounds__(BLOCK) k_stream_copy(const vf4* __restrict__ src, vf4* __restrict__ dst, u64 n16) {
+  const u64 stride = (u64)gridDim.x * BLOCK;
+  u64 i = (u64)blockIdx.x * BLOCK + threadIdx.x;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    vf4 a, b, c, d;
+    if constexpr (STREAM) {
+      a = __builtin_nontemporal_load(src + i);
+      b = __builtin_nontemporal_load(src + i + stride);
+      c = __builtin_nontemporal_load(src + i + 2 * stride);
+      d = __builtin_nontemporal_load(src + i + 3 * stride);
+      __builtin_nontemporal_store(a, dst + i);
+      __builtin_nontemporal_store(b, dst + i + stride);
+      __builtin_nontemporal_store(c, dst + i + 2 * stride);
+      __builtin_nontemporal_store(d, dst + i + 3 * stride);
+    } else {
+      a = src[i]; b = src[i + stride]; c = src[i + 2 * stride]; d = src[i + 3 * stride];
+      dst[i] = a; dst[i + stride] = b; dst[i + 2 * stride] = c; dst[i + 3 * stride] = d;
+    }
+  }
+  for (; i < n16; i += stride) dst[i] = src[i];
 }
 
 }  // namespace ctr

@@ -11,10 +11,12 @@ namespace ctr {
 
 // ---------------------------------------------------------------- table creation
 
-__global__ void k_table_clear(DevHeader* hdr, Slot* slots, u64 n_slots, u32* row_state, u64 n_rows_cap) {
+// keep_step_count: the number of accepted pushes (step count of the bias-corrected update) survives.
+__global__ void k_table_clear(DevHeader* hdr, Slot* slots, u64 n_slots, u32* row_state, u64 n_rows_cap,
+                              u32 keep_step_count) {
   const u64 tid = (u64)blockIdx.x * BLOCK + threadIdx.x;
   const u64 stride = (u64)gridDim.x * BLOCK;
-  if (tid < 64) reinterpret_cast<u32*>(hdr)[tid] = 0;
+  if (tid < 64 && !(keep_step_count && tid == HDR_WORD_N_PUSH)) reinterpret_cast<u32*>(hdr)[tid] = 0;
   for (u64 i = tid; i < n_slots; i += stride) {
     Slot s;
     s.key = KEY_EMPTY;
@@ -429,6 +431,9 @@ __global__ void k_collect_rows(const DevHeader* hdr, const Slot* __restrict__ sl
 // pooled[g, :] = sum over the segment's occurrences of x[row, :], in CSR order, binary32
 // inside a batch of 4 consecutive occurrences and binary64 across batches, rounded once
 // (error <= 3 * 2^-24 * sum |x|).  A row is rf floats and starts with x.
+#ifndef CTR_POOL_NT_OUT
+#define CTR_POOL_NT_OUT 0  // 1: the pooled output (written once, read by the next stage) leaves with the non-temporal hint
+#endif
 constexpr int POOL_NS = 2;      // segments a group works on at once
 constexpr int POOL_ROUNDS = 2;  // such pairs per group
 
@@ -519,7 +524,11 @@ __device__ __forceinline__ void pool_body(const DevHeader* hdr, const u32* __res
       const u32 l = (rnd * POOL_NS + s) * GROUPS + grp;
       if (l < tile_n && col_ok) {
         f4 o = {(float)acc[s].x, (float)acc[s].y, (float)acc[s].z, (float)acc[s].w};
+#if CTR_POOL_NT_OUT
+        if constexpr (OUT & 1) stg4_stream(pooled + (u64)(tile_g0 + l) * D + 4 * c, o);
+#else
         if constexpr (OUT & 1) stg4(pooled + (u64)(tile_g0 + l) * D + 4 * c, o);
+#endif
         if constexpr (OUT & 2) stg4_bf16(pooled_bf16 + (u64)(tile_g0 + l) * D + 4 * c, o);  // the fp32 value, rounded again
       }
     }

@@ -11,14 +11,16 @@ from tests.parity_util import to_device
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("kstep", [False, True])
-def test_captured_pull_push_replays_like_eager_steps(kstep):
+@pytest.mark.parametrize("variant", ["single", "kstep", "bias_corrected"])
+def test_captured_pull_push_replays_like_eager_steps(variant):
+    # bias_corrected: the step count and its correction factors live on the device, so every replay is a new step t
+    kstep = variant == "kstep"
     import torch
     from paper_2201_05500_amd.binding import CTR_OK, CTR_STEP_LOCAL, CTR_STEP_MERGE_PENDING, CtrTable
     w = WL.scaled(WL.WORKLOADS["mid"], capacity_rows=1 << 15, zipf_universe=1 << 15, batch=256)
     bt = to_device(WL.as_numpy(WL.make_batch(w, 0)))
     other = to_device(WL.as_numpy(WL.make_batch(w, 1)))
-    kw = dict(init_seed=7, n_replicas=2 if kstep else 1, kstep=kstep)
+    kw = dict(init_seed=7, n_replicas=2 if kstep else 1, kstep=kstep, bias_correction=variant == "bias_corrected")
     eager, graphed = CtrTable(w.capacity_rows, w.dim, **kw), CtrTable(w.capacity_rows, w.dim, **kw)
     mode = CTR_STEP_MERGE_PENDING if kstep else CTR_STEP_LOCAL
     G = w.n_segments

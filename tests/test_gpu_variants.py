@@ -36,6 +36,43 @@ def test_single_table_variants(variant, name, kw):
         compare_tables(gt, ot, what="%s variant %d after step %d" % (name, variant, s))
 
 
+def test_bias_corrected_step_count_skips_refused_pushes_and_counts_empty_ones():
+    """The step count t of the bias-corrected update is the number of pushes the table ACCEPTED: a push
+    that follows a pull the device refused (reserved key) is a no-op on the GPU and is rejected by the
+    oracle, and neither may advance t; a push of an empty batch is accepted and advances it."""
+    import torch
+    from paper_2201_05500_amd import binding as B
+    w = WL.scaled(WL.WORKLOADS["tiny"], capacity_rows=1 << 12, zipf_universe=3000, batch=32)
+    gt, ot = _pair(w, O.VAR_KINGMA)
+    step = 0
+    for phase in range(3):
+        for _ in range(2):
+            bn = WL.as_numpy(WL.make_batch(w, step))
+            run_step(gt, ot, to_device(bn), bn, what="step %d" % step)
+            compare_tables(gt, ot, what="after step %d" % step)
+            step += 1
+        if phase == 0:      # a pull the device refuses, then the push of its handle
+            bn = WL.as_numpy(WL.make_batch(w, 100))
+            bn["keys"][5] = np.uint64(0xFFFFFFFFFFFFFFFF)
+            bt = to_device(bn)
+            st, h, _ = gt.pull_pool(0, bt["keys"], bt["offsets"])
+            assert st == B.CTR_OK                                  # the host cannot see the bad key
+            assert ot.pull_pool(0, bn["keys"], bn["offsets"])[0] == O.E_BADKEY
+            assert gt.push_adam(0, h, bt["grad"]) == B.CTR_OK      # enqueued, a no-op on the device
+            assert ot.push_adam(0, bn["grad"]) == O.E_STATE        # the oracle has no batch to push
+            assert gt.last_status() == B.CTR_E_BADKEY
+            compare_tables(gt, ot, what="after the refused pull")
+        if phase == 1:      # an empty batch: nothing to update, but the push is accepted
+            keys = torch.empty(0, dtype=torch.int64, device="cuda")
+            offs = torch.zeros(w.n_segments + 1, dtype=torch.int32, device="cuda")
+            grad = torch.zeros((w.n_segments, w.dim), dtype=torch.float32, device="cuda")
+            st, h, _ = gt.pull_pool(0, keys, offs)
+            assert st == B.CTR_OK and gt.push_adam(0, h, grad) == B.CTR_OK
+            assert ot.pull_pool(0, np.empty(0, np.uint64), np.zeros(w.n_segments + 1, np.uint32))[0] == O.OK
+            assert ot.push_adam(0, np.zeros((w.n_segments, w.dim), np.float32)) == O.OK
+            assert gt.last_status() == B.CTR_OK
+
+
 def test_adagrad_export_has_no_first_moment():
     from paper_2201_05500_amd import binding as B
     import ctypes as C
