@@ -263,8 +263,6 @@ def main():
     ap.add_argument("--predict", action="store_true",
                     help="full workload: the timed steps are predictions (lookup without insert + tower forward) "
                          "on a table filled by the warm-up's training steps")
-    ap.add_argument("--no-tune", action="store_true",
-                    help="full workload: skip the tower's set-up search for the fastest product kernels")
     ap.add_argument("--grad-bf16", action="store_true",
                     help="the pooled gradients reach the push as bfloat16 (ctr_push_adam_bf16): not the "
                          "configuration the metric is quoted on, which has fp32 gradients")
@@ -336,9 +334,6 @@ def main():
         tower = CtrMlp(in_dim, WL.FULL_STEP_HIDDEN, lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, init_seed=3,
                        device=dev)
         tower.reserve(w.batch)
-        if not args.no_tune:          # set-up, before anything is timed
-            if tower.tune(w.batch) != CTR_OK:
-                raise RuntimeError("ctr_mlp_tune failed")
         grad_pooled = torch.empty((G, w.dim), dtype=torch.bfloat16 if args.grad_bf16 else torch.float32, device=dev)
         pooled_bf16 = torch.empty((G, w.dim), dtype=torch.bfloat16, device=dev)
         loss = torch.empty(1, dtype=torch.float32, device=dev)
@@ -522,9 +517,8 @@ def main():
         out["samples_per_s"] = w.batch * K / elapsed
         out["final_loss"] = None if args.predict else float(loss.cpu()[0])
         out["stage_ms"]["tower"] = tower_ms
-        out["config"]["tower"] = "%d-%s-1, click rate %g, product kernels %s" % (
-            in_dim, "-".join(str(h) for h in WL.FULL_STEP_HIDDEN), WL.FULL_STEP_CLICK_RATE,
-            "as the library picks them" if args.no_tune else "picked by a timed search at set-up")
+        out["config"]["tower"] = "%d-%s-1, click rate %g, matrix products by the library's own MFMA kernel" % (
+            in_dim, "-".join(str(h) for h in WL.FULL_STEP_HIDDEN), WL.FULL_STEP_CLICK_RATE)
         out["roofline_tower"] = {
             "bound": "mfma", "kernel": ("ctr_mlp_forward" if args.predict else "ctr_mlp_step") +
             " (all products and element-wise kernels of one tower call)",

@@ -8,18 +8,18 @@
  * This header covers that middle step: forward, sigmoid cross-entropy loss, backward down to the
  * gradient of the pooled embeddings (the input of ctr_push_adam), and the dense optimizer.
  *
- * Arithmetic: matrix products take bf16 operands with fp32 accumulation on the matrix cores
- * (vendor GEMM kernels through hipBLASLt; rocBLAS if hipBLASLt cannot start or the environment
- * variable CTR_MLP_NO_HIPBLASLT is set when the tower is created; everything else is hand-written
- * HIP).  Master parameters, moments and the
+ * Arithmetic: matrix products take bf16 operands with fp32 accumulation on the matrix cores, in
+ * the library's own kernel (fixed summation order; bias + ReLU + rounding, and the ReLU gate of a
+ * back-propagated gradient + rounding, are applied as the products are stored); no vendor GEMM
+ * library is involved.  Master parameters, moments and the
  * optimizer are fp32/fp64 exactly as in the sparse path: m0 = 0, v0 = eps, no bias correction,
  * x -= lr m / sqrt(den) with den = own v (one replica) or the shared v frozen at the last merge.
  * Rounding to bf16 (nearest-even) happens at: the input, the weight copies used by the products,
  * every hidden activation, and every back-propagated hidden gradient.
  *
  * Conventions are those of ctr_sparse.h: d_* device pointers owned by the caller, `hip_stream`
- * a hipStream_t, calls enqueue only, status codes of ctr_status.  The library handles the tower
- * owns may keep small device allocations of their own.
+ * a hipStream_t, calls enqueue only, status codes of ctr_status.  The tower allocates no device
+ * memory of its own.
  */
 #ifndef CTR_MLP_H
 #define CTR_MLP_H
@@ -91,15 +91,18 @@ int ctr_mlp_step_bf16_grad_bf16(ctr_mlp* m, uint32_t replica, const uint16_t* d_
                                 uint32_t batch, uint16_t* d_grad_pooled_bf16, float* d_loss, void* d_workspace,
                                 size_t workspace_bytes, uint32_t mode, void* hip_stream);
 
-/* Optional set-up call: for every matrix product of a step at this batch size, times each
- * applicable matrix-core kernel of the vendor library on synthetic operands and keeps the fastest
- * one whose result agrees with the default kernel's (to 1e-3 of the largest element) and repeats
- * bit for bit; steps at this batch size then use those kernels (a call with another batch size
- * drops them).  Takes a few seconds, synchronises the stream, overwrites d_workspace
- * (>= ctr_mlp_tune_workspace_bytes(cfg, batch), 256-byte aligned; larger than the step's), leaves
- * parameters and optimizer state untouched.  Errors: CTR_E_INVAL, CTR_E_NOMEM, CTR_E_DEVICE. */
-size_t ctr_mlp_tune_workspace_bytes(const ctr_mlp_config* cfg, uint32_t batch);
-int ctr_mlp_tune(ctr_mlp* m, uint32_t batch, void* d_workspace, size_t workspace_bytes, void* hip_stream);
+/* The tower's matrix product on its own, for tests and measurements (Algorithm 1's train_mini-batch is
+ * made of three of these per layer): C[m x n] (fp32, row-major, rows ldc floats apart) = A[m x k] B[k x n]
+ * with bf16 operands and fp32 accumulation on the matrix cores, by the library's own kernel.
+ *   a_k_contiguous != 0: A is stored as m rows of k values (rows lda apart); else as k rows of m values
+ *   b_k_contiguous != 0: B is stored as n rows of k values (rows ldb apart); else as k rows of n values
+ *   d_scratch: device fp32 scratch for contractions split over several workgroups (may be NULL: no
+ *              split), scratch_bytes its size; the summation order is fixed either way
+ * All of m, n, k, lda, ldb, ldc are multiples of 8, every pointer is 16-byte aligned, each operand holds
+ * less than 4 GiB.  Enqueues only.  Errors: CTR_E_INVAL, CTR_E_DEVICE. */
+int ctr_mlp_gemm(int a_k_contiguous, int b_k_contiguous, const uint16_t* d_a, uint32_t lda, const uint16_t* d_b,
+                 uint32_t ldb, uint32_t m, uint32_t n, uint32_t k, float* d_c, uint32_t ldc, void* d_scratch,
+                 size_t scratch_bytes, void* hip_stream);
 
 /* Algorithm 2's global-averaging branch over all dense parameters of the W replicas:
  * shared v = mean_j v_j; x_i = mean_j (x_j - [merge step pending in j] lr m_j / sqrt(shared v)). */

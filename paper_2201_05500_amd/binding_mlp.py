@@ -9,7 +9,7 @@ from .binding import CTR_OK, CTR_STEP_LOCAL, lib as _base_lib
 
 CTR_MLP_MAX_HIDDEN = 6
 EXPORTED = ("ctr_mlp_bytes", "ctr_mlp_workspace_bytes", "ctr_mlp_create", "ctr_mlp_destroy", "ctr_mlp_step",
-            "ctr_mlp_forward", "ctr_mlp_step_bf16", "ctr_mlp_step_bf16_grad_bf16", "ctr_mlp_forward_bf16", "ctr_mlp_tune_workspace_bytes", "ctr_mlp_tune", "ctr_mlp_kstep_merge", "ctr_mlp_n_params", "ctr_mlp_export", "ctr_mlp_import")
+            "ctr_mlp_forward", "ctr_mlp_step_bf16", "ctr_mlp_step_bf16_grad_bf16", "ctr_mlp_forward_bf16", "ctr_mlp_gemm", "ctr_mlp_kstep_merge", "ctr_mlp_n_params", "ctr_mlp_export", "ctr_mlp_import")
 
 
 class ctr_mlp_config(C.Structure):
@@ -56,10 +56,8 @@ def lib():
         L.ctr_mlp_step_bf16_grad_bf16.argtypes = L.ctr_mlp_step.argtypes
         L.ctr_mlp_forward_bf16.restype = ci
         L.ctr_mlp_forward_bf16.argtypes = L.ctr_mlp_forward.argtypes
-        L.ctr_mlp_tune_workspace_bytes.restype = sz
-        L.ctr_mlp_tune_workspace_bytes.argtypes = [cfgp, u32]
-        L.ctr_mlp_tune.restype = ci
-        L.ctr_mlp_tune.argtypes = [vp, u32, vp, sz, vp]
+        L.ctr_mlp_gemm.restype = ci
+        L.ctr_mlp_gemm.argtypes = [ci, ci, vp, u32, vp, u32, u32, u32, u32, vp, u32, vp, sz, vp]
         L.ctr_mlp_kstep_merge.restype = ci
         L.ctr_mlp_kstep_merge.argtypes = [vp, vp]
         L.ctr_mlp_export.restype = ci
@@ -154,18 +152,6 @@ class CtrMlp:
                 self.stream)
         return st, logits
 
-    def tune(self, batch):
-        """Kernel search for the products of a step at this batch size (set-up call, seconds)."""
-        torch = self._torch
-        need = int(lib().ctr_mlp_tune_workspace_bytes(C.byref(self.cfg), batch))
-        if need == 0:
-            raise ValueError("invalid batch")
-        tmp = torch.empty(need, dtype=torch.uint8, device=self.device)
-        st = lib().ctr_mlp_tune(self._handle, batch, tmp.data_ptr(), need, self.stream)
-        torch.cuda.synchronize(self.device)
-        del tmp
-        return st
-
     def kstep_merge(self):
         return lib().ctr_mlp_kstep_merge(self._handle, self.stream)
 
@@ -188,3 +174,9 @@ class CtrMlp:
         if st != CTR_OK:
             raise RuntimeError("ctr_mlp_export: %d" % st)
         return {"params": p, "m": m, "v": v, "vhat": vh}
+
+
+def ctr_mlp_gemm(a_k_contiguous, b_k_contiguous, d_a, lda, d_b, ldb, m, n, k, d_c, ldc, d_scratch, scratch_bytes,
+                 stream) -> int:
+    return lib().ctr_mlp_gemm(1 if a_k_contiguous else 0, 1 if b_k_contiguous else 0, d_a, lda, d_b, ldb, m, n, k, d_c,
+                              ldc, d_scratch, scratch_bytes, stream)

@@ -36,7 +36,7 @@ def build_variant(out: str, defines, verbose: bool = False) -> str:
     """The library alone, with extra -D switches, written to `out` (for A/B measurements of the compile-time
     variants the kernels' headers document; load it with CTR_SPARSE_LIB=<out>)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-D" + d for d in defines] + ["-o", out] + sources() + ["-lrocblas", "-lhipblaslt"]
+    cmd = [hipcc] + HIPCC_FLAGS + ["-D" + d for d in defines] + ["-o", out] + sources()
     if verbose:
         print(" ".join(cmd))
     subprocess.check_call(cmd)
@@ -45,7 +45,7 @@ def build_variant(out: str, defines, verbose: bool = False) -> str:
 
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB] + sources() + ["-lrocblas", "-lhipblaslt"]  # bf16 GEMMs of the dense tower
+    cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB] + sources()
     if verbose:
         print(" ".join(cmd))
     subprocess.check_call(cmd)

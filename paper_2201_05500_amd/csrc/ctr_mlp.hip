@@ -1,12 +1,8 @@
-// Host side of the dense-tower C ABI (include/ctr_mlp.h): memory layout, the sequence of library
-// bf16 GEMMs (hipBLASLt with a kernel chosen per product, rocBLAS as the fallback) and hand-written
-// kernels of one training step, the dense optimizer and its merge.
+// Host side of the dense-tower C ABI (include/ctr_mlp.h): memory layout, the sequence of hand-written
+// kernels of one training step (the bf16 matrix products of gemm_kernels.h with their fused epilogues, the
+// element-wise kernels of mlp_kernels.h), the dense optimizer and its merge.
 #include "../../include/ctr_mlp.h"
 #include "../../include/ctr_sparse.h"
-
-#include <hipblaslt/hipblaslt.h>
-#include <hipblaslt/hipblaslt-ext.hpp>
-#include <rocblas/rocblas.h>
 
 #include <algorithm>
 #include <cmath>
@@ -14,10 +10,10 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
-#include <new>
 #include <vector>
 
 #include "common.h"
+#include "gemm_kernels.h"
 #include "mlp_kernels.h"
 
 using namespace ctr;
@@ -25,9 +21,10 @@ using namespace ctr;
 namespace {
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
-// Scratch a split-K product kernel may ask for: room for four partial copies of the largest weight
-// gradient (products with a small result and a long contraction are split along the batch).
-size_t lt_ws_bytes(const ctr_mlp_config* c) {
+// Scratch for products whose contraction is split over several workgroups (gemm_kernels.h): room for
+// four fp32 partial copies of the largest weight gradient, at least 32 MiB, at most 512 MiB.  A product
+// that would need more is split less.
+size_t gemm_scratch_bytes(const ctr_mlp_config* c) {
   size_t mx = 0;
   for (u32 l = 0; l < c->n_hidden; ++l)
     mx = std::max(mx, (size_t)(l == 0 ? c->in_dim : c->hidden[l - 1]) * c->hidden[l] * sizeof(float));
@@ -82,8 +79,8 @@ void mem_layout(const ctr_mlp_config* c, const MlpLayout& L, MemLayout* M) {
 
 struct WsLayout {
   u32 max_h;
-  size_t off_h0, off_act[CTR_MLP_MAX_HIDDEN], off_z, off_da, off_dz[2], off_logits, off_dlogit, off_lterm, off_grads,
-      off_partial, off_lt_ws, lt_ws, total;
+  size_t off_h0, off_act[CTR_MLP_MAX_HIDDEN], off_dz[2], off_logits, off_dlogit, off_lterm, off_grads, off_partial,
+      off_gemm, gemm_bytes, total;
 };
 
 void ws_layout(const ctr_mlp_config* c, const MlpLayout& L, u32 B, WsLayout* S) {
@@ -96,8 +93,6 @@ void ws_layout(const ctr_mlp_config* c, const MlpLayout& L, u32 B, WsLayout* S) 
     S->off_act[i] = o;
     o += align256((size_t)B * c->hidden[i] * sizeof(bf16_t));
   }
-  S->off_z = o; o += align256((size_t)B * mh * sizeof(float));
-  S->off_da = o; o += align256((size_t)B * mh * sizeof(float));
   S->off_dz[0] = o; o += align256((size_t)B * mh * sizeof(bf16_t));
   S->off_dz[1] = o; o += align256((size_t)B * mh * sizeof(bf16_t));
   S->off_logits = o; o += align256((size_t)B * sizeof(float));
@@ -105,32 +100,13 @@ void ws_layout(const ctr_mlp_config* c, const MlpLayout& L, u32 B, WsLayout* S) 
   S->off_lterm = o; o += align256((size_t)B * sizeof(double));
   S->off_grads = o; o += align256((size_t)L.n_params * sizeof(float));
   S->off_partial = o; o += align256((size_t)COLSUM_SLICES * mh * sizeof(float));
-  S->off_lt_ws = o; S->lt_ws = lt_ws_bytes(c); o += S->lt_ws;
+  S->off_gemm = o; S->gemm_bytes = gemm_scratch_bytes(c); o += S->gemm_bytes;
   S->total = o;
 }
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? CTR_OK : CTR_E_DEVICE; }
 
 }  // namespace
-
-// The three products of a hidden layer.  Row-major matrices are handed to the column-major
-// library as the column-major matrices of their transposes ((XY)^T = Y^T X^T):
-//   OP_FWD  Z[B x o]  = H[B x i] W[i x o]      -> gemm(N, N, m = o, n = B, k = i)
-//   OP_DW   dW[i x o] = H^T[i x B] dZ[B x o]   -> gemm(N, T, m = o, n = i, k = B)
-//   OP_DH   dH[B x i] = dZ[B x o] W^T[o x i]   -> gemm(T, N, m = i, n = B, k = o)
-//   OP_DH16 the first layer's OP_DH with the result rounded to bf16 on the way out (the gradient of a
-//           bf16 input handed back in the input's precision); planned for layer 0 only
-enum { OP_FWD = 0, OP_DW = 1, OP_DH = 2, OP_DH16 = 3, N_OPS = 4 };
-
-struct LtPlan {
-  bool ready = false;  // descriptors exist and an algorithm was found
-  bool tuned = false;  // the algorithm is the winner of ctr_mlp_tune, not the library's first guess
-  hipblasLtMatmulDesc_t desc = nullptr;
-  hipblasLtMatrixLayout_t la = nullptr, lb = nullptr, lc = nullptr;
-  hipblasLtMatmulAlgo_t algo;
-  size_t ws = 0;
-  int m = 0, n = 0, k = 0;
-};
 
 struct ctr_mlp {
   ctr_mlp_config cfg;
@@ -139,274 +115,54 @@ struct ctr_mlp {
   char* mem;
   float *params, *m, *v, *vhat;
   bf16_t* pb;
-  rocblas_handle blas;
-  hipblasLtHandle_t lt;
-  u32 plan_batch;  // batch size the plans were made for (0: none)
-  LtPlan plans[CTR_MLP_MAX_HIDDEN][N_OPS];
   u32 pend_mask;  // replicas whose last step was a merge step not merged yet
 };
 
 namespace {
 
-struct GemmShape {
-  hipblasOperation_t opa, opb;
-  int m, n, k, lda, ldb, ldc;
-};
-
-GemmShape shape_of(const MlpLayout& L, u32 l, int op, u32 B) {
-  const int i = (int)L.in[l], o = (int)L.out[l], b = (int)B;
-  switch (op) {
-    case OP_FWD: return {HIPBLAS_OP_N, HIPBLAS_OP_N, o, b, i, o, i, o};
-    case OP_DW: return {HIPBLAS_OP_N, HIPBLAS_OP_T, o, i, b, o, i, o};
-    default: return {HIPBLAS_OP_T, HIPBLAS_OP_N, i, b, o, o, o, i};
-  }
+// The three products of a hidden layer with row-major matrices, as C[M x N] = A B of gemm_kernels.h
+// (which operand is stored with the contraction index contiguous differs from product to product):
+//   forward          act[B x o]  = bf16(relu(H[B x i] W[i x o] + bias))     A = H (k-contiguous), B = W (n-contiguous)
+//   weight gradient  dW[i x o]   = H^T[i x B] dZ[B x o]                     A = H (m-contiguous), B = dZ (n-contiguous)
+//   input gradient   dH[B x i]   = dZ[B x o] W^T[o x i]                     A = dZ (k-contiguous), B = W (k-contiguous)
+// The input gradient of a hidden layer goes straight through the ReLU of the layer below (mask = that
+// layer's activation) and is stored as bf16; the first layer's is the gradient of the pooled input,
+// stored as fp32 or bf16.
+bool product_forward(const MlpLayout& L, u32 l, u32 B, const bf16_t* h, const bf16_t* w, const float* bias,
+                     bf16_t* act, char* ws, const WsLayout& S, hipStream_t st) {
+  GemmArgs g{};
+  g.A = h; g.lda = L.in[l];
+  g.B = w; g.ldb = L.out[l];
+  g.M = B; g.N = L.out[l]; g.K = L.in[l];
+  g.C16 = act; g.ldc = L.out[l];
+  g.bias = bias;
+  g.epilogue = EPI_BIAS_RELU_BF16;
+  return gemm_enqueue(true, false, g, (float*)(ws + S.off_gemm), S.gemm_bytes, st) == hipSuccess;
 }
 
-void destroy_plan(LtPlan* p) {
-  if (p->desc) (void)hipblasLtMatmulDescDestroy(p->desc);
-  if (p->la) (void)hipblasLtMatrixLayoutDestroy(p->la);
-  if (p->lb) (void)hipblasLtMatrixLayoutDestroy(p->lb);
-  if (p->lc) (void)hipblasLtMatrixLayoutDestroy(p->lc);
-  *p = LtPlan();
+bool product_weight_grad(const MlpLayout& L, u32 l, u32 B, const bf16_t* h, const bf16_t* dz, float* dw, char* ws,
+                         const WsLayout& S, hipStream_t st) {
+  GemmArgs g{};
+  g.A = h; g.lda = L.in[l];
+  g.B = dz; g.ldb = L.out[l];
+  g.M = L.in[l]; g.N = L.out[l]; g.K = B;
+  g.C32 = dw; g.ldc = L.out[l];
+  g.epilogue = EPI_F32;
+  return gemm_enqueue(false, false, g, (float*)(ws + S.off_gemm), S.gemm_bytes, st) == hipSuccess;
 }
 
-void destroy_plans(ctr_mlp* t) {
-  for (u32 l = 0; l < CTR_MLP_MAX_HIDDEN; ++l)
-    for (int op = 0; op < N_OPS; ++op) destroy_plan(&t->plans[l][op]);
-  t->plan_batch = 0;
+// exactly one of out32 / out16 / (mask, out16): fp32, bf16, or bf16 gated by the sign of `mask`
+bool product_input_grad(const MlpLayout& L, u32 l, u32 B, const bf16_t* dz, const bf16_t* w, float* out32,
+                        bf16_t* out16, const bf16_t* mask, char* ws, const WsLayout& S, hipStream_t st) {
+  GemmArgs g{};
+  g.A = dz; g.lda = L.out[l];
+  g.B = w; g.ldb = L.out[l];
+  g.M = B; g.N = L.in[l]; g.K = L.out[l];
+  g.C32 = out32; g.C16 = out16; g.ldc = L.in[l];
+  g.mask = mask;
+  g.epilogue = out32 ? EPI_F32 : (mask ? EPI_RELU_MASK_BF16 : EPI_BF16);
+  return gemm_enqueue(true, true, g, (float*)(ws + S.off_gemm), S.gemm_bytes, st) == hipSuccess;
 }
-
-// Descriptors of one product and the library's own first choice of kernel for it.
-bool make_plan(ctr_mlp* t, u32 l, int op, u32 B, LtPlan* p) {
-  const GemmShape g = shape_of(t->L, l, op, B);
-  const bool ok = hipblasLtMatmulDescCreate(&p->desc, HIPBLAS_COMPUTE_32F, HIP_R_32F) == HIPBLAS_STATUS_SUCCESS &&
-                  hipblasLtMatmulDescSetAttribute(p->desc, HIPBLASLT_MATMUL_DESC_TRANSA, &g.opa, sizeof(g.opa)) ==
-                      HIPBLAS_STATUS_SUCCESS &&
-                  hipblasLtMatmulDescSetAttribute(p->desc, HIPBLASLT_MATMUL_DESC_TRANSB, &g.opb, sizeof(g.opb)) ==
-                      HIPBLAS_STATUS_SUCCESS &&
-                  hipblasLtMatrixLayoutCreate(&p->la, HIP_R_16BF, g.opa == HIPBLAS_OP_N ? g.m : g.k,
-                                              g.opa == HIPBLAS_OP_N ? g.k : g.m, g.lda) == HIPBLAS_STATUS_SUCCESS &&
-                  hipblasLtMatrixLayoutCreate(&p->lb, HIP_R_16BF, g.opb == HIPBLAS_OP_N ? g.k : g.n,
-                                              g.opb == HIPBLAS_OP_N ? g.n : g.k, g.ldb) == HIPBLAS_STATUS_SUCCESS &&
-                  hipblasLtMatrixLayoutCreate(&p->lc, op == OP_DH16 ? HIP_R_16BF : HIP_R_32F, g.m, g.n, g.ldc) ==
-                      HIPBLAS_STATUS_SUCCESS;
-  if (!ok) return false;
-  p->m = g.m; p->n = g.n; p->k = g.k;
-  hipblasLtMatmulPreference_t pref = nullptr;
-  if (hipblasLtMatmulPreferenceCreate(&pref) != HIPBLAS_STATUS_SUCCESS) return false;
-  const uint64_t max_ws = lt_ws_bytes(&t->cfg);
-  hipblasLtMatmulHeuristicResult_t res[4];
-  int n_res = 0;
-  bool found = hipblasLtMatmulPreferenceSetAttribute(pref, HIPBLASLT_MATMUL_PREF_MAX_WORKSPACE_BYTES, &max_ws,
-                                                      sizeof(max_ws)) == HIPBLAS_STATUS_SUCCESS &&
-               hipblasLtMatmulAlgoGetHeuristic(t->lt, p->desc, p->la, p->lb, p->lc, p->lc, pref, 4, res, &n_res) ==
-                   HIPBLAS_STATUS_SUCCESS;
-  (void)hipblasLtMatmulPreferenceDestroy(pref);
-  if (!found) return false;
-  for (int r = 0; r < n_res; ++r) {
-    if (res[r].state == HIPBLAS_STATUS_SUCCESS && res[r].workspaceSize <= max_ws) {
-      p->algo = res[r].algo;
-      p->ws = res[r].workspaceSize;
-      p->ready = true;
-      return true;
-    }
-  }
-  return false;
-}
-
-// Plans are made for one batch size and kept until a call comes with another.
-void ensure_plans(ctr_mlp* t, u32 B) {
-  if (t->plan_batch == B || !t->lt) return;
-  destroy_plans(t);
-  for (u32 l = 0; l + 1 < t->L.n_layers; ++l)
-    for (int op = 0; op < N_OPS; ++op)
-      if ((op == OP_DH16 && l != 0) || !make_plan(t, l, op, B, &t->plans[l][op])) destroy_plan(&t->plans[l][op]);
-  t->plan_batch = B;
-}
-
-// rocBLAS's default kernel for a product (bf16 operands, fp32 accumulation; the result fp32, or
-// bf16 for OP_DH16).
-bool rocblas_product(ctr_mlp* t, u32 l, int op, u32 B, const void* a, const void* b, void* c) {
-  const float alpha = 1.0f, beta = 0.0f;
-  const GemmShape g = shape_of(t->L, l, op, B);
-  const rocblas_datatype ct = op == OP_DH16 ? rocblas_datatype_bf16_r : rocblas_datatype_f32_r;
-  return rocblas_gemm_ex(t->blas, g.opa == HIPBLAS_OP_N ? rocblas_operation_none : rocblas_operation_transpose,
-                         g.opb == HIPBLAS_OP_N ? rocblas_operation_none : rocblas_operation_transpose, g.m, g.n, g.k,
-                         &alpha, a, rocblas_datatype_bf16_r, g.lda, b, rocblas_datatype_bf16_r, g.ldb, &beta, c, ct,
-                         g.ldc, c, ct, g.ldc, rocblas_datatype_f32_r, rocblas_gemm_algo_standard, 0, 0) ==
-         rocblas_status_success;
-}
-
-// One product on the matrix cores: the planned hipBLASLt kernel, else rocBLAS's default.
-// c: fp32, except bf16 for OP_DH16.
-bool product(ctr_mlp* t, u32 l, int op, u32 B, const void* a, const void* b, void* c, char* ws, const WsLayout& S,
-             hipStream_t st) {
-  const float alpha = 1.0f, beta = 0.0f;
-  const LtPlan& p = t->plans[l][op];
-  if (t->plan_batch == B && p.ready)
-    return hipblasLtMatmul(t->lt, p.desc, &alpha, a, p.la, b, p.lb, &beta, c, p.lc, c, p.lc, &p.algo,
-                           ws + S.off_lt_ws, p.ws, st) == HIPBLAS_STATUS_SUCCESS;
-  return rocblas_product(t, l, op, B, a, b, c);
-}
-
-// ---------------------------------------------------------------- kernel search (ctr_mlp_tune)
-
-size_t tune_result_bytes(const MlpLayout& L, u32 B) {
-  size_t mx = 0;
-  for (u32 l = 0; l + 1 < L.n_layers; ++l) {
-    mx = std::max(mx, (size_t)B * L.out[l]);        // forward
-    mx = std::max(mx, (size_t)L.in[l] * L.out[l]);  // weight gradient
-    mx = std::max(mx, (size_t)B * L.in[l]);         // input gradient
-  }
-  return align256(mx * sizeof(float));
-}
-
-struct Tuner {
-  ctr_mlp* t;
-  hipStream_t st;
-  char* ws;
-  const WsLayout& S;
-  u32* d_words;
-  hipEvent_t e0 = nullptr, e1 = nullptr;
-  bool ok = false;
-
-  Tuner(ctr_mlp* t_, hipStream_t st_, char* ws_, const WsLayout& S_, u32* d_words_)
-      : t(t_), st(st_), ws(ws_), S(S_), d_words(d_words_) {
-    if (hipEventCreate(&e0) != hipSuccess) return;
-    if (hipEventCreate(&e1) != hipSuccess) return;
-    ok = true;
-  }
-  ~Tuner() {
-    if (e0) (void)hipEventDestroy(e0);
-    if (e1) (void)hipEventDestroy(e1);
-  }
-
-  // Milliseconds of one run of `algo` into `out`, or a negative value if the library refuses it.
-  float run(const LtPlan& p, const hipblasLtMatmulAlgo_t& algo, size_t wsz, const void* a, const void* b, void* out) {
-    const float alpha = 1.0f, beta = 0.0f;
-    if (hipEventRecord(e0, st) != hipSuccess) return -1.0f;
-    const hipblasStatus_t rc = hipblasLtMatmul(t->lt, p.desc, &alpha, a, p.la, b, p.lb, &beta, out, p.lc, out, p.lc,
-                                               &algo, ws + S.off_lt_ws, wsz, st);
-    if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) return -1.0f;
-    if (rc != HIPBLAS_STATUS_SUCCESS) return -1.0f;
-    float ms = -1.0f;
-    if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) return -1.0f;
-    return ms;
-  }
-
-  bool read_words(u32 h[4]) {
-    return hipMemcpyAsync(h, d_words, 4 * sizeof(u32), hipMemcpyDeviceToHost, st) == hipSuccess &&
-           hipStreamSynchronize(st) == hipSuccess;
-  }
-
-  // The candidate agrees with the reference (accumulation order aside) and repeats bit for bit.
-  // fp32 results: to 1e-3 of the largest element.  bf16 results (n even): two correct kernels may
-  // round an element to neighbouring bf16 values, one unit in the last place of the largest
-  // element (2^-7 of it) at most.
-  bool valid(const LtPlan& p, const hipblasLtMatmulAlgo_t& algo, size_t wsz, const void* a, const void* b,
-             const void* ref, void* cand, u64 n, bool out_bf16) {
-    u32 h1[4], h2[4];
-    for (int rep = 0; rep < 2; ++rep) {
-      if (hipMemsetAsync(d_words, 0, 4 * sizeof(u32), st) != hipSuccess) return false;
-      if (run(p, algo, wsz, a, b, cand) < 0.0f) return false;
-      if (out_bf16) {
-        hipLaunchKernelGGL(k_max_diff_bf16, dim3(2048), dim3(BLOCK), 0, st, (const bf16_t*)ref, (const bf16_t*)cand, n,
-                           d_words);
-        hipLaunchKernelGGL(k_hash_bits, dim3(2048), dim3(BLOCK), 0, st, (const float*)cand, n / 2,
-                           (unsigned long long*)(d_words + 2));
-      } else {
-        hipLaunchKernelGGL(k_max_diff, dim3(2048), dim3(BLOCK), 0, st, (const float*)ref, (const float*)cand, n,
-                           d_words);
-        hipLaunchKernelGGL(k_hash_bits, dim3(2048), dim3(BLOCK), 0, st, (const float*)cand, n,
-                           (unsigned long long*)(d_words + 2));
-      }
-      if (!read_words(rep ? h2 : h1)) return false;
-    }
-    float md, ma;
-    memcpy(&md, &h1[0], 4);
-    memcpy(&ma, &h1[1], 4);
-    return md <= (out_bf16 ? 0.0078125f : 1e-3f) * ma && h1[2] == h2[2] && h1[3] == h2[3];
-  }
-
-  // Replaces the plan's kernel by the fastest applicable one that passes valid().  A product for
-  // which nothing better is found keeps the library's choice.  Returns false on a device error only.
-  bool tune_one(u32 l, int op, u32 B, float* ref, float* cand) {
-    if (op == OP_DH16 && l != 0) return true;  // exists for the first layer only
-    LtPlan& p = t->plans[l][op];
-    if (!p.ready) {
-      if (getenv("CTR_MLP_TUNE_LOG")) fprintf(stderr, "ctr_mlp_tune: layer %u product %d: no plan (rocBLAS runs it)\n", l, op);
-      return true;
-    }
-    const MlpLayout& L = t->L;
-    bf16_t* act_in = l == 0 ? (bf16_t*)(ws + S.off_h0) : (bf16_t*)(ws + S.off_act[l - 1]);  // B x in_l
-    bf16_t* dzb = (bf16_t*)(ws + S.off_dz[0]);                                              // B x out_l
-    const bf16_t* w = t->pb + L.w_off[l];
-    const void* a = op == OP_DW ? (const void*)dzb : (const void*)w;
-    const void* b = (op == OP_DH || op == OP_DH16) ? (const void*)dzb : (const void*)act_in;
-    const u64 n = (u64)p.m * p.n;
-    hipLaunchKernelGGL(k_fill_pattern_bf16, dim3(2048), dim3(BLOCK), 0, st, act_in, (u64)B * L.in[l], 0x1234u + l);
-    hipLaunchKernelGGL(k_fill_pattern_bf16, dim3(2048), dim3(BLOCK), 0, st, dzb, (u64)B * L.out[l], 0x9876u + l);
-    // reference: rocBLAS's own kernel for the same product
-    if (!rocblas_product(t, l, op, B, a, b, ref)) return true;  // nothing to compare against: keep the plan as it is
-    std::vector<hipblasLtMatmulHeuristicResult_t> all;
-    const GemmShape g = shape_of(L, l, op, B);
-    const hipDataType out_t = op == OP_DH16 ? HIP_R_16BF : HIP_R_32F;
-    if (hipblaslt_ext::getAllAlgos(t->lt, hipblaslt_ext::GemmType::HIPBLASLT_GEMM, g.opa, g.opb, HIP_R_16BF, HIP_R_16BF,
-                                   out_t, out_t, HIPBLAS_COMPUTE_32F, all) != HIPBLAS_STATUS_SUCCESS)
-      return true;
-    struct Timed { float ms; size_t idx, wsz; };
-    std::vector<Timed> timed;
-    size_t n_big = 0, n_sup = 0;
-    const float alpha = 1.0f, beta = 0.0f;
-    float best = run(p, p.algo, p.ws, a, b, cand);  // the current choice; the first run warms up
-    best = run(p, p.algo, p.ws, a, b, cand);
-    if (best >= 0.0f) best = std::min(best, run(p, p.algo, p.ws, a, b, cand));
-    if (best < 0.0f) {
-      if (getenv("CTR_MLP_TUNE_LOG")) fprintf(stderr, "ctr_mlp_tune: layer %u product %d: the planned kernel does not run\n", l, op);
-      return hipGetLastError() == hipSuccess;
-    }
-    const float current = best;
-    for (size_t i = 0; i < all.size(); ++i) {
-      size_t wsz = 0;
-      if (hipblaslt_ext::matmulIsAlgoSupported(t->lt, p.desc, &alpha, p.la, p.lb, &beta, p.lc, p.lc, all[i].algo, wsz) !=
-          HIPBLAS_STATUS_SUCCESS)
-        continue;
-      if (wsz > S.lt_ws) { ++n_big; continue; }
-      ++n_sup;
-      if (run(p, all[i].algo, wsz, a, b, cand) < 0.0f) continue;  // the first run of a kernel pays for loading it
-      float ms = run(p, all[i].algo, wsz, a, b, cand);
-      if (ms < 0.0f) continue;
-      if (ms < 1.1f * best) {  // a contender: one more look
-        const float ms2 = run(p, all[i].algo, wsz, a, b, cand);
-        if (ms2 >= 0.0f) ms = std::min(ms, ms2);
-      }
-      best = std::min(best, ms);
-      timed.push_back({ms, i, wsz});
-    }
-    std::sort(timed.begin(), timed.end(), [](const Timed& x, const Timed& y) { return x.ms < y.ms; });
-    const bool log = getenv("CTR_MLP_TUNE_LOG") != nullptr;
-    if (log)
-      fprintf(stderr, "ctr_mlp_tune: layer %u product %d (m %d n %d k %d): library's choice %.3f ms (index %d), %zu listed, %zu applicable, %zu need more scratch, %zu ran, fastest %.3f ms\n",
-              l, op, p.m, p.n, p.k, current, hipblaslt_ext::getIndexFromAlgo(p.algo), all.size(), n_sup, n_big, timed.size(), timed.empty() ? -1.0f : timed[0].ms);
-    if (log)
-      for (size_t r = 0; r < std::min<size_t>(timed.size(), 4); ++r)
-        fprintf(stderr, "ctr_mlp_tune:   #%zu %.3f ms ws %zu index %d %s\n", r, timed[r].ms, timed[r].wsz,
-                hipblaslt_ext::getIndexFromAlgo(all[timed[r].idx].algo),
-                hipblaslt_ext::getKernelNameFromAlgo(t->lt, all[timed[r].idx].algo).substr(0, 110).c_str());
-    for (const Timed& c : timed) {
-      if (c.ms >= 0.97f * current) break;  // not better than what the library chose by itself
-      const bool good = valid(p, all[c.idx].algo, c.wsz, a, b, ref, cand, n, op == OP_DH16);
-      if (log) fprintf(stderr, "ctr_mlp_tune:   candidate %zu at %.3f ms: %s\n", c.idx, c.ms, good ? "taken" : "rejected");
-      if (good) {
-        p.algo = all[c.idx].algo;
-        p.ws = c.wsz;
-        p.tuned = true;
-        break;
-      }
-    }
-    return hipGetLastError() == hipSuccess;
-  }
-};
 
 // Forward through the hidden layers and the output layer; activations stay in the workspace.
 // The input is either fp32 (rounded to bf16 into the workspace) or already bf16 (used in place).
@@ -416,19 +172,14 @@ bool forward(ctr_mlp* t, u32 replica, const float* d_pooled, const bf16_t* d_poo
   const float* P = t->params + (u64)replica * t->M.stride;
   const bf16_t* PB = t->pb + (u64)replica * t->M.stride;
   const bf16_t* h = d_pooled_bf16;
-  float* z = (float*)(ws + S.off_z);
   if (!h) {
     const u64 n0 = (u64)B * L.in[0];
     hipLaunchKernelGGL(k_cast_bf16, dim3(blocks_for(n0 / 4)), dim3(BLOCK), 0, st, d_pooled, (bf16_t*)(ws + S.off_h0), n0);
     h = (const bf16_t*)(ws + S.off_h0);
   }
   for (u32 l = 0; l + 1 < L.n_layers; ++l) {
-    const int i = (int)L.in[l], o = (int)L.out[l];
-    if (!product(t, l, OP_FWD, B, PB + L.w_off[l], h, z, ws, S, st)) return false;
     bf16_t* a = (bf16_t*)(ws + S.off_act[l]);
-    const u64 n = (u64)B * o;
-    hipLaunchKernelGGL(k_bias_relu_bf16, dim3(blocks_for(n / 4)), dim3(BLOCK), 0, st, z,
-                       P + L.w_off[l] + (u64)i * o, (u32)o, n, a);
+    if (!product_forward(L, l, B, h, PB + L.w_off[l], P + L.w_off[l] + (u64)L.in[l] * L.out[l], a, ws, S, st)) return false;
     h = a;
   }
   const u32 lo = L.n_layers - 1;
@@ -486,23 +237,11 @@ int ctr_mlp_create(const ctr_mlp_config* cfg, void* d_mem, size_t bytes, void* h
   t->pb = (bf16_t*)(t->mem + t->M.off_pb);
   t->vhat = cfg->kstep ? (float*)(t->mem + t->M.off_vhat) : nullptr;
   t->pend_mask = 0;
-  if (rocblas_create_handle(&t->blas) != rocblas_status_success) {
-    delete t;
-    return CTR_E_DEVICE;
-  }
-  // CTR_MLP_NO_HIPBLASLT in the environment (or a hipBLASLt that cannot start) sends the products through rocBLAS
-  if (getenv("CTR_MLP_NO_HIPBLASLT") != nullptr || hipblasLtCreate(&t->lt) != HIPBLAS_STATUS_SUCCESS) t->lt = nullptr;
-  t->plan_batch = 0;
-  // fixed summation order: no atomics in the products
-  (void)rocblas_set_atomics_mode(t->blas, rocblas_atomics_not_allowed);
-  (void)rocblas_set_pointer_mode(t->blas, rocblas_pointer_mode_host);
   hipStream_t st = (hipStream_t)hip_stream;
   hipLaunchKernelGGL(k_mlp_init, dim3(blocks_for(t->L.n_params)), dim3(BLOCK), 0, st, t->L,
                      cfg->init_seed * 0x9E3779B97F4A7C15ull, cfg->eps, cfg->n_replicas, t->M.stride, t->params, t->m,
                      t->v, t->vhat, t->pb);
   if (launch_status() != CTR_OK) {
-    (void)rocblas_destroy_handle(t->blas);
-    if (t->lt) (void)hipblasLtDestroy(t->lt);
     delete t;
     return CTR_E_DEVICE;
   }
@@ -512,9 +251,6 @@ int ctr_mlp_create(const ctr_mlp_config* cfg, void* d_mem, size_t bytes, void* h
 
 int ctr_mlp_destroy(ctr_mlp* t) {
   if (!t) return CTR_E_INVAL;
-  destroy_plans(t);
-  (void)rocblas_destroy_handle(t->blas);
-  if (t->lt) (void)hipblasLtDestroy(t->lt);
   delete t;
   return CTR_OK;
 }
@@ -529,8 +265,6 @@ static int mlp_forward_impl(ctr_mlp* t, uint32_t replica, const float* d_pooled,
   ws_layout(&t->cfg, t->L, batch, &S);
   if (workspace_bytes < S.total) return CTR_E_NOMEM;
   hipStream_t st = (hipStream_t)hip_stream;
-  if (rocblas_set_stream(t->blas, st) != rocblas_status_success) return CTR_E_DEVICE;
-  ensure_plans(t, batch);
   if (!forward(t, replica, d_pooled, d_pooled_bf16, batch, (char*)d_workspace, S, d_logits, st)) return CTR_E_DEVICE;
   return launch_status();
 }
@@ -550,8 +284,6 @@ static int mlp_step_impl(ctr_mlp* t, uint32_t replica, const float* d_pooled, co
   ws_layout(&t->cfg, t->L, batch, &S);
   if (workspace_bytes < S.total) return CTR_E_NOMEM;
   hipStream_t st = (hipStream_t)hip_stream;
-  if (rocblas_set_stream(t->blas, st) != rocblas_status_success) return CTR_E_DEVICE;
-  ensure_plans(t, batch);
 
   const MlpLayout& L = t->L;
   char* ws = (char*)d_workspace;
@@ -560,7 +292,6 @@ static int mlp_step_impl(ctr_mlp* t, uint32_t replica, const float* d_pooled, co
   float* dlogit = (float*)(ws + S.off_dlogit);
   float* grads = (float*)(ws + S.off_grads);
   float* partial = (float*)(ws + S.off_partial);
-  float* da = (float*)(ws + S.off_da);
   const bf16_t* PB = t->pb + (u64)replica * t->M.stride;
 
   double* lterm = (double*)(ws + S.off_lterm);
@@ -588,21 +319,18 @@ static int mlp_step_impl(ctr_mlp* t, uint32_t replica, const float* d_pooled, co
   for (int l = (int)lo - 1; l >= 0; --l) {
     const int i = (int)L.in[l], o = (int)L.out[l];
     const bf16_t* h_prev = l == 0 ? h0 : (const bf16_t*)(ws + S.off_act[l - 1]);
-    if (!product(t, (u32)l, OP_DW, B, dz, h_prev, grads + L.w_off[l], ws, S, st)) return CTR_E_DEVICE;
+    if (!product_weight_grad(L, (u32)l, B, h_prev, dz, grads + L.w_off[l], ws, S, st)) return CTR_E_DEVICE;
     hipLaunchKernelGGL(k_colsum_partial, dim3((o + 31) / 32, COLSUM_SLICES), dim3(BLOCK), 0, st, dz, (const float*)nullptr,
                        B, (u32)o, partial);
     hipLaunchKernelGGL(k_colsum_final, dim3(blocks_for(o)), dim3(BLOCK), 0, st, partial, (u32)o,
                        grads + L.w_off[l] + (u64)i * o);
-    // dH_prev[B x i] = dZ[B x o] W^T[o x i]; for the first layer this is the gradient of the pooled input
-    if (l == 0 && d_grad_pooled_bf16) {
-      if (!product(t, 0, OP_DH16, B, PB + L.w_off[0], dz, d_grad_pooled_bf16, ws, S, st)) return CTR_E_DEVICE;
+    // dH_prev[B x i] = dZ[B x o] W^T[o x i]: for the first layer the gradient of the pooled input; for a hidden
+    // layer gated by the ReLU below and rounded to bf16 on the way out (the next dZ)
+    if (l == 0) {
+      if (!product_input_grad(L, 0, B, dz, PB + L.w_off[0], d_grad_pooled, d_grad_pooled_bf16, nullptr, ws, S, st))
+        return CTR_E_DEVICE;
     } else {
-      float* dst = l == 0 ? d_grad_pooled : da;
-      if (!product(t, (u32)l, OP_DH, B, PB + L.w_off[l], dz, dst, ws, S, st)) return CTR_E_DEVICE;
-    }
-    if (l > 0) {
-      const u64 n = (u64)B * i;
-      hipLaunchKernelGGL(k_relu_bwd_bf16, dim3(blocks_for(n / 4)), dim3(BLOCK), 0, st, da, h_prev, n, dz_next);
+      if (!product_input_grad(L, (u32)l, B, dz, PB + L.w_off[l], nullptr, dz_next, h_prev, ws, S, st)) return CTR_E_DEVICE;
       std::swap(dz, dz_next);
     }
   }
@@ -653,43 +381,23 @@ int ctr_mlp_step_bf16_grad_bf16(ctr_mlp* t, uint32_t replica, const uint16_t* d_
                        d_workspace, workspace_bytes, mode, hip_stream);
 }
 
-size_t ctr_mlp_tune_workspace_bytes(const ctr_mlp_config* cfg, uint32_t batch) {
-  if (!mlp_config_ok(cfg) || batch == 0 || batch % 8 != 0 || batch > CTR_MLP_MAX_BATCH) return 0;
-  MlpLayout L;
-  WsLayout S;
-  make_layout(cfg, &L);
-  ws_layout(cfg, L, batch, &S);
-  return S.total + 2 * tune_result_bytes(L, batch) + 256;
-}
-
-int ctr_mlp_tune(ctr_mlp* t, uint32_t batch, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
-  if (!t || !d_workspace) return CTR_E_INVAL;
-  if (batch == 0 || batch % 8 != 0 || batch > CTR_MLP_MAX_BATCH) return CTR_E_INVAL;
-  if (((uintptr_t)d_workspace & 255) != 0) return CTR_E_INVAL;
-  WsLayout S;
-  ws_layout(&t->cfg, t->L, batch, &S);
-  const size_t res_bytes = tune_result_bytes(t->L, batch);
-  if (workspace_bytes < S.total + 2 * res_bytes + 256) return CTR_E_NOMEM;
-  if (!t->lt) return CTR_OK;  // no kernel to choose: the products run through rocBLAS
-  hipStream_t st = (hipStream_t)hip_stream;
-  if (rocblas_set_stream(t->blas, st) != rocblas_status_success) return CTR_E_DEVICE;
-  ensure_plans(t, batch);
-  char* ws = (char*)d_workspace;
-  float* ref = (float*)(ws + S.total);
-  float* cand = (float*)(ws + S.total + res_bytes);
-  u32* d_words = (u32*)(ws + S.total + 2 * res_bytes);  // [0..1] max diff / max abs, [2..3] a 64-bit hash
-  Tuner tu(t, st, ws, S, d_words);
-  if (!tu.ok) return CTR_E_DEVICE;
-  try {  // the candidate lists are host containers: no exception may cross the C boundary
-    for (u32 l = 0; l + 1 < t->L.n_layers; ++l)
-      for (int op = 0; op < N_OPS; ++op)
-        if (!tu.tune_one(l, op, batch, ref, cand)) return CTR_E_DEVICE;
-  } catch (const std::bad_alloc&) {
-    return CTR_E_NOMEM;
-  } catch (...) {
-    return CTR_E_DEVICE;
-  }
-  return launch_status();
+// The tower's matrix product on its own (testing and measurement): C32[M x N] = A B.
+int ctr_mlp_gemm(int a_k_contiguous, int b_k_contiguous, const uint16_t* d_a, uint32_t lda, const uint16_t* d_b,
+                 uint32_t ldb, uint32_t m, uint32_t n, uint32_t k, float* d_c, uint32_t ldc, void* d_scratch,
+                 size_t scratch_bytes, void* hip_stream) {
+  if (!d_a || !d_b || !d_c) return CTR_E_INVAL;
+  if (m == 0 || n == 0 || k == 0 || ((m | n | k | lda | ldb | ldc) % 8u) != 0u) return CTR_E_INVAL;
+  if (lda < (a_k_contiguous ? k : m) || ldb < (b_k_contiguous ? k : n) || ldc < n) return CTR_E_INVAL;
+  if ((((uintptr_t)d_a | (uintptr_t)d_b | (uintptr_t)d_c | (uintptr_t)d_scratch) & 15) != 0) return CTR_E_INVAL;
+  GemmArgs g{};
+  g.A = d_a; g.lda = lda;
+  g.B = d_b; g.ldb = ldb;
+  g.M = m; g.N = n; g.K = k;
+  g.C32 = d_c; g.ldc = ldc;
+  g.epilogue = EPI_F32;
+  const hipError_t rc = gemm_enqueue(a_k_contiguous != 0, b_k_contiguous != 0, g, (float*)d_scratch,
+                                     d_scratch ? scratch_bytes : 0, (hipStream_t)hip_stream);
+  return rc == hipSuccess ? CTR_OK : (rc == hipErrorInvalidValue ? CTR_E_INVAL : CTR_E_DEVICE);
 }
 
 int ctr_mlp_kstep_merge(ctr_mlp* t, void* hip_stream) {

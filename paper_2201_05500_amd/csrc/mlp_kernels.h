@@ -1,5 +1,5 @@
-// Hand-written kernels of the dense tower: everything except the matrix products (those are
-// rocBLAS bf16 GEMMs on the matrix cores).
+// Element-wise and reduction kernels of the dense tower (the matrix products, with bias + ReLU and the
+// ReLU gate of back-propagated gradients fused into their epilogues, are in gemm_kernels.h).
 //
 // Paper: the train_mini-batch step of Algorithm 1 on the network of Section 2.1, and Algorithm 2
 // (k-step Adam) on the dense parameters.  bf16 rounding is nearest-even, done here by hand so that
@@ -24,21 +24,6 @@ __global__ void k_cast_bf16(const float* __restrict__ src, bf16_t* __restrict__ 
   ushort4 o;
   o.x = to_bf16(v.x); o.y = to_bf16(v.y); o.z = to_bf16(v.z); o.w = to_bf16(v.w);
   *reinterpret_cast<ushort4*>(dst + i) = o;
-}
-
-// a = bf16(relu(z + bias)), row-major [rows x H], H multiple of 4.
-__global__ void k_bias_relu_bf16(const float* __restrict__ z, const float* __restrict__ bias, u32 H, u64 n,
-                                 bf16_t* __restrict__ a) {
-  const u64 i = ((u64)blockIdx.x * BLOCK + threadIdx.x) * 4;
-  if (i >= n) return;
-  const f4 v = ldg4(z + i);
-  const f4 b = ldg4(bias + (u32)(i % H));
-  ushort4 o;
-  o.x = to_bf16(fmaxf(v.x + b.x, 0.0f));
-  o.y = to_bf16(fmaxf(v.y + b.y, 0.0f));
-  o.z = to_bf16(fmaxf(v.z + b.z, 0.0f));
-  o.w = to_bf16(fmaxf(v.w + b.w, 0.0f));
-  *reinterpret_cast<ushort4*>(a + i) = o;
 }
 
 // Output layer (width 1): logit[b] = a[b, :] . w + bias.  One wave per sample, fixed summation order.
@@ -137,21 +122,6 @@ __global__ void k_sum_f32(const float* __restrict__ x, u32 n, float* __restrict_
   if (threadIdx.x == 0) *out = part[0];
 }
 
-// Back through a hidden ReLU: dz = bf16(da * [a > 0]), 4 values per thread.
-__global__ void k_relu_bwd_bf16(const float* __restrict__ da, const bf16_t* __restrict__ a, u64 n,
-                                bf16_t* __restrict__ dz) {
-  const u64 i = ((u64)blockIdx.x * BLOCK + threadIdx.x) * 4;
-  if (i >= n) return;
-  const f4 g = ldg4(da + i);
-  const ushort4 av = *reinterpret_cast<const ushort4*>(a + i);
-  ushort4 o;
-  o.x = to_bf16(from_bf16(av.x) > 0.0f ? g.x : 0.0f);
-  o.y = to_bf16(from_bf16(av.y) > 0.0f ? g.y : 0.0f);
-  o.z = to_bf16(from_bf16(av.z) > 0.0f ? g.z : 0.0f);
-  o.w = to_bf16(from_bf16(av.w) > 0.0f ? g.w : 0.0f);
-  *reinterpret_cast<ushort4*>(dz + i) = o;
-}
-
 // Initial parameters of every replica: weights from the integer recipe of the row initialiser with
 // key = layer << 48 | index, scaled to a standard deviation of sqrt(2 / fan_in); biases 0; m = 0;
 // v = shared v = eps (Algorithm 2, "Initialize"); bf16 copies of the parameters.
@@ -227,68 +197,6 @@ __global__ void k_dense_merge(float* __restrict__ params, const float* __restric
     params[j * stride + i] = xb;
     pb[j * stride + i] = hb;
   }
-}
-
-// ---------------------------------------------------------------- helpers of the kernel search
-
-// Bounded pseudo-random bf16 values in (-1/16, 1/16): operands for timing and checking a product.
-__global__ void k_fill_pattern_bf16(bf16_t* __restrict__ dst, u64 n, u32 seed) {
-  for (u64 i = (u64)blockIdx.x * BLOCK + threadIdx.x; i < n; i += (u64)gridDim.x * BLOCK) {
-    u32 x = (u32)i * 2654435761u + seed;
-    x ^= x >> 15; x *= 2246822519u; x ^= x >> 13;
-    dst[i] = to_bf16(((int)(x & 0xFFFFu) - 32768) * (1.0f / 524288.0f));
-  }
-}
-
-// out[0] = max |a - b|, out[1] = max |a| as float bit patterns (non-negative floats order like
-// unsigned integers); a NaN anywhere sets out[0] to the pattern of +inf.  out[] zeroed by the caller.
-__global__ void k_max_diff(const float* __restrict__ a, const float* __restrict__ b, u64 n, u32* __restrict__ out) {
-  float md = 0.0f, ma = 0.0f;
-  for (u64 i = (u64)blockIdx.x * BLOCK + threadIdx.x; i < n; i += (u64)gridDim.x * BLOCK) {
-    const float x = a[i], y = b[i];
-    float d = fabsf(x - y);
-    if (!(d == d)) d = __uint_as_float(0x7F800000u);
-    md = fmaxf(md, d);
-    ma = fmaxf(ma, fabsf(x));
-  }
-  for (int off = WAVE / 2; off > 0; off >>= 1) {
-    md = fmaxf(md, __shfl_xor(md, off, WAVE));
-    ma = fmaxf(ma, __shfl_xor(ma, off, WAVE));
-  }
-  if (lane_id() == 0) {
-    atomicMax(&out[0], __float_as_uint(md));
-    atomicMax(&out[1], __float_as_uint(ma));
-  }
-}
-
-// k_max_diff for two bf16 arrays.
-__global__ void k_max_diff_bf16(const bf16_t* __restrict__ a, const bf16_t* __restrict__ b, u64 n,
-                                u32* __restrict__ out) {
-  float md = 0.0f, ma = 0.0f;
-  for (u64 i = (u64)blockIdx.x * BLOCK + threadIdx.x; i < n; i += (u64)gridDim.x * BLOCK) {
-    const float x = from_bf16(a[i]), y = from_bf16(b[i]);
-    float d = fabsf(x - y);
-    if (!(d == d)) d = __uint_as_float(0x7F800000u);
-    md = fmaxf(md, d);
-    ma = fmaxf(ma, fabsf(x));
-  }
-  for (int off = WAVE / 2; off > 0; off >>= 1) {
-    md = fmaxf(md, __shfl_xor(md, off, WAVE));
-    ma = fmaxf(ma, __shfl_xor(ma, off, WAVE));
-  }
-  if (lane_id() == 0) {
-    atomicMax(&out[0], __float_as_uint(md));
-    atomicMax(&out[1], __float_as_uint(ma));
-  }
-}
-
-// Order-independent 64-bit sum of (bit pattern x per-index odd multiplier): equal for equal contents.
-__global__ void k_hash_bits(const float* __restrict__ a, u64 n, unsigned long long* __restrict__ out) {
-  u64 h = 0;
-  for (u64 i = (u64)blockIdx.x * BLOCK + threadIdx.x; i < n; i += (u64)gridDim.x * BLOCK)
-    h += (u64)__float_as_uint(a[i]) * ((i * 0x9E3779B97F4A7C15ull) | 1ull);
-  for (int off = WAVE / 2; off > 0; off >>= 1) h += __shfl_xor(h, off, WAVE);
-  if (lane_id() == 0) atomicAdd(out, (unsigned long long)h);
 }
 
 }  // namespace ctr

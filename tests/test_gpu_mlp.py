@@ -168,24 +168,16 @@ def test_bf16_input_equals_fp32_input_bit_for_bit():
         assert np.array_equal(ea[k], eb[k]), k
 
 
-@pytest.mark.parametrize("fallback", [False, True])
-@pytest.mark.parametrize("tuned", [False, True])
-def test_bf16_gradient_output(monkeypatch, fallback, tuned):
+def test_bf16_gradient_output():
     """ctr_mlp_step_bf16_grad_bf16: the gradient of the pooled input rounded to bf16 on the way out of the first
-    layer's product (vendor kernel, searched kernel, or the rocBLAS fallback).  Against the oracle's gradient
-    rounded the same way (a value on a rounding boundary may land on the neighbouring bf16 value: 2^-8 relative,
-    inside the element bound); the tower's own state is bit for bit that of the fp32-gradient step."""
+    layer's product.  Against the oracle's gradient rounded the same way (a value on a rounding boundary may land
+    on the neighbouring bf16 value: 2^-8 relative, inside the element bound); the tower's own state is bit for bit
+    that of the fp32-gradient step, and the bf16 gradient is the fp32 one rounded (same sums, same order)."""
     import torch
-    if fallback:
-        monkeypatch.setenv("CTR_MLP_NO_HIPBLASLT", "1")
     rng = np.random.default_rng(41)
     in_dim, hidden, B = 384, [256, 64], 512
     ga, o = _pair(in_dim, hidden)
     gb, _ = _pair(in_dim, hidden)
-    if fallback:
-        monkeypatch.delenv("CTR_MLP_NO_HIPBLASLT")
-    if tuned:
-        assert ga.tune(B) == 0 and gb.tune(B) == 0
     for s in range(3):
         pooled, labels, dp, dl = _batch(rng, B, in_dim)
         dpb = dp.to(torch.bfloat16)
@@ -193,20 +185,16 @@ def test_bf16_gradient_output(monkeypatch, fallback, tuned):
         sa, lossa, gpa = ga.step(0, dpb, dl)
         sb, lossb, gpb = gb.step(0, dpb, dl, grad_pooled=g16)
         assert sa == 0 and sb == 0 and gpb.dtype == torch.bfloat16 and gpb.data_ptr() == g16.data_ptr()
-        if not tuned:                                            # a search may pick differently for the twin
-            assert torch.equal(lossa, lossb)
+        assert torch.equal(lossa, lossb)
+        assert torch.equal(gpb, gpa.to(torch.bfloat16))
         oloss, ogp = o.step(0, pooled, labels, grad_bf16=True)
         assert abs(float(lossb.cpu()[0]) - float(oloss)) <= 1e-4 * max(1.0, float(oloss))
         assert not (ogp.view(np.uint32) & 0xFFFF).any()
         got = gpb.to(torch.float32).cpu().numpy()
         close_rows(got, ogp, "bf16 grad of pooled step %d" % s, in_dim)
-        # against the fp32 gradient of the twin tower: one bf16 rounding apart (2^-9 relative), unless the two
-        # products took kernels with different summation orders, which the row criteria allow for
-        close_rows(got, gpa.cpu().numpy(), "bf16 against fp32 gradient step %d" % s, in_dim)
-        if not tuned:
-            ea, eb = ga.export(), gb.export()
-            for k in ("params", "m", "v"):
-                assert np.array_equal(ea[k], eb[k]), k
+        ea, eb = ga.export(), gb.export()
+        for k in ("params", "m", "v"):
+            assert np.array_equal(ea[k], eb[k]), k
     close_enough(gb.export()["params"], o.params[0], "parameters", rtol=1e-3, norm_tol=1e-3)
 
 
@@ -228,48 +216,62 @@ def test_bf16_gradient_output_argument_checks():
     torch.cuda.synchronize()
 
 
-def test_kernel_search_keeps_the_results():
-    """ctr_mlp_tune may swap the product kernels: outputs stay within the accumulation-order tolerance of the
-    untuned tower's, parity with the oracle holds, and the tuned tower repeats its results bit for bit."""
+def _own_gemm(a_kc, b_kc, A, B, M, N, K, scratch=None):
+    """C = A B through ctr_mlp_gemm; A, B: bf16 device tensors in the layouts the flags name."""
     import torch
-    rng = np.random.default_rng(21)
-    in_dim, hidden, B = 512, [256, 128], 1024
-    ga, o = _pair(in_dim, hidden)
-    gb, _ = _pair(in_dim, hidden)
-    assert gb.tune(B) == 0
-    assert np.array_equal(gb.export()["params"], ga.export()["params"])          # the search leaves the state alone
-    for s in range(2):
-        pooled, labels, dp, dl = _batch(rng, B, in_dim)
-        st1, l1 = gb.forward(0, dp)
-        st2, l2 = gb.forward(0, dp)
-        assert st1 == 0 and st2 == 0 and torch.equal(l1, l2)                     # the same kernels again: the same bits
-        sa, lossa, gpa = ga.step(0, dp, dl)
-        sb, lossb, gpb = gb.step(0, dp, dl)
-        assert sa == 0 and sb == 0
-        oloss, ogp = o.step(0, pooled, labels)
-        assert abs(float(lossb.cpu()[0]) - float(oloss)) <= 1e-4 * max(1.0, float(oloss))
-        close_rows(gpb.cpu().numpy(), ogp, "tuned grad of pooled step %d" % s, in_dim)
-        close_rows(gpb.cpu().numpy(), gpa.cpu().numpy(), "tuned vs untuned step %d" % s, in_dim)
-    close_enough(gb.export()["params"], o.params[0], "tuned parameters", rtol=1e-3, norm_tol=1e-3)
+    from paper_2201_05500_amd import binding_mlp as BM
+    Cm = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    st = BM.ctr_mlp_gemm(a_kc, b_kc, A.data_ptr(), A.shape[1], B.data_ptr(), B.shape[1], M, N, K, Cm.data_ptr(), N,
+                         scratch.data_ptr() if scratch is not None else None,
+                         scratch.numel() * 4 if scratch is not None else 0, torch.cuda.current_stream().cuda_stream)
+    return st, Cm
 
 
-def test_rocblas_fallback_path(monkeypatch):
-    """With hipBLASLt switched off at creation the products run through rocBLAS: same parity, and a kernel
-    search has nothing to do."""
-    monkeypatch.setenv("CTR_MLP_NO_HIPBLASLT", "1")
-    rng = np.random.default_rng(31)
-    in_dim, hidden, B = 192, [128, 64], 256
-    g, o = _pair(in_dim, hidden)
-    monkeypatch.delenv("CTR_MLP_NO_HIPBLASLT")
-    assert g.tune(B) == 0
-    for s in range(2):
-        pooled, labels, dp, dl = _batch(rng, B, in_dim)
-        st, loss, gp = g.step(0, dp, dl)
-        assert st == 0
-        oloss, ogp = o.step(0, pooled, labels)
-        assert abs(float(loss.cpu()[0]) - float(oloss)) <= 1e-4 * max(1.0, float(oloss))
-        close_rows(gp.cpu().numpy(), ogp, "fallback grad of pooled step %d" % s, in_dim)
-    close_enough(g.export()["params"], o.params[0], "fallback parameters", rtol=1e-3, norm_tol=1e-3)
+@pytest.mark.parametrize("a_kc,b_kc", [(True, False), (False, False), (True, True), (False, True)])
+@pytest.mark.parametrize("M,N,K", [(264, 200, 136), (8, 8, 8), (256, 256, 64), (520, 776, 328), (512, 256, 4096),
+                                   (1032, 24, 2056)])
+def test_own_matrix_product_against_a_vendor_product(a_kc, b_kc, M, N, K):
+    """The library's MFMA kernel against torch.matmul (a vendor GEMM, here only as a cross-check) on the same bf16
+    operands, every operand layout, sizes with ragged tiles in every dimension, a contraction that is split, and a
+    contraction whose length is no multiple of the 64-wide step.  Both accumulate bf16 products in fp32; the
+    orders differ, so the bound is the accumulation error: 1e-3 of the largest element."""
+    import torch
+    gen = torch.Generator(device="cuda").manual_seed(M * 31 + N * 7 + K)
+    Af = torch.randn((M, K), device="cuda", generator=gen)
+    Bf = torch.randn((K, N), device="cuda", generator=gen)
+    A16, B16 = Af.to(torch.bfloat16), Bf.to(torch.bfloat16)
+    A_store = A16.contiguous() if a_kc else A16.t().contiguous()          # [M, K] or [K, M]
+    B_store = B16.t().contiguous() if b_kc else B16.contiguous()          # [N, K] or [K, N]
+    scratch = torch.empty(8 << 20, dtype=torch.float32, device="cuda")
+    st, got = _own_gemm(a_kc, b_kc, A_store, B_store, M, N, K, scratch)
+    assert st == 0
+    ref = A16.double() @ B16.double()                                     # exact products, fp64 sums
+    err = (got.double() - ref).abs().max().item()
+    assert err <= 1e-3 * ref.abs().max().item() + 1e-6, (err, ref.abs().max().item())
+    vendor = (A16 @ B16).float()                                          # bf16 output: one more rounding
+    assert (got - vendor).abs().max().item() <= 2.0 ** -7 * ref.abs().max().item()
+    # the same call again gives the same bits (fixed summation order, also across a split contraction)
+    st2, again = _own_gemm(a_kc, b_kc, A_store, B_store, M, N, K, scratch)
+    assert st2 == 0 and torch.equal(got, again)
+    # without scratch the contraction is not split: same result to accumulation order
+    st3, unsplit = _own_gemm(a_kc, b_kc, A_store, B_store, M, N, K, None)
+    assert st3 == 0 and (unsplit - got).abs().max().item() <= 1e-3 * ref.abs().max().item() + 1e-6
+
+
+def test_own_matrix_product_argument_checks():
+    import torch
+    from paper_2201_05500_amd import binding as B
+    from paper_2201_05500_amd import binding_mlp as BM
+    a = torch.zeros((16, 16), dtype=torch.bfloat16, device="cuda")
+    c = torch.zeros((16, 16), dtype=torch.float32, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    ok = lambda **kw: BM.ctr_mlp_gemm(**dict(dict(a_k_contiguous=True, b_k_contiguous=True, d_a=a.data_ptr(), lda=16,
+                                                  d_b=a.data_ptr(), ldb=16, m=16, n=16, k=16, d_c=c.data_ptr(), ldc=16,
+                                                  d_scratch=None, scratch_bytes=0, stream=st), **kw))
+    assert ok() == B.CTR_OK
+    assert ok(m=12) == B.CTR_E_INVAL and ok(k=0) == B.CTR_E_INVAL and ok(lda=8) == B.CTR_E_INVAL
+    assert ok(d_a=None) == B.CTR_E_INVAL and ok(d_c=c.data_ptr() + 4) == B.CTR_E_INVAL and ok(ldc=8) == B.CTR_E_INVAL
+    torch.cuda.synchronize()
 
 
 def layerwise_close(gpu, ref, shapes, what, tol):
