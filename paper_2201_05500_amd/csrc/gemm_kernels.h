@@ -34,6 +34,9 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef u32 u32x4 __attribute__((ext_vector_type(4)));  // 16 bytes in flight between memory, registers and LDS
 
+#ifndef CTR_GEMM_FETCH_AFTER_STAGE
+#define CTR_GEMM_FETCH_AFTER_STAGE 0
+#endif
 constexpr u32 GEMM_BM = 256, GEMM_BN = 256, GEMM_BK = 64;
 constexpr u32 GEMM_TILE_BYTES = GEMM_BM * GEMM_BK * 2;  // one operand tile in LDS: 32 KB
 constexpr u32 GEMM_LDS_BYTES = 4 * GEMM_TILE_BYTES;     // A and B, two buffers each: 128 KB
@@ -339,6 +342,27 @@ k_gemm_bf16(const bf16_t* __restrict__ Ap, const bf16_t* __restrict__ Bp, GemmAr
   const bool last_partial = n_steps > 0 && k_begin + n_steps * GEMM_BK > g.K;
   const u32 n_loop = n_steps - (last_partial ? 1u : 0u);  // steps whose tiles lie inside K
   u32 s = 0;
+#if CTR_GEMM_FETCH_AFTER_STAGE
+  // variant: the registers are refilled as soon as they have been staged (before the barrier)
+  if (n_loop > 1) {
+    gemm_fetch<A_KC>(Ap, g.lda, k_begin + GEMM_BK, offa, ra);
+    gemm_fetch<B_KC>(Bp, g.ldb, k_begin + GEMM_BK, offb, rb);
+  }
+  for (; s + 1 < n_loop; ++s) {
+    const u32 buf = s & 1u;
+    const u32 k_next = k_begin + (s + 1) * GEMM_BK;
+    gemm_step<A_KC, B_KC, false>(gemm_lds + buf * GEMM_TILE_BYTES + a_base,
+                                 gemm_lds + (2 + buf) * GEMM_TILE_BYTES + b_base, frag_half, frag_swz, acc, Ap, Bp, g, offa,
+                                 offb, 0u, 0u, ra, rb);
+    gemm_stage<A_KC>(gemm_lds + (buf ^ 1u) * GEMM_TILE_BYTES, ra, false, g.K, k_next);
+    gemm_stage<B_KC>(gemm_lds + (2 + (buf ^ 1u)) * GEMM_TILE_BYTES, rb, false, g.K, k_next);
+    if (s + 2 < n_loop) {
+      gemm_fetch<A_KC>(Ap, g.lda, k_next + GEMM_BK, offa, ra);
+      gemm_fetch<B_KC>(Bp, g.ldb, k_next + GEMM_BK, offb, rb);
+    }
+    __syncthreads();
+  }
+#else
   for (; s + 1 < n_loop; ++s) {
     const u32 buf = s & 1u;
     const u32 k_next = k_begin + (s + 1) * GEMM_BK;
@@ -349,6 +373,7 @@ k_gemm_bf16(const bf16_t* __restrict__ Ap, const bf16_t* __restrict__ Bp, GemmAr
     gemm_stage<B_KC>(gemm_lds + (2 + (buf ^ 1u)) * GEMM_TILE_BYTES, rb, false, g.K, k_next);
     __syncthreads();
   }
+#endif
   if (last_partial && n_steps > 1) {  // step s = n_steps - 2 with the partial tile behind it
     const u32 buf = s & 1u;
     const u32 k_next = k_begin + (s + 1) * GEMM_BK;

@@ -163,8 +163,10 @@ def test_full_step_config_one_step(capsys, grad_bf16):
     _say(capsys, "oracle tower done, loss", float(oloss))
     assert abs(float(loss.cpu()[0]) - float(oloss)) <= 1e-4 * max(1.0, float(oloss))
     gp_h = gp.to(torch.float32).cpu().numpy()                           # widening a bf16 value is exact
+    from tests.test_gpu_mlp import OBSERVED
     n_round, n_mask = close_rows(gp_h, ogp, "gradient of the pooled input", in_dim)
-    _say(capsys, "gradient rows with rounding cascades:", n_round, "with a flipped mask:", n_mask, "of", w.batch)
+    _say(capsys, "gradient rows with rounding cascades:", n_round, "with a flipped mask:", n_mask, "of", w.batch,
+         "| worst row error %.3g, norm-wise error of the other rows %.3g" % OBSERVED["gradient of the pooled input"][2:4])
     e = gm.export()
     close_enough(e["params"], om.params[0], "tower parameters", rtol=1e-3, norm_tol=1e-3)
     close_enough(e["m"], om.m[0], "tower first moment")

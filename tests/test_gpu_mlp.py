@@ -29,8 +29,11 @@ def close_enough(gpu, ref, what, rtol=1e-2, frac_atol=2e-3, norm_tol=2e-3, outli
     assert nerr <= norm_tol, "%s: norm-wise error %.3g" % (what, nerr)
 
 
-def close_rows(gpu, ref, what, row_len, rtol=1e-2, frac_atol=2e-3, round_rows=0.05, round_err=1e-2,
-               mask_rows=2e-2, mask_err=0.6, norm_tol=3e-3):
+OBSERVED = {}   # what -> (rows off, rows with a flipped mask, worst row error, norm-wise error of the rest)
+
+
+def close_rows(gpu, ref, what, row_len, rtol=1e-2, frac_atol=2e-3, round_rows=0.04, round_err=1e-2,
+               mask_rows=1.2e-2, mask_err=0.3, norm_tol=1.5e-3):
     """Per-sample outputs (one row per sample) at sizes where rare rounding events are certain to occur somewhere.
     A back-propagated hidden gradient that sits on a bf16 rounding boundary may round the other way on the GPU
     (2^-8 relative on that element); everything downstream of it in that sample then moves by up to about
@@ -43,7 +46,10 @@ def close_rows(gpu, ref, what, row_len, rtol=1e-2, frac_atol=2e-3, round_rows=0.
     its spread, and one of 512 of them lies that close to zero with probability ~0.1: about 1 % of the samples.
     So: rows with any element outside atol + rtol |ref| may be at
     most `round_rows` of all rows; of those, rows with a norm-wise error above `round_err` at most `mask_rows`
-    (but one is always allowed), none above `mask_err`; and all the other rows together within `norm_tol` norm-wise."""
+    (but one is always allowed), none above `mask_err`; and all the other rows together within `norm_tol` norm-wise.
+    The bars are what the full-size step shows (3.2 % of the rows off, 0.71 % with a flipped mask, worst row error 0.225, the other rows 5e-4 norm-wise)
+    plus a margin of a quarter to a half; the observed figures of every call are kept in OBSERVED and printed by
+    the full-size tests, so that a change in them is visible."""
     gpu = np.asarray(gpu, np.float64).reshape(-1, row_len)
     ref = np.asarray(ref, np.float64).reshape(-1, row_len)
     assert gpu.shape == ref.shape, what
@@ -52,8 +58,11 @@ def close_rows(gpu, ref, what, row_len, rtol=1e-2, frac_atol=2e-3, round_rows=0.
     diff = gpu - ref
     badrow = (np.abs(diff) > frac_atol * rms + rtol * np.abs(ref)).any(axis=1)
     rowerr = np.linalg.norm(diff, axis=1) / (np.linalg.norm(ref, axis=1) + 1e-30)
-    assert badrow.mean() <= round_rows, "%s: %d of %d rows off" % (what, int(badrow.sum()), n)
     n_mask = int((rowerr > round_err).sum())
+    keep0 = rowerr <= round_err
+    OBSERVED[what] = (int(badrow.sum()), n_mask, float(rowerr.max()),
+                      float(np.linalg.norm(diff[keep0]) / (np.linalg.norm(ref[keep0]) + 1e-30)), n)
+    assert badrow.sum() <= max(1, int(round_rows * n)), "%s: %d of %d rows off" % (what, int(badrow.sum()), n)
     assert n_mask <= max(1, int(mask_rows * n)), "%s: %d of %d rows off by more than %g" % (what, n_mask, n, round_err)
     assert rowerr.max() <= mask_err, "%s: worst row error %.3g" % (what, rowerr.max())
     keep = rowerr <= round_err                      # the flipped-mask rows are bounded above, one by one
