@@ -432,7 +432,7 @@ __global__ void k_collect_rows(const DevHeader* hdr, const Slot* __restrict__ sl
 // inside a batch of 4 consecutive occurrences and binary64 across batches, rounded once
 // (error <= 3 * 2^-24 * sum |x|).  A row is rf floats and starts with x.
 #ifndef CTR_POOL_NT_OUT
-#define CTR_POOL_NT_OUT 0  // 1: the pooled output (written once, read by the next stage) leaves with the non-temporal hint
+#define CTR_POOL_NT_OUT 1  // the pooled output (written once, read by the next stage) leaves with the non-temporal hint
 #endif
 constexpr int POOL_NS = 2;      // segments a group works on at once
 constexpr int POOL_ROUNDS = 2;  // such pairs per group

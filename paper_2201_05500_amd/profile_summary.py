@@ -71,6 +71,8 @@ def main():
     ap.add_argument("write_dir")
     ap.add_argument("--note", default="")
     ap.add_argument("--command", default="", help="the bench.py command line that was profiled")
+    ap.add_argument("--steps", type=int, default=0,
+                    help="steps the profiled command ran (warm-up + timed); default: the launches of the push kernel")
     a = ap.parse_args()
     sys.path.insert(0, ROOT)
     from paper_2201_05500_amd.build import source_hash
@@ -85,8 +87,8 @@ def main():
         lines.append("  rocprofv3 --kernel-trace --stats --output-format csv -d %s -- %s" % (a.trace_dir, a.command))
         lines.append("  rocprofv3 --pmc FETCH_SIZE --output-format csv -d %s -- %s" % (a.fetch_dir, a.command))
         lines.append("  rocprofv3 --pmc WRITE_SIZE --output-format csv -d %s -- %s" % (a.write_dir, a.command))
-        lines.append("  python3 -m paper_2201_05500_amd.profile_summary %s %s %s %s" % (a.name, a.trace_dir, a.fetch_dir,
-                                                                                     a.write_dir))
+        lines.append("  python3 -m paper_2201_05500_amd.profile_summary %s %s %s %s%s" % (
+            a.name, a.trace_dir, a.fetch_dir, a.write_dir, (" --steps %d" % a.steps) if a.steps else ""))
     lines.append("")
     lines.append("== rocprofv3 --kernel-trace --stats (the library's kernels; GEMM kernels of the tower if any)")
     lines.append("%-72s %6s %10s %10s %10s %7s" % ("kernel", "calls", "avg_us", "min_us", "max_us", "pct"))
@@ -108,7 +110,7 @@ def main():
     lines.append("== rocprofv3 --pmc FETCH_SIZE / --pmc WRITE_SIZE (KiB per dispatch as counted; LAST dispatch of each "
                  "kernel = the steady-most step; GB = scaled)")
     lines.append("%-72s %6s %14s %14s %9s" % ("kernel", "calls", "FETCH_KiB", "WRITE_KiB", "GB"))
-    steps = max([len(v) for k, v in F.items() if "k_push_span" in k] or [1])
+    steps = a.steps or max([len(v) for k, v in F.items() if "k_push_span<" in k] or [1])
     rec = {"kernels": {}, "step": {"fetch_KiB": 0.0, "write_KiB": 0.0}}
     for k, vs in F.items():
         if not ours(k) or COPY_KERNEL in k or "k_table_clear" in k:
