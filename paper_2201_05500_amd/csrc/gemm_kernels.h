@@ -34,9 +34,6 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef u32 u32x4 __attribute__((ext_vector_type(4)));  // 16 bytes in flight between memory, registers and LDS
 
-#ifndef CTR_GEMM_FETCH_AFTER_STAGE
-#define CTR_GEMM_FETCH_AFTER_STAGE 0
-#endif
 constexpr u32 GEMM_BM = 256, GEMM_BN = 256, GEMM_BK = 64;
 constexpr u32 GEMM_TILE_BYTES = GEMM_BM * GEMM_BK * 2;  // one operand tile in LDS: 32 KB
 constexpr u32 GEMM_LDS_BYTES = 4 * GEMM_TILE_BYTES;     // A and B, two buffers each: 128 KB
@@ -284,7 +281,11 @@ __device__ __forceinline__ void gemm_step(const char* la, const char* lb, u32 fr
 
 // The operand pointers are kernel parameters of their own (not members of the argument block), so that
 // the compiler knows them to be global memory.
-template <bool A_KC, bool B_KC>
+// EARLY: the registers are refilled with the next tiles as soon as they have been staged (before the
+// barrier, all 16 loads at once) instead of during the first half of the following step.  Long
+// contractions gain from it (the requests get the barrier and the fragment reads as extra time), short
+// ones lose (measured: 300 and 64 steps per work item -5 % and -2 %, 16 steps +10 %); the host picks.
+template <bool A_KC, bool B_KC, bool EARLY>
 __global__ void __launch_bounds__(256, 1)
 k_gemm_bf16(const bf16_t* __restrict__ Ap, const bf16_t* __restrict__ Bp, GemmArgs g) {
   extern __shared__ __align__(16) char gemm_lds[];
@@ -342,38 +343,37 @@ k_gemm_bf16(const bf16_t* __restrict__ Ap, const bf16_t* __restrict__ Bp, GemmAr
   const bool last_partial = n_steps > 0 && k_begin + n_steps * GEMM_BK > g.K;
   const u32 n_loop = n_steps - (last_partial ? 1u : 0u);  // steps whose tiles lie inside K
   u32 s = 0;
-#if CTR_GEMM_FETCH_AFTER_STAGE
-  // variant: the registers are refilled as soon as they have been staged (before the barrier)
-  if (n_loop > 1) {
-    gemm_fetch<A_KC>(Ap, g.lda, k_begin + GEMM_BK, offa, ra);
-    gemm_fetch<B_KC>(Bp, g.ldb, k_begin + GEMM_BK, offb, rb);
-  }
-  for (; s + 1 < n_loop; ++s) {
-    const u32 buf = s & 1u;
-    const u32 k_next = k_begin + (s + 1) * GEMM_BK;
-    gemm_step<A_KC, B_KC, false>(gemm_lds + buf * GEMM_TILE_BYTES + a_base,
-                                 gemm_lds + (2 + buf) * GEMM_TILE_BYTES + b_base, frag_half, frag_swz, acc, Ap, Bp, g, offa,
-                                 offb, 0u, 0u, ra, rb);
-    gemm_stage<A_KC>(gemm_lds + (buf ^ 1u) * GEMM_TILE_BYTES, ra, false, g.K, k_next);
-    gemm_stage<B_KC>(gemm_lds + (2 + (buf ^ 1u)) * GEMM_TILE_BYTES, rb, false, g.K, k_next);
-    if (s + 2 < n_loop) {
-      gemm_fetch<A_KC>(Ap, g.lda, k_next + GEMM_BK, offa, ra);
-      gemm_fetch<B_KC>(Bp, g.ldb, k_next + GEMM_BK, offb, rb);
+  if constexpr (EARLY) {
+    if (n_loop > 1) {
+      gemm_fetch<A_KC>(Ap, g.lda, k_begin + GEMM_BK, offa, ra);
+      gemm_fetch<B_KC>(Bp, g.ldb, k_begin + GEMM_BK, offb, rb);
     }
-    __syncthreads();
+    for (; s + 1 < n_loop; ++s) {
+      const u32 buf = s & 1u;
+      const u32 k_next = k_begin + (s + 1) * GEMM_BK;
+      gemm_step<A_KC, B_KC, false>(gemm_lds + buf * GEMM_TILE_BYTES + a_base,
+                                   gemm_lds + (2 + buf) * GEMM_TILE_BYTES + b_base, frag_half, frag_swz, acc, Ap, Bp, g,
+                                   offa, offb, 0u, 0u, ra, rb);
+      gemm_stage<A_KC>(gemm_lds + (buf ^ 1u) * GEMM_TILE_BYTES, ra, false, g.K, k_next);
+      gemm_stage<B_KC>(gemm_lds + (2 + (buf ^ 1u)) * GEMM_TILE_BYTES, rb, false, g.K, k_next);
+      if (s + 2 < n_loop) {
+        gemm_fetch<A_KC>(Ap, g.lda, k_next + GEMM_BK, offa, ra);
+        gemm_fetch<B_KC>(Bp, g.ldb, k_next + GEMM_BK, offb, rb);
+      }
+      __syncthreads();
+    }
+  } else {
+    for (; s + 1 < n_loop; ++s) {
+      const u32 buf = s & 1u;
+      const u32 k_next = k_begin + (s + 1) * GEMM_BK;
+      gemm_step<A_KC, B_KC, true>(gemm_lds + buf * GEMM_TILE_BYTES + a_base,
+                                  gemm_lds + (2 + buf) * GEMM_TILE_BYTES + b_base, frag_half, frag_swz, acc, Ap, Bp, g,
+                                  offa, offb, k_next, k_next, ra, rb);
+      gemm_stage<A_KC>(gemm_lds + (buf ^ 1u) * GEMM_TILE_BYTES, ra, false, g.K, k_next);
+      gemm_stage<B_KC>(gemm_lds + (2 + (buf ^ 1u)) * GEMM_TILE_BYTES, rb, false, g.K, k_next);
+      __syncthreads();
+    }
   }
-#else
-  for (; s + 1 < n_loop; ++s) {
-    const u32 buf = s & 1u;
-    const u32 k_next = k_begin + (s + 1) * GEMM_BK;
-    gemm_step<A_KC, B_KC, true>(gemm_lds + buf * GEMM_TILE_BYTES + a_base,
-                                gemm_lds + (2 + buf) * GEMM_TILE_BYTES + b_base, frag_half, frag_swz, acc, Ap, Bp, g, offa,
-                                offb, k_next, k_next, ra, rb);
-    gemm_stage<A_KC>(gemm_lds + (buf ^ 1u) * GEMM_TILE_BYTES, ra, false, g.K, k_next);
-    gemm_stage<B_KC>(gemm_lds + (2 + (buf ^ 1u)) * GEMM_TILE_BYTES, rb, false, g.K, k_next);
-    __syncthreads();
-  }
-#endif
   if (last_partial && n_steps > 1) {  // step s = n_steps - 2 with the partial tile behind it
     const u32 buf = s & 1u;
     const u32 k_next = k_begin + (s + 1) * GEMM_BK;
@@ -465,21 +465,29 @@ inline hipError_t gemm_enqueue(bool a_kc, bool b_kc, GemmArgs g, float* partial,
   g.partial = partial;
   const u32 grid = p.tiles_m * p.tiles_n * p.n_split;
   hipError_t rc = hipSuccess;
-#define CTR_GEMM_LAUNCH(AK, BK_)                                                                                  \
+#define CTR_GEMM_LAUNCH(AK, BK_, EA)                                                                              \
   do {                                                                                                            \
     static bool prepared = false; /* LDS beyond 64 KB has to be asked for once per kernel */                      \
     if (!prepared) {                                                                                              \
-      rc = hipFuncSetAttribute((const void*)k_gemm_bf16<AK, BK_>, hipFuncAttributeMaxDynamicSharedMemorySize,     \
+      rc = hipFuncSetAttribute((const void*)k_gemm_bf16<AK, BK_, EA>, hipFuncAttributeMaxDynamicSharedMemorySize, \
                                (int)GEMM_LDS_BYTES);                                                              \
       if (rc != hipSuccess) return rc;                                                                            \
       prepared = true;                                                                                            \
     }                                                                                                             \
-    hipLaunchKernelGGL((k_gemm_bf16<AK, BK_>), dim3(grid), dim3(BLOCK), GEMM_LDS_BYTES, st, g.A, g.B, g);                  \
+    hipLaunchKernelGGL((k_gemm_bf16<AK, BK_, EA>), dim3(grid), dim3(BLOCK), GEMM_LDS_BYTES, st, g.A, g.B, g);     \
   } while (0)
-  if (a_kc && b_kc) CTR_GEMM_LAUNCH(true, true);
-  else if (a_kc) CTR_GEMM_LAUNCH(true, false);
-  else if (b_kc) CTR_GEMM_LAUNCH(false, true);
-  else CTR_GEMM_LAUNCH(false, false);
+  const bool early = p.k_per_split / GEMM_BK >= 32;  // steps per work item
+  const int which = (a_kc ? 4 : 0) | (b_kc ? 2 : 0) | (early ? 1 : 0);
+  switch (which) {
+    case 7: CTR_GEMM_LAUNCH(true, true, true); break;
+    case 6: CTR_GEMM_LAUNCH(true, true, false); break;
+    case 5: CTR_GEMM_LAUNCH(true, false, true); break;
+    case 4: CTR_GEMM_LAUNCH(true, false, false); break;
+    case 3: CTR_GEMM_LAUNCH(false, true, true); break;
+    case 2: CTR_GEMM_LAUNCH(false, true, false); break;
+    case 1: CTR_GEMM_LAUNCH(false, false, true); break;
+    default: CTR_GEMM_LAUNCH(false, false, false); break;
+  }
 #undef CTR_GEMM_LAUNCH
   if (g.n_split > 1) {
     const u64 mn = (u64)g.M * g.N;

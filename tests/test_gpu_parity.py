@@ -300,6 +300,38 @@ def test_workspace_sized_once_for_the_largest_batch_serves_smaller_ones():
     torch.cuda.synchronize()
 
 
+def test_merge_counters_and_copy_kernel():
+    """The measurement aids: ctr_merge_stats counts the rows a merge averaged and the deferred steps it applied;
+    ctr_stream_copy copies."""
+    import torch
+    from paper_2201_05500_amd import binding as B
+    D, W = 8, 3
+    gt, ot = _tables(256, D, W=W, kstep=True)
+    assert gt.merge_stats() == (0, 0)
+    # replica 0 touches keys {1, 2, 3} locally; replicas 1 and 2 touch {3, 4} on a merge step
+    for j, keys, mode in ((0, [1, 2, 3], O.STEP_LOCAL), (1, [3, 4], O.STEP_MERGE_PENDING), (2, [4, 3], O.STEP_MERGE_PENDING)):
+        bn = _manual_batch(keys, [0, len(keys)], D)
+        run_step(gt, ot, to_device(bn), bn, replica=j, mode=mode)
+    assert gt.kstep_merge() == B.CTR_OK and ot.kstep_merge() == 0
+    assert gt.merge_stats() == (4, 4)            # rows of keys 1..4; pending: (3, r1), (4, r1), (4, r2), (3, r2)
+    assert gt.kstep_merge() == B.CTR_OK          # nothing touched since: nothing merged
+    assert gt.merge_stats() == (4, 4)
+    compare_tables(gt, ot, what="after the counted merge")
+    src = torch.arange(1 << 20, dtype=torch.float32, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    for nt in (False, True):
+        dst = torch.zeros_like(src)
+        assert B.ctr_stream_copy(dst.data_ptr(), src.data_ptr(), src.numel() * 4, nt, st) == B.CTR_OK
+        assert torch.equal(dst, src)
+        part = torch.zeros(1000, dtype=torch.float32, device="cuda")          # a size that is no multiple of the stride
+        assert B.ctr_stream_copy(part.data_ptr(), src.data_ptr(), 4000, nt, st) == B.CTR_OK
+        assert torch.equal(part, src[:1000])
+    assert B.ctr_stream_copy(dst.data_ptr(), src.data_ptr(), 1000 * 4 + 4, False, st) == B.CTR_E_INVAL   # not 16-byte units
+    assert B.ctr_stream_copy(dst.data_ptr() + 4, src.data_ptr(), 4096, False, st) == B.CTR_E_INVAL
+    assert B.ctr_stream_copy(None, src.data_ptr(), 4096, False, st) == B.CTR_E_INVAL
+    torch.cuda.synchronize()
+
+
 def test_same_calls_give_bit_identical_results():
     w = WL.scaled(WL.WORKLOADS["large"], capacity_rows=1 << 15, zipf_universe=20000, batch=64)
     outs = []
