@@ -28,8 +28,9 @@ COPY_KIB = float(1 << 20)
 
 
 def _one(pattern):
-    g = sorted(glob.glob(pattern, recursive=True))
-    return g[0] if g else None
+    """the newest match: a directory that was profiled into twice holds both runs' files"""
+    g = sorted(glob.glob(pattern, recursive=True), key=os.path.getmtime)
+    return g[-1] if g else None
 
 
 def _short(name):
