@@ -275,6 +275,14 @@ def main():
     ap.add_argument("--grad-bf16", action="store_true",
                     help="the pooled gradients reach the push as bfloat16 (ctr_push_adam_bf16): not the "
                          "configuration the metric is quoted on, which has fp32 gradients")
+    ap.add_argument("--push-order", default="default",
+                    help="order in which the push runs its work spans (ctr_debug_set_push_order): default (the "
+                         "library's: win32 for gradient arrays of 256 MiB and more), list, winN (spans inside one "
+                         "row first, grouped by N windows of the gradient array), splitN (those in a launch of "
+                         "their own), mixN (the other spans dealt between the windows)")
+    ap.add_argument("--ab-push-order", default="",
+                    help="comma-separated orders (as for --push-order) compared AFTER the timed region in this same "
+                         "process: 8 rounds, one step per order and round, medians reported as push_order_ab")
     ap.add_argument("--seam", action="store_true",
                     help="time the working-set seam instead of training steps: ctr_table_load of every row of the "
                          "workload's table, ctr_table_collect of the same keys, ctr_table_clear (one cycle per step)")
@@ -316,6 +324,18 @@ def main():
                      beta2=w.beta2, eps=w.eps, init_seed=1, init_std=w.init_std, kstep=kstep,
                      load_factor=w.load_factor, device=dev, adagrad=args.variant == "adagrad",
                      prose=args.variant == "prose", bias_correction=args.variant == "kingma")
+
+    def set_push_order(name):
+        if name == "default":
+            return
+        kinds = {"list": None, "win": 0, "split": 1, "mix": 2}
+        kind = next((k for k in kinds if name.startswith(k)), None)
+        if kind is None:
+            raise SystemExit("bench.py: unknown push order %r" % name)
+        windows = 0 if kind == "list" else int(name[len(kind):])
+        if table.set_push_order(windows, kinds[kind] or 0, 0) != CTR_OK:
+            raise SystemExit("bench.py: push order %r refused" % name)
+    set_push_order(args.push_order)
 
     # every input of every step resident in HBM before timing; for the k-step workload a "step"
     # is one local step of every replica (plus the merge on every k-th)
@@ -429,6 +449,29 @@ def main():
         raise RuntimeError("device status %d after the timed steps" % status)
     rows_after = table.n_rows
     elapsed = t1 - t0
+
+    push_order_ab = None
+    if args.ab_push_order and not args.predict and not kstep:     # same process, same table, same batches: only the order differs
+        names = [n for n in args.ab_push_order.split(",") if n]
+        acc = {n: {"push": [], "step": []} for n in names}
+        s_ab = Wm
+        for _ in range(8):
+            for n in names:
+                set_push_order(n)
+                table.profile_read()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                run_step(Wm + (s_ab - Wm) % K)
+                e1.record()
+                torch.cuda.synchronize()
+                st_ab = table.profile_read()
+                acc[n]["push"].append(st_ab["push"][0] / max(st_ab["push"][1], 1))
+                acc[n]["step"].append(e0.elapsed_time(e1))
+                s_ab += 1
+        push_order_ab = {n: {"push_ms_median": median(sorted(v["push"])), "step_ms_median": median(sorted(v["step"]))}
+                         for n, v in acc.items()}
+        if table.last_status() != CTR_OK:
+            raise RuntimeError("device status after the order comparison")
     keys_total = sum(batches[i]["keys"].numel() for i in range(Wm * reps, total_steps * reps))
     L_mean = keys_total / (K * reps)
 
@@ -468,6 +511,8 @@ def main():
         "warmup": Wm,
         "ms_per_step": ms_step,
         "ms_per_step_median": median(step_ms),
+        "push_order": args.push_order,
+        "push_order_ab": push_order_ab,
         "ms_per_step_median_last_80pct": median(steady),
         "higher_is_better": True,
         "scaling": "weak",

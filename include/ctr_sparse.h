@@ -305,6 +305,16 @@ int ctr_last_status(ctr_table* t, void* hip_stream);
  * than the call was given makes the call return CTR_E_NOMEM.  Errors: CTR_E_INVAL. */
 int ctr_debug_set_geometry(ctr_table* t, uint32_t span, uint32_t probe_items);
 
+/* Measurement and test hook: the order in which later pushes run their work spans (Algorithm 1's push
+ * step; results do not depend on it).  windows = 0: list order.  windows = 2..128 (a power of two): the
+ * spans that lie inside one row - gradient gathers in ascending segment order - run first, grouped by which
+ * of `windows` equal parts of the gradient array they begin in, so that the spans in flight together gather
+ * from one part and the second use of a gradient row finds it in the last-level cache; the others follow in
+ * list order.  split_launch = 1: those spans get a launch of their own; 2: one launch, the other spans dealt
+ * evenly between the parts.  Pushes whose gradient array is smaller than min_grad_bytes keep the list order.
+ * A new table starts with 32 windows, one launch, 256 MiB.  Errors: CTR_E_INVAL. */
+int ctr_debug_set_push_order(ctr_table* t, uint32_t windows, uint32_t split_launch, uint64_t min_grad_bytes);
+
 /* When enabled, a pair of HIP events is recorded around each stage of the
  * following calls, on the stream they run on (one pair per execution). */
 int ctr_profile_enable(ctr_table* t, int on);

@@ -29,7 +29,7 @@ EXPORTED = (
     "ctr_table_bytes", "ctr_workspace_bytes", "ctr_table_create", "ctr_table_destroy",
     "ctr_pull_pool", "ctr_pull_pool_bf16", "ctr_lookup_pool", "ctr_lookup_pool_noalloc", "ctr_push_adam", "ctr_push_adam_bf16", "ctr_kstep_merge", "ctr_table_load", "ctr_table_collect", "ctr_table_clear",
     "ctr_table_size", "ctr_table_export",
-    "ctr_batch_export", "ctr_batch_stats", "ctr_merge_stats", "ctr_stream_copy", "ctr_last_status", "ctr_debug_set_geometry", "ctr_profile_enable",
+    "ctr_batch_export", "ctr_batch_stats", "ctr_merge_stats", "ctr_stream_copy", "ctr_last_status", "ctr_debug_set_geometry", "ctr_debug_set_push_order", "ctr_profile_enable",
     "ctr_profile_read",
 )
 
@@ -77,6 +77,8 @@ def lib():
     L.ctr_pull_pool.argtypes = [vp, u32, vp, u64, vp, u32, vp, vp, sz, C.POINTER(vp), vp]
     L.ctr_debug_set_geometry.restype = ci
     L.ctr_debug_set_geometry.argtypes = [vp, u32, u32]
+    L.ctr_debug_set_push_order.restype = ci
+    L.ctr_debug_set_push_order.argtypes = [vp, u32, u32, u64]
     L.ctr_lookup_pool.restype = ci
     L.ctr_lookup_pool.argtypes = [vp, u32, vp, u64, vp, u32, vp, vp, vp, sz, vp]
     L.ctr_lookup_pool_noalloc.restype = ci
@@ -389,6 +391,10 @@ class CtrTable:
         st = lib().ctr_debug_set_geometry(self._handle, span, probe_items)
         self._ws_slack = 1 << 20 if (span or probe_items) else 0
         return st
+
+    def set_push_order(self, windows=0, split_launch=0, min_grad_bytes=256 << 20):
+        """Measurement and test hook (ctr_debug_set_push_order)."""
+        return lib().ctr_debug_set_push_order(self._handle, windows, split_launch, min_grad_bytes)
 
     def profile_enable(self, on=True):
         return lib().ctr_profile_enable(self._handle, 1 if on else 0)

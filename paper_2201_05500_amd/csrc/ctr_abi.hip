@@ -81,6 +81,19 @@ struct WorkLayout {
       off_head, off_tail, off_block_head, off_span_flags, off_span_rows, total;
 };
 
+// How a list of n elements is cut into the chunks the sort's launches work on.
+SortGeom sort_geom(u64 n) {
+  const u64 tiles = (n + SORT_TILE - 1) / SORT_TILE;
+  const u64 chunks = std::min<u64>(std::max<u64>(tiles, 1), SORT_MAX_CHUNKS);
+  const u64 per = (n + chunks - 1) / chunks;
+  const u64 chunk_elems = std::max<u64>(((per + SORT_TILE - 1) / SORT_TILE) * SORT_TILE, SORT_TILE);
+  SortGeom g;
+  g.n = (u32)n;
+  g.chunk_elems = (u32)chunk_elems;
+  g.n_chunks = (u32)std::max<u64>((n + chunk_elems - 1) / chunk_elems, 1);
+  return g;
+}
+
 // force_span / force_items: 0 = chosen by batch size; otherwise the geometry a test asks for.
 void work_layout(u32 D, u64 n_keys, WorkLayout* L, u32 force_span = 0, u32 force_items = 0) {
   const u64 n = n_keys;
@@ -91,13 +104,7 @@ void work_layout(u32 D, u64 n_keys, WorkLayout* L, u32 force_span = 0, u32 force
   if (force_span) L->span = force_span;
   L->n_spans = (u32)((n + L->span - 1) / L->span);
   L->n_span_blocks = (L->n_spans + SPANS_PER_BLOCK - 1) / SPANS_PER_BLOCK;
-  u64 tiles = (n + SORT_TILE - 1) / SORT_TILE;
-  u64 chunks = std::min<u64>(std::max<u64>(tiles, 1), SORT_MAX_CHUNKS);
-  u64 per = (n + chunks - 1) / chunks;
-  u64 chunk_elems = std::max<u64>(((per + SORT_TILE - 1) / SORT_TILE) * SORT_TILE, SORT_TILE);
-  L->geo.n = (u32)n;
-  L->geo.chunk_elems = (u32)chunk_elems;
-  L->geo.n_chunks = (u32)std::max<u64>((n + chunk_elems - 1) / chunk_elems, 1);
+  L->geo = sort_geom(n);
   size_t o = 0;
   const size_t arr = align256(n * sizeof(u32));
   L->off_occ_row = o; o += arr;
@@ -193,6 +200,8 @@ struct ctr_table {
   ctr_batch cur;
   bool has_live;
   u32 force_span, force_items;  // test hook: 0 = geometry by batch size
+  u32 push_windows, push_split;  // execution order of the push's spans (ctr_debug_set_push_order)
+  u64 push_order_min_grad_bytes;
   bool profile;
   // stage timers: one (start, stop) event pair per recorded execution since the last read
   std::vector<hipEvent_t> ev_start[CTR_N_STAGES], ev_stop[CTR_N_STAGES];
@@ -364,6 +373,9 @@ int ctr_table_create(const ctr_config* cfg, void* d_mem, size_t bytes, void* hip
   t->generation = 0;
   t->has_live = false;
   t->force_span = t->force_items = 0;
+  t->push_windows = CTR_PUSH_WINDOWS;
+  t->push_split = CTR_PUSH_SPLIT;
+  t->push_order_min_grad_bytes = CTR_PUSH_ORDER_MIN_GRAD_BYTES;
   t->profile = false;
   for (int i = 0; i < CTR_N_STAGES; ++i) t->ev_used[i] = 0;
   hipStream_t st = (hipStream_t)hip_stream;
@@ -610,13 +622,49 @@ static int push_adam_impl(ctr_table* t, uint32_t replica, ctr_batch* handle, con
     u32* span_rows = (u32*)(batch->ws + wl.off_span_rows);
 #define CTR_SPAN_LAUNCH(KERNEL)                                                                                   \
   LPR_DISPATCH(t->lpr, KERNEL, grid, st, t->hdr, batch->sorted_rows, batch->sorted_segs, n, wl.span, d_grad_pooled, \
-               vals, t->vhat, t->row_state, t->D, t->rf, P, head, tail, span_flags, span_rows)
+               vals, t->vhat, t->row_state, t->D, t->rf, P, head, tail, span_flags, span_rows, order, cold_count)
 #define CTR_FIXUP_LAUNCH(KERNEL)                                                                                 \
   LPR_DISPATCH(t->lpr, KERNEL, fgrid, st, t->hdr, batch->sorted_rows, n, wl.n_spans, wl.span, vals, t->vhat,       \
                t->row_state, t->D, t->rf, P, head, tail, block_head, span_flags)
     {
       StageTimer tm(t, CTR_STAGE_PUSH, st);
       const u32 grid = blocks_for((u64)wl.n_spans * t->lpr);
+      const u32 *order = nullptr, *cold_count = nullptr;
+      // Execution order of the spans: one pass of the radix sort over (window key, span index).  Its four
+      // short arrays live in the sort's key buffer that does not hold the sorted list.
+      if (t->push_windows) {
+        u32* ka = (u32*)(batch->ws + wl.off_ka);
+        u32* kb = (u32*)(batch->ws + wl.off_kb);
+        u32* spare = (batch->sorted_rows == ka) ? kb : ka;
+        const u32 ns4 = (wl.n_spans + 3u) & ~3u;  // the sort reads 16 bytes at a time
+        const u64 grad_bytes = (u64)batch->n_seg * t->D * (grad_bf16 ? 2u : 4u);
+        if (grad_bytes >= t->push_order_min_grad_bytes && batch->n_seg > 0 && 16ull * ns4 <= 4ull * n) {
+          u32 *key_in = spare, *val_in = spare + ns4, *key_out = spare + 2 * ns4, *val_out = spare + 3 * ns4;
+          u32 seg_shift = 0;
+          while (((batch->n_seg - 1) >> seg_shift) >= t->push_windows) ++seg_shift;
+          const SortGeom g2 = sort_geom(wl.n_spans);
+          u32* hist = (u32*)(batch->ws + wl.off_hist);
+          u32* digit_total = (u32*)(batch->ws + wl.off_digit_total);
+          hipLaunchKernelGGL(k_span_keys, dim3(blocks_for(wl.n_spans)), dim3(BLOCK), 0, st, t->hdr, batch->sorted_rows,
+                             batch->sorted_segs, n, wl.span, wl.n_spans, seg_shift, t->push_windows,
+                             t->push_split == 2u ? 1u : 0u, key_in, val_in);
+          hipLaunchKernelGGL(k_sort_hist, dim3(g2.n_chunks), dim3(BLOCK), 0, st, t->hdr, key_in, g2, 0u, 255u, hist);
+          hipLaunchKernelGGL(k_sort_scan, dim3(RADIX), dim3(BLOCK), 0, st, t->hdr, hist, g2.n_chunks, digit_total);
+          hipLaunchKernelGGL(k_sort_scatter, dim3(g2.n_chunks), dim3(BLOCK), 0, st, t->hdr, key_in, val_in, key_out,
+                             val_out, g2, 0u, 255u, hist, digit_total);
+          order = val_out;
+          if (t->push_split == 1u) {
+            cold_count = digit_total + t->push_windows;  // spans with the key one past the last window
+            if (grad_bf16) {
+              LPR_DISPATCH(t->lpr, k_push_hot_g16, grid, st, t->hdr, batch->sorted_rows, batch->sorted_segs, n, wl.span,
+                           d_grad_pooled, t->D, head, tail, span_flags, span_rows, order, cold_count);
+            } else {
+              LPR_DISPATCH(t->lpr, k_push_hot, grid, st, t->hdr, batch->sorted_rows, batch->sorted_segs, n, wl.span,
+                           d_grad_pooled, t->D, head, tail, span_flags, span_rows, order, cold_count);
+            }
+          }
+        }
+      }
       if (grad_bf16) {
         switch (kind) {
           case STEP_ADAM_SHARED: CTR_SPAN_LAUNCH(k_push_span_shared_g16); break;
@@ -885,6 +933,15 @@ int ctr_debug_set_geometry(ctr_table* t, uint32_t span, uint32_t probe_items) {
   if (probe_items != 0 && probe_items != 1 && probe_items != (uint32_t)PROBE_MAX_ITEMS) return CTR_E_INVAL;
   t->force_span = span;
   t->force_items = probe_items;
+  return CTR_OK;
+}
+
+int ctr_debug_set_push_order(ctr_table* t, uint32_t windows, uint32_t split_launch, uint64_t min_grad_bytes) {
+  if (!t) return CTR_E_INVAL;
+  if (windows > 128 || (windows & (windows - 1)) != 0 || split_launch > 2) return CTR_E_INVAL;
+  t->push_windows = windows;
+  t->push_split = split_launch;
+  t->push_order_min_grad_bytes = min_grad_bytes;
   return CTR_OK;
 }
 

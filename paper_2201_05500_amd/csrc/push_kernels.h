@@ -44,6 +44,29 @@ constexpr u32 NO_ROW = 0xFFFFFFFFu;
 #ifndef CTR_PUSH_MIN_WAVES
 #define CTR_PUSH_MIN_WAVES 1  // waves per SIMD the span kernel is compiled for
 #endif
+// Execution order of the spans (initial values; ctr_debug_set_push_order changes them per table).
+// CTR_PUSH_WINDOWS > 0 (a power of two up to 128): the spans that lie inside one row - pure gradient gathers,
+// in ascending segment order - are run first, grouped by which of that many windows of the gradient array
+// they begin in, so that the spans in flight at one time gather from one window and the second use of a
+// gradient row finds it in the last-level cache; the other spans follow in list order.  Only the order of
+// execution changes: every span still writes its own partial sums.  0: list order.
+#ifndef CTR_PUSH_WINDOWS
+#define CTR_PUSH_WINDOWS 32
+#endif
+// 0: one launch, those spans first.  1: they get a launch of their own (k_push_hot: nothing but gathers and
+// one partial sum per span, CTR_PUSH_HOT_PB gradient rows in flight per lane group), the rest a second one.
+// 2: one launch, the other spans dealt evenly between the windows.  (Measured: 0 and 2 equal, 1 slower.)
+#ifndef CTR_PUSH_SPLIT
+#define CTR_PUSH_SPLIT 0
+#endif
+#ifndef CTR_PUSH_HOT_PB
+#define CTR_PUSH_HOT_PB 8
+#endif
+// a gradient array smaller than this many bytes stays in the last-level cache whatever the order: its
+// pushes keep the list order (and save the four short launches that compute the other one)
+#ifndef CTR_PUSH_ORDER_MIN_GRAD_BYTES
+#define CTR_PUSH_ORDER_MIN_GRAD_BYTES (256ull << 20)
+#endif
 
 // Which row update a launch performs (compile-time, so that each variant carries only its own
 // registers and loads).
@@ -186,6 +209,84 @@ __global__ void k_push_begin(DevHeader* hdr, double b1, double b2) {
   hdr->bc2 = 1.0 / (1.0 - pow(b2, (double)t));
 }
 
+// Sort key of a span for the windowed execution order: the window of the gradient array its first
+// occurrence gathers from if the whole span belongs to one row, one past the last window otherwise.
+__global__ void k_span_keys(const DevHeader* hdr, const u32* __restrict__ sr, const u32* __restrict__ ss, u32 n,
+                            u32 span, u32 n_spans, u32 seg_shift, u32 n_windows, u32 interleave,
+                            u32* __restrict__ key, u32* __restrict__ val) {
+  if (hdr->status) return;
+  const u32 s = blockIdx.x * BLOCK + threadIdx.x;
+  if (s >= n_spans) return;
+  const u32 b = s * span, e = min(b + span, n);
+  // one row only, and not the whole of it: the span leaves exactly one partial sum
+  const bool hot = sr[b] == sr[e - 1] && ((b > 0 && sr[b - 1] == sr[b]) || (e < n && sr[e] == sr[b]));
+  const u32 w = min(ss[b] >> seg_shift, n_windows - 1u);
+  if (interleave)  // the other spans are dealt evenly, by list position, between the windows
+    key[s] = hot ? 2u * w : 2u * (u32)(((u64)s * n_windows) / n_spans) + 1u;
+  else
+    key[s] = hot ? w : n_windows;
+  val[s] = s;
+}
+
+// The spans k_span_keys gave a window (the first n_spans - cold_count[0] of `order`): sum of the span's
+// gradient rows in list order, left as the head (the row began in an earlier span) or the tail partial.
+template <int LPR, bool GB>
+__device__ __forceinline__ void push_hot_body(const DevHeader* hdr, const u32* __restrict__ sr,
+                                              const u32* __restrict__ ss, u32 n, u32 span,
+                                              const void* __restrict__ grad_any, u32 D,
+                                              double* __restrict__ head_part, double* __restrict__ tail_part,
+                                              u32* __restrict__ span_flags, u32* __restrict__ span_rows,
+                                              const u32* __restrict__ order, const u32* __restrict__ cold_count) {
+  if (hdr->status) return;
+  constexpr int PB = CTR_PUSH_HOT_PB < LPR ? CTR_PUSH_HOT_PB : LPR;
+  const u32 n_spans = (n + span - 1) / span;
+  const u32 idx = (blockIdx.x * BLOCK + threadIdx.x) / LPR;
+  if (idx >= n_spans - min(cold_count[0], n_spans)) return;
+  const u32 s = order[idx];
+  if (s >= n_spans) return;
+  const u32 c = threadIdx.x % LPR;
+  const u32 b = s * span, e = min(b + span, n);
+  const bool col_ok = c * 4 < D;
+  d4 acc = {0.0, 0.0, 0.0, 0.0};
+  for (u32 i0 = b; i0 < e; i0 += LPR) {  // lane c holds the segment of list entry i0 + c
+    const u32 mine = (i0 + c < e) ? ss[i0 + c] : 0u;
+    const u32 cnt = min((u32)LPR, e - i0);
+#pragma unroll
+    for (u32 j0 = 0; j0 < (u32)LPR; j0 += PB) {
+      f4 gv[PB];
+#pragma unroll
+      for (int j = 0; j < PB; ++j) {
+        const u32 g = __shfl(mine, (int)(j0 + j), LPR);
+        gv[j].x = gv[j].y = gv[j].z = gv[j].w = 0.0f;
+        if (j0 + j < cnt && col_ok) {
+          if constexpr (GB) {
+            const uint2 raw = *reinterpret_cast<const uint2*>(static_cast<const bf16_t*>(grad_any) + (u64)g * D + 4 * c);
+            gv[j].x = __uint_as_float(raw.x << 16);
+            gv[j].y = __uint_as_float(raw.x & 0xFFFF0000u);
+            gv[j].z = __uint_as_float(raw.y << 16);
+            gv[j].w = __uint_as_float(raw.y & 0xFFFF0000u);
+          } else {
+            gv[j] = ldg4(static_cast<const float*>(grad_any) + (u64)g * D + 4 * c);
+          }
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < PB; ++j) {
+        acc.x += (double)gv[j].x;
+        acc.y += (double)gv[j].y;
+        acc.z += (double)gv[j].z;
+        acc.w += (double)gv[j].w;
+      }
+    }
+  }
+  const bool open = b > 0 && sr[b - 1] == sr[b];
+  if (col_ok) store_partial(open ? head_part : tail_part, s, D, c, acc);
+  if (c == 0) {
+    span_flags[s] = (sr[b] << 2) | (open ? SF_HEAD : SF_TAIL);
+    span_rows[s] = open ? 0u : 1u;
+  }
+}
+
 // Span walk.  Each batch of PB occurrences issues, before anything is consumed,
 // the PB gradient-row loads and the x/m/v loads of every row that ends inside
 // the batch, so that a group keeps several KB in flight instead of one
@@ -198,7 +299,8 @@ __device__ __forceinline__ void push_span_body(const DevHeader* hdr, const u32* 
                                                const float* __restrict__ vhat, u32* __restrict__ row_state, u32 D,
                                                u32 rf, const AdamParams& P_in, double* __restrict__ head_part,
                                                double* __restrict__ tail_part, u32* __restrict__ span_flags,
-                                               u32* __restrict__ span_rows) {
+                                               u32* __restrict__ span_rows, const u32* __restrict__ order,
+                                               const u32* __restrict__ cold_count) {
   if (hdr->status) return;
   AdamParams P = P_in;
   if constexpr (KIND == STEP_ADAM_KINGMA) {
@@ -206,7 +308,19 @@ __device__ __forceinline__ void push_span_body(const DevHeader* hdr, const u32* 
     P.bc2 = hdr->bc2;
   }
   constexpr int PB = CTR_PUSH_PB;
-  const u32 s = (blockIdx.x * BLOCK + threadIdx.x) / LPR;
+  u32 s = (blockIdx.x * BLOCK + threadIdx.x) / LPR;
+  if (order) {  // the spans are run in the order of this permutation of their indices ...
+    const u32 n_spans = (n + span - 1) / span;
+    u32 skip = 0;
+    if (cold_count) {  // ... of which only the last cold_count[0] are this launch's
+      const u32 n_cold = min(cold_count[0], n_spans);
+      if (s >= n_cold) return;
+      skip = n_spans - n_cold;
+    }
+    if (skip + s >= n_spans) return;
+    s = order[skip + s];
+    if (s >= n_spans) return;
+  }
   const u32 c = threadIdx.x % LPR;
   const u32 b = s * span;
   if (b >= n) return;
@@ -326,9 +440,11 @@ __device__ __forceinline__ void push_span_body(const DevHeader* hdr, const u32* 
   const DevHeader *hdr, const u32 *__restrict__ sr, const u32 *__restrict__ ss, u32 n, u32 span,               \
       const void *__restrict__ grad, float *__restrict__ values, const float *__restrict__ vhat,               \
       u32 *__restrict__ row_state, u32 D, u32 rf, AdamParams P, double *__restrict__ head_part,                \
-      double *__restrict__ tail_part, u32 *__restrict__ span_flags, u32 *__restrict__ span_rows
-#define CTR_PUSH_SPAN_PASS \
-  hdr, sr, ss, n, span, grad, values, vhat, row_state, D, rf, P, head_part, tail_part, span_flags, span_rows
+      double *__restrict__ tail_part, u32 *__restrict__ span_flags, u32 *__restrict__ span_rows,               \
+      const u32 *__restrict__ order, const u32 *__restrict__ cold_count
+#define CTR_PUSH_SPAN_PASS                                                                                      \
+  hdr, sr, ss, n, span, grad, values, vhat, row_state, D, rf, P, head_part, tail_part, span_flags, span_rows, \
+      order, cold_count
 
 // one kernel per step kind (the dispatch macro on the host takes kernels templated on LPR only)
 #define CTR_DEFINE_PUSH_SPAN(NAME, KIND)                                                          \
@@ -340,6 +456,22 @@ __device__ __forceinline__ void push_span_body(const DevHeader* hdr, const u32* 
   __global__ void __launch_bounds__(BLOCK, CTR_PUSH_MIN_WAVES) NAME##_g16(CTR_PUSH_SPAN_ARGS) {   \
     push_span_body<LPR, KIND, true>(CTR_PUSH_SPAN_PASS);                                          \
   }
+#define CTR_PUSH_HOT_ARGS                                                                                       \
+  const DevHeader *hdr, const u32 *__restrict__ sr, const u32 *__restrict__ ss, u32 n, u32 span,               \
+      const void *__restrict__ grad, u32 D, double *__restrict__ head_part, double *__restrict__ tail_part,    \
+      u32 *__restrict__ span_flags, u32 *__restrict__ span_rows, const u32 *__restrict__ order,                \
+      const u32 *__restrict__ cold_count
+template <int LPR>
+__global__ void __launch_bounds__(BLOCK) k_push_hot(CTR_PUSH_HOT_ARGS) {
+  push_hot_body<LPR, false>(hdr, sr, ss, n, span, grad, D, head_part, tail_part, span_flags, span_rows, order,
+                            cold_count);
+}
+template <int LPR>
+__global__ void __launch_bounds__(BLOCK) k_push_hot_g16(CTR_PUSH_HOT_ARGS) {
+  push_hot_body<LPR, true>(hdr, sr, ss, n, span, grad, D, head_part, tail_part, span_flags, span_rows, order,
+                           cold_count);
+}
+
 CTR_DEFINE_PUSH_SPAN(k_push_span, STEP_ADAM_OWN)
 CTR_DEFINE_PUSH_SPAN(k_push_span_shared, STEP_ADAM_SHARED)
 CTR_DEFINE_PUSH_SPAN(k_push_span_adagrad, STEP_ADAGRAD)

@@ -178,6 +178,42 @@ def test_all_keys_distinct_and_ragged_tail(geometry):
         compare_tables(gt, ot, what="distinct n=%d" % n)
 
 
+PUSH_ORDERS = [(2, 0), (32, 0), (128, 0), (8, 1), (64, 1), (4, 2), (128, 2)]   # (windows, 0 hot first / 1 own launch / 2 dealt)
+
+
+@pytest.mark.parametrize("order", PUSH_ORDERS)
+def test_push_span_order_does_not_change_results(order):
+    """The push may run its work spans in another order (rows of many occurrences first, grouped by the part of
+    the gradient array they gather from): same bits as the list order, and parity with the oracle."""
+    from paper_2201_05500_amd.binding import CtrTable
+    D, R = 16, 1 << 14
+    for n, span in ((50000, 16), (9000, 32), (200001, 128)):
+        rng = np.random.default_rng(n)
+        # a few very popular keys (spans inside one row), a Zipf-like middle, and singletons
+        keys = np.where(rng.random(n) < 0.55, rng.integers(1, 4, n), rng.zipf(1.3, n) + 10).astype(np.uint64)
+        keys[rng.random(n) < 0.1] += np.uint64(1 << 33)
+        keys = keys % np.uint64(1 << 40) + np.uint64(1)
+        if np.unique(keys).size > R:
+            keys = keys % np.uint64(R // 2) + np.uint64(1)
+        off = np.unique(np.concatenate([[0, n], rng.integers(0, n + 1, n // 4)])).astype(np.uint32)
+        bn = _manual_batch(keys, off, D, seed=n)
+        gt, ot = _tables(R, D)
+        ref = CtrTable(R, D, init_seed=3)
+        assert gt.set_geometry(span, 0) == 0 and ref.set_geometry(span, 0) == 0
+        assert gt.set_push_order(order[0], order[1], 0) == 0
+        assert ref.set_push_order(0, 0, 0) == 0
+        bt = to_device(bn)
+        for s in range(2):
+            run_step(gt, ot, bt, bn, what="push order %s n=%d" % (order, n))
+            st, h, _ = ref.pull_pool(0, bt["keys"], bt["offsets"])
+            assert st == 0 and ref.push_adam(0, h, bt["grad"]) == 0
+        compare_tables(gt, ot, what="push order %s n=%d" % (order, n))
+        a, b = gt.table_export(), ref.table_export()
+        for f in ("keys", "x", "m", "v"):
+            assert np.array_equal(a[f], b[f]), "push order %s n=%d: %s differs from the list order" % (order, n, f)
+    assert gt.set_push_order(3, 0, 0) != 0 and gt.set_push_order(256, 0, 0) != 0 and gt.set_push_order(4, 3, 0) != 0
+
+
 def test_empty_batch_and_empty_segments():
     D = 8
     gt, ot = _tables(64, D)
