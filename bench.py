@@ -465,7 +465,8 @@ def main():
                 e1.record()
                 torch.cuda.synchronize()
                 st_ab = table.profile_read()
-                acc[n]["push"].append(st_ab["push"][0] / max(st_ab["push"][1], 1))
+                acc[n]["push"].append(st_ab["push"][0] / max(st_ab["push"][1], 1) +      # the span walk ...
+                                      st_ab["order"][0] / max(st_ab["order"][1], 1))     # ... and what orders it
                 acc[n]["step"].append(e0.elapsed_time(e1))
                 s_ab += 1
         push_order_ab = {n: {"push_ms_median": median(sorted(v["push"])), "step_ms_median": median(sorted(v["step"]))}

@@ -296,7 +296,8 @@ int ctr_last_status(ctr_table* t, void* hip_stream);
 #define CTR_STAGE_PUSH 4    /* gradient segment-reduce fused with Adam */
 #define CTR_STAGE_FIXUP 5   /* rows whose occurrences span several work spans */
 #define CTR_STAGE_MERGE 6   /* k-step merge */
-#define CTR_N_STAGES 7
+#define CTR_STAGE_ORDER 7   /* execution order of the push's work spans (large gradient arrays only) */
+#define CTR_N_STAGES 8
 
 /* Test hook: fixes the work geometry of later pulls and pushes instead of letting the batch size
  * choose it (span: occurrences per work span of the push, 16/32/64/128; probe_items: occurrences

@@ -21,9 +21,9 @@ LIB_PATH = os.environ.get("CTR_SPARSE_LIB") or os.path.join(_HERE, "libctr_spars
 CTR_OK, CTR_E_INVAL, CTR_E_NOMEM, CTR_E_FULL, CTR_E_BADKEY, CTR_E_STATE, CTR_E_DEVICE = range(7)
 CTR_F_KSTEP, CTR_F_ADAGRAD, CTR_F_KSTEP_PROSE, CTR_F_BIAS_CORRECTION = 1, 2, 4, 8
 CTR_STEP_LOCAL, CTR_STEP_MERGE_PENDING = 0, 1
-CTR_N_STAGES = 7
+CTR_N_STAGES = 8
 CTR_NOALLOC_MAX_KEYS = 1 << 22
-STAGE_NAMES = ("probe", "insert", "pool", "sort", "push", "fixup", "merge")
+STAGE_NAMES = ("probe", "insert", "pool", "sort", "push", "fixup", "merge", "order")
 
 EXPORTED = (
     "ctr_table_bytes", "ctr_workspace_bytes", "ctr_table_create", "ctr_table_destroy",

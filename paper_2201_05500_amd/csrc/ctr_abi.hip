@@ -626,43 +626,48 @@ static int push_adam_impl(ctr_table* t, uint32_t replica, ctr_batch* handle, con
 #define CTR_FIXUP_LAUNCH(KERNEL)                                                                                 \
   LPR_DISPATCH(t->lpr, KERNEL, fgrid, st, t->hdr, batch->sorted_rows, n, wl.n_spans, wl.span, vals, t->vhat,       \
                t->row_state, t->D, t->rf, P, head, tail, block_head, span_flags)
+    const u32 grid = blocks_for((u64)wl.n_spans * t->lpr);
+    const u32 *order = nullptr, *cold_count = nullptr;
+    bool hot_launch = false;
+    // Execution order of the spans: one pass of the radix sort over (window key, span index).  Its four
+    // short arrays live in the sort's key buffer that does not hold the sorted list.
+    if (t->push_windows) {
+      u32* ka = (u32*)(batch->ws + wl.off_ka);
+      u32* kb = (u32*)(batch->ws + wl.off_kb);
+      u32* spare = (batch->sorted_rows == ka) ? kb : ka;
+      const u32 ns4 = (wl.n_spans + 3u) & ~3u;  // the sort reads 16 bytes at a time
+      const u64 grad_bytes = (u64)batch->n_seg * t->D * (grad_bf16 ? 2u : 4u);
+      if (grad_bytes >= t->push_order_min_grad_bytes && batch->n_seg > 0 && 16ull * ns4 <= 4ull * n) {
+        StageTimer tm(t, CTR_STAGE_ORDER, st);
+        u32 *key_in = spare, *val_in = spare + ns4, *key_out = spare + 2 * ns4, *val_out = spare + 3 * ns4;
+        u32 seg_shift = 0;
+        while (((batch->n_seg - 1) >> seg_shift) >= t->push_windows) ++seg_shift;
+        const SortGeom g2 = sort_geom(wl.n_spans);
+        u32* hist = (u32*)(batch->ws + wl.off_hist);
+        u32* digit_total = (u32*)(batch->ws + wl.off_digit_total);
+        hipLaunchKernelGGL(k_span_keys, dim3(blocks_for(wl.n_spans)), dim3(BLOCK), 0, st, t->hdr, batch->sorted_rows,
+                           batch->sorted_segs, n, wl.span, wl.n_spans, seg_shift, t->push_windows,
+                           t->push_split == 2u ? 1u : 0u, key_in, val_in);
+        hipLaunchKernelGGL(k_sort_hist, dim3(g2.n_chunks), dim3(BLOCK), 0, st, t->hdr, key_in, g2, 0u, 255u, hist);
+        hipLaunchKernelGGL(k_sort_scan, dim3(RADIX), dim3(BLOCK), 0, st, t->hdr, hist, g2.n_chunks, digit_total);
+        hipLaunchKernelGGL(k_sort_scatter, dim3(g2.n_chunks), dim3(BLOCK), 0, st, t->hdr, key_in, val_in, key_out,
+                           val_out, g2, 0u, 255u, hist, digit_total);
+        order = val_out;
+        if (t->push_split == 1u) {
+          cold_count = digit_total + t->push_windows;  // spans with the key one past the last window
+          hot_launch = true;
+        }
+      }
+    }
     {
       StageTimer tm(t, CTR_STAGE_PUSH, st);
-      const u32 grid = blocks_for((u64)wl.n_spans * t->lpr);
-      const u32 *order = nullptr, *cold_count = nullptr;
-      // Execution order of the spans: one pass of the radix sort over (window key, span index).  Its four
-      // short arrays live in the sort's key buffer that does not hold the sorted list.
-      if (t->push_windows) {
-        u32* ka = (u32*)(batch->ws + wl.off_ka);
-        u32* kb = (u32*)(batch->ws + wl.off_kb);
-        u32* spare = (batch->sorted_rows == ka) ? kb : ka;
-        const u32 ns4 = (wl.n_spans + 3u) & ~3u;  // the sort reads 16 bytes at a time
-        const u64 grad_bytes = (u64)batch->n_seg * t->D * (grad_bf16 ? 2u : 4u);
-        if (grad_bytes >= t->push_order_min_grad_bytes && batch->n_seg > 0 && 16ull * ns4 <= 4ull * n) {
-          u32 *key_in = spare, *val_in = spare + ns4, *key_out = spare + 2 * ns4, *val_out = spare + 3 * ns4;
-          u32 seg_shift = 0;
-          while (((batch->n_seg - 1) >> seg_shift) >= t->push_windows) ++seg_shift;
-          const SortGeom g2 = sort_geom(wl.n_spans);
-          u32* hist = (u32*)(batch->ws + wl.off_hist);
-          u32* digit_total = (u32*)(batch->ws + wl.off_digit_total);
-          hipLaunchKernelGGL(k_span_keys, dim3(blocks_for(wl.n_spans)), dim3(BLOCK), 0, st, t->hdr, batch->sorted_rows,
-                             batch->sorted_segs, n, wl.span, wl.n_spans, seg_shift, t->push_windows,
-                             t->push_split == 2u ? 1u : 0u, key_in, val_in);
-          hipLaunchKernelGGL(k_sort_hist, dim3(g2.n_chunks), dim3(BLOCK), 0, st, t->hdr, key_in, g2, 0u, 255u, hist);
-          hipLaunchKernelGGL(k_sort_scan, dim3(RADIX), dim3(BLOCK), 0, st, t->hdr, hist, g2.n_chunks, digit_total);
-          hipLaunchKernelGGL(k_sort_scatter, dim3(g2.n_chunks), dim3(BLOCK), 0, st, t->hdr, key_in, val_in, key_out,
-                             val_out, g2, 0u, 255u, hist, digit_total);
-          order = val_out;
-          if (t->push_split == 1u) {
-            cold_count = digit_total + t->push_windows;  // spans with the key one past the last window
-            if (grad_bf16) {
-              LPR_DISPATCH(t->lpr, k_push_hot_g16, grid, st, t->hdr, batch->sorted_rows, batch->sorted_segs, n, wl.span,
-                           d_grad_pooled, t->D, head, tail, span_flags, span_rows, order, cold_count);
-            } else {
-              LPR_DISPATCH(t->lpr, k_push_hot, grid, st, t->hdr, batch->sorted_rows, batch->sorted_segs, n, wl.span,
-                           d_grad_pooled, t->D, head, tail, span_flags, span_rows, order, cold_count);
-            }
-          }
+      if (hot_launch) {
+        if (grad_bf16) {
+          LPR_DISPATCH(t->lpr, k_push_hot_g16, grid, st, t->hdr, batch->sorted_rows, batch->sorted_segs, n, wl.span,
+                       d_grad_pooled, t->D, head, tail, span_flags, span_rows, order, cold_count);
+        } else {
+          LPR_DISPATCH(t->lpr, k_push_hot, grid, st, t->hdr, batch->sorted_rows, batch->sorted_segs, n, wl.span,
+                       d_grad_pooled, t->D, head, tail, span_flags, span_rows, order, cold_count);
         }
       }
       if (grad_bf16) {
