@@ -72,6 +72,7 @@ def main():
     ap.add_argument("write_dir")
     ap.add_argument("--note", default="")
     ap.add_argument("--command", default="", help="the bench.py command line that was profiled")
+    ap.add_argument("--out-dir", default=os.path.join(ROOT, "profiles"), help="where the two files are written")
     ap.add_argument("--steps", type=int, default=0,
                     help="steps the profiled command ran (warm-up + timed); default: the launches of the push kernel")
     a = ap.parse_args()
@@ -139,7 +140,7 @@ def main():
                 "source_hash": source_hash(), "command": a.command,
                 "note": "KiB per launch as counted by rocprofv3 (last dispatch of the run); bytes = KiB * 1024 * scale"})
     lines.append("measured on commit %s, kernel source hash %s" % (commit, rec["source_hash"]))
-    out_dir = os.path.join(ROOT, "profiles")
+    out_dir = a.out_dir
     with open(os.path.join(out_dir, "%s_kernels.txt" % a.name), "w") as f:
         f.write("\n".join(lines) + "\n")
     with open(os.path.join(out_dir, "%s_traffic.json" % a.name), "w") as f:

@@ -115,6 +115,8 @@ def test_null_and_misaligned_arguments():
     assert L.ctr_kstep_merge(None, None) == B.CTR_E_INVAL
     assert L.ctr_push_adam(None, 0, None, None, 0, None) == B.CTR_E_INVAL
     assert L.ctr_last_status(None, None) == B.CTR_E_INVAL
+    assert L.ctr_debug_set_geometry(None, 0, 0) == B.CTR_E_INVAL
+    assert L.ctr_debug_set_push_order(None, 32, 0, 0) == B.CTR_E_INVAL
 
 
 def test_headers_are_plain_c99(tmp_path):
