@@ -132,8 +132,8 @@ def cpu_baseline_full(w, WL, seconds_hint=20.0):
         threads = os.cpu_count() or 1
     n_steps, keys_done, t_spent = 0, 0, 0.0
     while t_spent < seconds_hint / 2 and n_steps < 4:
-        bn = WL.as_numpy(WL.make_batch(ws, n_steps, with_grad=False))
-        labels = WL.make_labels(ws, n_steps).numpy()
+        bn = WL.as_numpy(WL.make_batch(ws, n_steps % w.steps, with_grad=False))
+        labels = WL.make_labels(ws, n_steps % w.steps).numpy()
         t0 = time.perf_counter()
         st, pooled = ot.pull_pool(0, bn["keys"], bn["offsets"])
         assert st == 0
@@ -165,7 +165,7 @@ def cpu_baseline(w, WL, seconds_hint=20.0):
     for step in range(n_warm + 3):
         if step >= n_warm and t_spent >= seconds_hint / 2:
             break
-        bn = WL.as_numpy(WL.make_batch(ws, step))
+        bn = WL.as_numpy(WL.make_batch(ws, step % w.steps))   # the configuration's own distinct batches, then repeated
         t0 = time.perf_counter()
         st, _ = ot.pull_pool(0, bn["keys"], bn["offsets"])
         assert st == 0

@@ -83,3 +83,13 @@ def test_profile_summary_scales_counters_by_the_copy_kernel(tmp_path):
     assert rec["source_hash"] and rec["workload"] == "unit_step"
     text = open(os.path.join(out, "unit_step_kernels.txt")).read()
     assert "k_push_span<16>" in text and "fetch x2.000, write x1.000" in text and "python3 bench.py" in text
+
+
+def test_cpu_baseline_runs_the_oracle_on_the_configurations_own_batches():
+    """The tiny configuration has one distinct batch, repeated: the baseline must repeat it too (five different
+    batches would overflow its 2^16-row table)."""
+    import bench
+    from paper_2201_05500_amd import workloads as WL
+    cb = bench.cpu_baseline(WL.WORKLOADS["tiny"], WL)
+    assert cb["kind"] == "oracle" and cb["unit"] == "keys/s" and cb["cores"] == 1 and cb["value"] > 0
+    assert "timed step(s)" in cb["sample"]
