@@ -44,3 +44,26 @@ def test_bench_kstep_line_reports_the_merge():
     d = _run("--workload", "kstep", "--steps", "4", "--warmup", "4", "--no-cpu-baseline")
     assert d["roofline"]["kernel"] == "k_merge" and d["roofline"]["algorithmic_bytes_per_launch"] > 0
     assert d["stage_launches_per_step"]["merge"] == 0.25
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("args", [
+    ["--workload", "tiny", "--variant", "adagrad"],
+    ["--workload", "tiny", "--variant", "kingma"],
+    ["--workload", "tiny", "--grad-bf16"],
+    ["--workload", "tiny", "--push-order", "split4", "--no-cpu-baseline"],
+    ["--workload", "tiny", "--seam"],
+    ["--workload", "kstep", "--variant", "prose", "--no-cpu-baseline"],
+])
+def test_bench_modes_print_one_line(args):
+    d = _run(*(args + ["--steps", "4", "--warmup", "4"]))
+    assert d["value"] > 0 and d["ms_per_step"] > 0 and d["n_gpus"] == 1
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("args", [["--workload", "tiny", "--variant", "prose"], ["--workload", "kstep", "--variant", "adagrad"],
+                                  ["--workload", "tiny", "--predict"]])
+def test_bench_refuses_combinations_it_does_not_time(args):
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py")] + args, capture_output=True, text=True, cwd=ROOT,
+                       timeout=600)
+    assert r.returncode == 2 and r.stdout.strip() == "" and "bench.py:" in r.stderr
