@@ -11,9 +11,11 @@ from tests.parity_util import to_device
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("variant", ["single", "kstep", "bias_corrected"])
+@pytest.mark.parametrize("variant", ["single", "kstep", "bias_corrected", "ordered_spans", "ordered_spans_own_launch"])
 def test_captured_pull_push_replays_like_eager_steps(variant):
     # bias_corrected: the step count and its correction factors live on the device, so every replay is a new step t
+    # ordered_spans*: the graphed table's push computes and follows an execution order of its spans (the launches
+    # a large gradient array adds), the eager one keeps the list order: same bits
     kstep = variant == "kstep"
     import torch
     from paper_2201_05500_amd.binding import CTR_OK, CTR_STEP_LOCAL, CTR_STEP_MERGE_PENDING, CtrTable
@@ -22,6 +24,9 @@ def test_captured_pull_push_replays_like_eager_steps(variant):
     other = to_device(WL.as_numpy(WL.make_batch(w, 1)))
     kw = dict(init_seed=7, n_replicas=2 if kstep else 1, kstep=kstep, bias_correction=variant == "bias_corrected")
     eager, graphed = CtrTable(w.capacity_rows, w.dim, **kw), CtrTable(w.capacity_rows, w.dim, **kw)
+    if variant.startswith("ordered_spans"):
+        assert graphed.set_push_order(8, 1 if variant.endswith("own_launch") else 0, 0) == CTR_OK
+        assert eager.set_push_order(0, 0, 0) == CTR_OK
     mode = CTR_STEP_MERGE_PENDING if kstep else CTR_STEP_LOCAL
     G = w.n_segments
     pooled_e = torch.empty((G, w.dim), dtype=torch.float32, device="cuda:0")
