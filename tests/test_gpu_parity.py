@@ -214,6 +214,24 @@ def test_push_span_order_does_not_change_results(order):
     assert gt.set_push_order(3, 0, 0) != 0 and gt.set_push_order(256, 0, 0) != 0 and gt.set_push_order(4, 3, 0) != 0
 
 
+@pytest.mark.parametrize("D", [4, 8, 32, 64, 100, 256])
+def test_push_span_order_every_lane_group_width(D):
+    """The ordered push (one-row spans in a launch of their own, and in the common launch) for every width of the lane
+    group that walks a span, including a dimension that does not fill its group."""
+    n, R = 30000, 1 << 12
+    rng = np.random.default_rng(D)
+    keys = np.where(rng.random(n) < 0.6, rng.integers(1, 3, n), rng.integers(10, 2000, n)).astype(np.uint64)
+    off = np.unique(np.concatenate([[0, n], rng.integers(0, n + 1, n // 5)])).astype(np.uint32)
+    bn = _manual_batch(keys, off, D, seed=D)
+    bt = to_device(bn)
+    for order in ((4, 1), (16, 0), (2, 2)):
+        gt, ot = _tables(R, D)
+        assert gt.set_geometry(16, 0) == 0 and gt.set_push_order(order[0], order[1], 0) == 0
+        for s in range(2):
+            run_step(gt, ot, bt, bn, what="D=%d order %s" % (D, order))
+        compare_tables(gt, ot, what="D=%d order %s" % (D, order))
+
+
 def test_empty_batch_and_empty_segments():
     D = 8
     gt, ot = _tables(64, D)
