@@ -262,8 +262,10 @@ def seam_bench(args, torch, WL, CtrTable, CTR_OK, dev):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=40,
+                    help="timed steps (default 40: with the 10 warm-up steps the 50 steps of the large configuration, "
+                         "each on its own batch; the 10 merge rounds of the k-step configuration)")
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="large")
     ap.add_argument("--variant", default="alg2", choices=["alg2", "adagrad", "prose", "kingma"],
                     help="row update: Algorithm 2's Adam (default), AdaGrad, the prose reading of the merge, "
